@@ -1,0 +1,145 @@
+/*
+ * fipa.h -- C ABI of the factorized Invariant Point Attention library for MI355X (gfx950).
+ *
+ * The library computes the attention core of FlashIPA (Algorithm 1, steps 2-9): frame
+ * application and lifting of queries / keys / values, one softmax(Q^ K^T) V^ over the
+ * concatenated scalar, point and pair-factor features, the split, the inverse frame on the
+ * point output (Eq. 4) and the z1 contraction of the pair output -- without ever forming the
+ * L x L x c_z pair tensor or the L x L attention matrix.  The result equals standard IPA
+ * (Eqs. 2-4) evaluated on z_ij = z1_i^T z2_j (Section 2.4).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, contiguous, row-major and
+ *     16-byte aligned.  `desc` is a HOST pointer.
+ *   - The library allocates nothing, frees nothing and never synchronises: all work is
+ *     enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - `workspace` is caller-owned device scratch of at least fipa_workspace_bytes(); its
+ *     contents are undefined afterwards.  Forward and backward do not share state through it.
+ *   - Outputs are fully overwritten.  Query rows whose mask byte is 0 receive zeros (and
+ *     contribute nothing to any gradient); keys whose mask byte is 0 receive exactly zero
+ *     weight, whatever finite values their slots hold.
+ *   - Return value: FIPA_OK or a negative FIPA_ERR_* code.  Argument errors are detected on
+ *     the host before anything is enqueued.
+ *   - Calls on different streams with different workspaces may run concurrently.
+ */
+#ifndef FIPA_H
+#define FIPA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FIPA_OK 0
+#define FIPA_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, bad dtype               */
+#define FIPA_ERR_UNSUPPORTED (-2) /* shape outside what the kernels are built for (see below) */
+#define FIPA_ERR_WORKSPACE (-3)   /* workspace_bytes smaller than fipa_workspace_bytes()      */
+#define FIPA_ERR_ALIGNMENT (-4)   /* a tensor pointer is not 16-byte aligned                  */
+#define FIPA_ERR_LAUNCH (-5)      /* HIP reported an error when a kernel was enqueued         */
+
+#define FIPA_DTYPE_F32 0  /* q,k,v,points,z1,z2 float32; direct fp32 evaluation (no MFMA)      */
+#define FIPA_DTYPE_BF16 1 /* q,k,v,points,z1,z2 bfloat16; bf16 MFMA with fp32 accumulation      */
+
+/*
+ * Problem description (symbols of Section 2.2 / Algorithm 1):
+ *   B batch, L residues (padded length), H heads, c scalar q/k/v width, Pq = N_query,
+ *   Pv = N_value, cz = d_z pair channels, r = factor rank.
+ *   w_L, w_C: the constants of Eq. 3 (AlphaFold2 uses sqrt(1/3) and sqrt(2/(9*Pq))).
+ *   qk_scale: the 1/sqrt(c) of Eq. 3.
+ * Shapes supported:  FIPA_DTYPE_F32: c + 3*Pv + r*cz <= 576 and r*cz <= 512.
+ *                    FIPA_DTYPE_BF16: c + 12*Pq <= 64, c + 6*Pv <= 64, c % 8 == 0,
+ *                    r*cz in {32, 64, 128, 256, 512}.
+ */
+typedef struct fipa_desc {
+    int32_t B, L, H, c, Pq, Pv, cz, r;
+    int32_t dtype; /* FIPA_DTYPE_* : type of q,k,v,q_pts,k_pts,v_pts,z1,z2 and of their gradients */
+    float w_L, w_C;
+    float qk_scale;
+    uint32_t flags; /* reserved, must be 0 */
+} fipa_desc;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int fipa_version(void);
+
+/* Static, human-readable text for a return code. */
+const char *fipa_status_string(int status);
+
+/*
+ * Scratch sizes in bytes for fipa_forward / fipa_backward with this description.  Both are
+ * affine in L (the linear-memory property of Section 2.3).  Either output pointer may be
+ * NULL.  Host-only, touches no device.
+ */
+int fipa_workspace_bytes(const fipa_desc *desc, size_t *forward_bytes, size_t *backward_bytes);
+
+/*
+ * Forward (Algorithm 1, steps 2-9, with Eq. 4's inverse frame).
+ *   q, k, v          [B, L, H, c]        scalar queries / keys / values (desc->dtype)
+ *   q_pts, k_pts     [B, L, H, Pq, 3]    query / key points, local frame (desc->dtype)
+ *   v_pts            [B, L, H, Pv, 3]    value points, local frame (desc->dtype)
+ *   rot, trans       [B, L, 3, 3], [B, L, 3]  frames T_i = (R_i, t_i), always float32:
+ *                                        global = R_i * local + t_i
+ *   z1, z2           [B, L, r, cz]       pair factors, z_ij[d] = sum_rho z1_i[rho,d] z2_j[rho,d]
+ *   w_b              [H, cz] float32     weights of the pair-bias Linear of Eq. 2 (its additive
+ *                                        constant cancels in the softmax and is not an input)
+ *   gamma            [H] float32         per-head point weight gamma^h of Eq. 3, used as given
+ *   mask             [B, L] bytes, 1 = valid residue; NULL = all valid
+ *   o                [B, L, H, c]      float32   sum_j a_ij v_j
+ *   o_pts            [B, L, H, Pv, 3]  float32   T_i^{-1} o sum_j a_ij (T_j o v_j), local frame of i
+ *   o_pair           [B, L, H, cz]     float32   sum_j a_ij z_ij
+ *   lse              [B, H, L] float32, or NULL: natural log-sum-exp over valid keys of the
+ *                    softmax argument of Eq. 3 (0 for masked query rows); fipa_backward needs it.
+ */
+int fipa_forward(const fipa_desc *desc,
+                 const void *q, const void *k, const void *v,
+                 const void *q_pts, const void *k_pts, const void *v_pts,
+                 const float *rot, const float *trans,
+                 const void *z1, const void *z2,
+                 const float *w_b, const float *gamma, const uint8_t *mask,
+                 float *o, float *o_pts, float *o_pair, float *lse,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three
+ * point sets, z1, z2 (same shapes and dtype as the inputs) and gamma ([H], float32), given
+ * the upstream gradients d_o, d_o_pts, d_o_pair (float32, shapes of o, o_pts, o_pair) and
+ * the forward results o, o_pts, o_pair, lse.  Frames and w_b are treated as constants.
+ * d_gamma is overwritten (not accumulated).  The paper gives no backward; it is the chain
+ * rule through Eqs. 3-4 and z_ij = z1_i^T z2_j.
+ * Supported for FIPA_DTYPE_BF16 with r*cz <= 256; otherwise FIPA_ERR_UNSUPPORTED.
+ */
+int fipa_backward(const fipa_desc *desc,
+                  const void *q, const void *k, const void *v,
+                  const void *q_pts, const void *k_pts, const void *v_pts,
+                  const float *rot, const float *trans,
+                  const void *z1, const void *z2,
+                  const float *w_b, const float *gamma, const uint8_t *mask,
+                  const float *o, const float *o_pts, const float *o_pair, const float *lse,
+                  const float *d_o, const float *d_o_pts, const float *d_o_pair,
+                  void *d_q, void *d_k, void *d_v,
+                  void *d_q_pts, void *d_k_pts, void *d_v_pts,
+                  void *d_z1, void *d_z2, float *d_gamma,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Optional stage timing for benchmarks.  Between fipa_profile_begin() and fipa_profile_end()
+ * every fipa_forward / fipa_backward call on any stream additionally records HIP events around
+ * its stages on that stream (up to `capacity` calls; later calls run untimed).  This is the only
+ * process-wide state in the library and is not thread safe; do not use it with concurrent calls.
+ *   stage 0: preparation + packing (frame application, lifting)     Algorithm 1 steps 2-6
+ *   stage 1: fused attention                                        Algorithm 1 step 7
+ *   stage 2: epilogue (split, inverse frame, z1 contraction)        Algorithm 1 steps 8-9
+ * fipa_profile_end waits for the recorded events (it synchronises with them, nothing else),
+ * writes the mean duration of each stage in milliseconds to stage_ms[FIPA_PROFILE_STAGES] and
+ * the number of timed calls to *n_calls, and releases the events.  begin allocates the events
+ * (host-side driver objects, no device memory).
+ */
+#define FIPA_PROFILE_STAGES 3
+int fipa_profile_begin(int capacity);
+int fipa_profile_end(float *stage_ms, int *n_calls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FIPA_H */

@@ -1,0 +1,172 @@
+"""Thin ctypes binding of libfipa.so (include/fipa.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; torch is used for device memory
+and the current stream.  Loading fails loudly when the library has not been built -- there
+is no fallback.
+"""
+import ctypes
+import math
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfipa.so")
+
+FIPA_OK = 0
+FIPA_ERR_INVALID_ARG = -1
+FIPA_ERR_UNSUPPORTED = -2
+FIPA_ERR_WORKSPACE = -3
+FIPA_ERR_ALIGNMENT = -4
+FIPA_ERR_LAUNCH = -5
+FIPA_DTYPE_F32 = 0
+FIPA_DTYPE_BF16 = 1
+
+EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
+           "fipa_backward", "fipa_profile_begin", "fipa_profile_end")
+PROFILE_STAGES = 3
+
+
+class FipaDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "L", "H", "c", "Pq", "Pv", "cz", "r", "dtype")] + \
+               [("w_L", ctypes.c_float), ("w_C", ctypes.c_float), ("qk_scale", ctypes.c_float),
+                ("flags", ctypes.c_uint32)]
+
+
+class FipaError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %d (%s)" % (where, code, status_string(code)))
+
+
+_LIB = None
+
+
+def lib():
+    """Load libfipa.so once; raise if it is missing (build it with paper_2505_11580_amd/build.py)."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libfipa.so not built: run `python -m paper_2505_11580_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.fipa_version.restype = ctypes.c_int
+        L.fipa_status_string.restype = ctypes.c_char_p
+        L.fipa_status_string.argtypes = [ctypes.c_int]
+        L.fipa_workspace_bytes.restype = ctypes.c_int
+        L.fipa_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.fipa_forward.restype = ctypes.c_int
+        L.fipa_forward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 17 + [vp, sz, vp]
+        L.fipa_backward.restype = ctypes.c_int
+        L.fipa_backward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 29 + [vp, sz, vp]
+        L.fipa_profile_begin.restype = ctypes.c_int
+        L.fipa_profile_begin.argtypes = [ctypes.c_int]
+        L.fipa_profile_end.restype = ctypes.c_int
+        L.fipa_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+        _LIB = L
+    return _LIB
+
+
+def status_string(code):
+    return lib().fipa_status_string(int(code)).decode()
+
+
+def make_desc(B, L, H, c, Pq, Pv, cz, r, dtype, w_L=None, w_C=None, qk_scale=None):
+    """Description struct; defaults are the AlphaFold2 constants w_L = sqrt(1/3),
+    w_C = sqrt(2/(9 Pq)) and qk_scale = 1/sqrt(c)."""
+    return FipaDesc(B, L, H, c, Pq, Pv, cz, r, dtype,
+                    math.sqrt(1.0 / 3.0) if w_L is None else w_L,
+                    math.sqrt(2.0 / (9.0 * Pq)) if w_C is None else w_C,
+                    1.0 / math.sqrt(c) if qk_scale is None else qk_scale, 0)
+
+
+def workspace_bytes(desc):
+    fwd, bwd = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    rc = lib().fipa_workspace_bytes(ctypes.byref(desc), ctypes.byref(fwd), ctypes.byref(bwd))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_workspace_bytes")
+    return fwd.value, bwd.value
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def fipa_forward(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,
+                 o, o_pts, o_pair, lse, workspace):
+    """Enqueue fipa_forward on torch's current stream.  All tensors are device tensors laid
+    out as include/fipa.h states; `workspace` is a uint8 device tensor.  Returns nothing;
+    raises FipaError on a non-zero status."""
+    args = [q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask, o, o_pts, o_pair, lse]
+    rc = lib().fipa_forward(ctypes.byref(desc), *[_ptr(t) for t in args], _ptr(workspace),
+                            ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_forward")
+
+
+def fipa_backward(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,
+                  o, o_pts, o_pair, lse, d_o, d_o_pts, d_o_pair,
+                  d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2, d_gamma, workspace):
+    args = [q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,
+            o, o_pts, o_pair, lse, d_o, d_o_pts, d_o_pair,
+            d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2, d_gamma]
+    rc = lib().fipa_backward(ctypes.byref(desc), *[_ptr(t) for t in args], _ptr(workspace),
+                             ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_backward")
+
+
+def fipa_profile_begin(capacity):
+    rc = lib().fipa_profile_begin(int(capacity))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_profile_begin")
+
+
+def fipa_profile_end():
+    """Returns ([mean ms of stage 0, 1, 2], number of timed calls)."""
+    ms = (ctypes.c_float * PROFILE_STAGES)()
+    n = ctypes.c_int(0)
+    rc = lib().fipa_profile_end(ms, ctypes.byref(n))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_profile_end")
+    return [float(x) for x in ms], n.value
+
+
+# ---- conveniences for tests and the benchmark (allocation + upload; no arithmetic) ----------
+
+def upload(inp, device="cuda:0"):
+    """numpy workload dict (workloads.make_inputs) -> device tensors + desc."""
+    import torch
+    d = inp["dims"]
+    bf16 = inp["dtype"] == "bf16"
+    desc = make_desc(d["B"], d["L"], d["H"], d["c"], d["Pq"], d["Pv"], d["cz"], d["r"],
+                     FIPA_DTYPE_BF16 if bf16 else FIPA_DTYPE_F32, inp["w_L"], inp["w_C"])
+    dev = {}
+    for n in ("q", "k", "v", "q_pts", "k_pts", "v_pts", "z1", "z2"):
+        t = torch.from_numpy(inp[n]).to(device)
+        dev[n] = t.to(torch.bfloat16).contiguous() if bf16 else t.contiguous()
+    for n in ("rot", "trans", "w_b", "gamma", "d_o", "d_o_pts", "d_o_pair"):
+        if n in inp:
+            dev[n] = torch.from_numpy(inp[n]).to(device).contiguous()
+    dev["mask"] = None if inp.get("mask") is None else torch.from_numpy(inp["mask"]).to(device).contiguous()
+    return desc, dev
+
+
+def alloc_outputs(desc, device="cuda:0"):
+    import torch
+    B, L, H = desc.B, desc.L, desc.H
+    f = dict(dtype=torch.float32, device=device)
+    fwd, _ = workspace_bytes(desc)
+    return dict(o=torch.empty(B, L, H, desc.c, **f), o_pts=torch.empty(B, L, H, desc.Pv, 3, **f),
+                o_pair=torch.empty(B, L, H, desc.cz, **f), lse=torch.empty(B, H, L, **f),
+                workspace=torch.empty(max(fwd, 16), dtype=torch.uint8, device=device))
+
+
+def forward(desc, dev, out):
+    fipa_forward(desc, dev["q"], dev["k"], dev["v"], dev["q_pts"], dev["k_pts"], dev["v_pts"],
+                 dev["rot"], dev["trans"], dev["z1"], dev["z2"], dev["w_b"], dev["gamma"], dev["mask"],
+                 out["o"], out["o_pts"], out["o_pair"], out["lse"], out["workspace"])

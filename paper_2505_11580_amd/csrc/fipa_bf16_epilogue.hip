@@ -1,0 +1,67 @@
+// Split of the lifted output, inverse frame on the point part (Eq. 4) and contraction of the
+// pair part with z1 (Algorithm 1 steps 8-9).  Memory bound: one wave per (batch, head, row).
+#include "fipa_bf16_common.h"
+
+namespace fipa {
+
+namespace {
+
+__global__ __launch_bounds__(256) void fipa_epilogue_bf16_kernel(EpiParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t row_id = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // over B*L*H, h fastest
+    if (row_id >= (size_t)p.B * p.L * p.H) return;
+    const int h = (int)(row_id % p.H);
+    const size_t bi = row_id / p.H;
+    const int i = (int)(bi % p.L);
+    const int b = (int)(bi / p.L);
+    const int c = p.c, nv = 3 * p.Pv, DV = kDH + p.DZ;
+    const size_t bh = (size_t)b * p.H + h;
+    const float *oh = p.Ohat + (bh * p.Lp + i) * DV;
+    const bool valid = p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true;
+
+    for (int d = lane; d < c; d += 64) p.o[row_id * c + d] = valid ? oh[d] : 0.f;
+
+    const float *R = p.rot + ((size_t)b * p.L + i) * 9;
+    const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+    for (int idx = lane; idx < nv; idx += 64) {
+        const int pp = idx / 3, x = idx - 3 * pp;
+        float val = 0.f;
+        if (valid) {
+            for (int y = 0; y < 3; ++y) {
+                const int cc = 3 * pp + y;
+                const float G = oh[v_pt_col(c, p.Pv, cc, 0)] + oh[v_pt_col(c, p.Pv, cc, 1)];
+                val += R[3 * y + x] * (G - (t[y] - p.cen[4 * b + y]));
+            }
+        }
+        p.o_pts[row_id * nv + idx] = val;
+    }
+
+    const bf16_t *z1 = p.z1 + ((size_t)b * p.L + i) * p.DZ;
+    for (int d = lane; d < p.cz; d += 64) {
+        float val = 0.f;
+        if (valid)
+            for (int rho = 0; rho < p.r; ++rho)
+                val += bf2f(z1[rho * p.cz + d]) * oh[kDH + rho * p.cz + d];
+        p.o_pair[row_id * p.cz + d] = val;
+    }
+
+    // natural log-sum-exp of Eq. 3's argument: undo the log2 scaling and put back the
+    // per-query |Q|^2 term that was left out of the logits
+    if (p.lse && lane == 0) {
+        const float l2 = p.lse2[bh * p.Lp + i];
+        p.lse[bh * p.L + i] = (valid && l2 > -INFINITY) ? l2 * kLn2 - p.qbias[bh * p.Lp + i] : 0.f;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_epilogue_bf16(const EpiParams &p, hipStream_t stream)
+{
+    const size_t rows = (size_t)p.B * p.L * p.H;
+    hipLaunchKernelGGL(fipa_epilogue_bf16_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0,
+                       stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace fipa

@@ -1,0 +1,64 @@
+// Host side of the bf16 forward: workspace carving and the pack -> attention -> epilogue chain.
+#include "fipa_bf16_common.h"
+
+namespace fipa {
+
+size_t bf16_forward_workspace(const fipa_desc &d) { return bf16_layout(d).total; }
+
+hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream_t stream)
+{
+    const Bf16Layout w = bf16_layout(d);
+    char *base = static_cast<char *>(ws);
+    float *cen = reinterpret_cast<float *>(base + w.cen);
+    int *kvlen = reinterpret_cast<int *>(base + w.kvlen);
+
+    StageTimer timer(stream);
+    timer.begin(0);
+    hipError_t e = launch_prep(d, a.trans, a.mask, cen, kvlen, stream);
+    if (e != hipSuccess) return e;
+
+    PackParams pk;
+    pk.q = (const bf16_t *)a.q; pk.k = (const bf16_t *)a.k; pk.v = (const bf16_t *)a.v;
+    pk.q_pts = (const bf16_t *)a.q_pts; pk.k_pts = (const bf16_t *)a.k_pts;
+    pk.v_pts = (const bf16_t *)a.v_pts;
+    pk.z1 = (const bf16_t *)a.z1; pk.z2 = (const bf16_t *)a.z2;
+    pk.rot = a.rot; pk.trans = a.trans; pk.w_b = a.w_b; pk.gamma = a.gamma; pk.cen = cen;
+    pk.mask = a.mask;
+    pk.Qh = (bf16_t *)(base + w.Qh); pk.Qz = (bf16_t *)(base + w.Qz);
+    pk.Kh = (bf16_t *)(base + w.Kh); pk.Z2 = (bf16_t *)(base + w.Z2);
+    pk.VhT = (bf16_t *)(base + w.VhT); pk.Z2T = (bf16_t *)(base + w.Z2T);
+    pk.kbias = (float *)(base + w.kbias); pk.qbias = (float *)(base + w.qbias);
+    pk.B = d.B; pk.L = d.L; pk.Lp = w.Lp; pk.NT = w.NT; pk.H = d.H; pk.c = d.c; pk.Pq = d.Pq;
+    pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.DZ;
+    pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
+    e = launch_pack_bf16(pk, stream);
+    if (e != hipSuccess) return e;
+    timer.end(0);
+
+    AttnParams at;
+    at.Qh = pk.Qh; at.Qz = pk.Qz; at.Kh = pk.Kh; at.Z2 = pk.Z2; at.VhT = pk.VhT; at.Z2T = pk.Z2T;
+    at.kbias = pk.kbias; at.kvlen = kvlen;
+    at.Ohat = (float *)(base + w.Ohat); at.lse2 = (float *)(base + w.lse2);
+    at.B = d.B; at.L = d.L; at.Lp = w.Lp; at.H = d.H; at.NT = w.NT;
+    at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H;
+    timer.begin(1);
+    e = launch_attn_fwd_bf16(at, w.DZ, stream);
+    if (e != hipSuccess) return e;
+    timer.end(1);
+
+    EpiParams ep;
+    ep.Ohat = at.Ohat; ep.lse2 = at.lse2; ep.qbias = pk.qbias; ep.rot = a.rot; ep.trans = a.trans;
+    ep.cen = cen; ep.z1 = pk.z1; ep.mask = a.mask;
+    ep.o = a.o; ep.o_pts = a.o_pts; ep.o_pair = a.o_pair; ep.lse = a.lse;
+    ep.B = d.B; ep.L = d.L; ep.Lp = w.Lp; ep.H = d.H; ep.c = d.c; ep.Pv = d.Pv; ep.cz = d.cz;
+    ep.r = d.r; ep.DZ = w.DZ;
+    timer.begin(2);
+    e = launch_epilogue_bf16(ep, stream);
+    timer.end(2);
+    return e;
+}
+
+size_t bf16_backward_workspace(const fipa_desc &) { return 0; }
+hipError_t bf16_backward(const fipa_desc &, const BwdArgs &, void *, hipStream_t) { return hipErrorNotSupported; }
+
+}  // namespace fipa

@@ -1,0 +1,64 @@
+// Internal declarations shared by the HIP sources of libfipa (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fipa.h"
+
+namespace fipa {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// All tensor arguments of fipa_forward, as passed by the caller.
+struct FwdArgs {
+    const void *q, *k, *v, *q_pts, *k_pts, *v_pts;
+    const float *rot, *trans;
+    const void *z1, *z2;
+    const float *w_b, *gamma;
+    const uint8_t *mask;
+    float *o, *o_pts, *o_pair, *lse;
+};
+
+struct BwdArgs {
+    FwdArgs f;  // inputs and saved forward results (o, o_pts, o_pair, lse are read here)
+    const float *d_o, *d_o_pts, *d_o_pair;
+    void *d_q, *d_k, *d_v, *d_q_pts, *d_k_pts, *d_v_pts, *d_z1, *d_z2;
+    float *d_gamma;
+};
+
+// Stage timing (fipa_profile_begin / fipa_profile_end).  A StageTimer is created per API call;
+// when profiling is inactive every method is a no-op.
+class StageTimer {
+   public:
+    explicit StageTimer(hipStream_t stream);
+    void begin(int stage);  // record the start event of `stage`
+    void end(int stage);    // record its stop event
+
+   private:
+    hipStream_t stream_;
+    int slot_;
+};
+
+// Per-batch centroid of the valid translations (any common shift of all frames leaves the
+// result unchanged, Section 2; subtracting it keeps global coordinates small) and the number
+// of leading key slots that must be visited (1 + index of the last valid residue).
+//   cen   [B,4] floats (x, y, z, unused),  kvlen [B] ints
+hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, float *cen,
+                       int *kvlen, hipStream_t stream);
+
+// fp32 direct path (fipa_f32.hip)
+size_t f32_forward_workspace(const fipa_desc &d);
+hipError_t f32_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream_t stream);
+
+// bf16 MFMA path (fipa_bf16_*.hip)
+size_t bf16_forward_workspace(const fipa_desc &d);
+hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream_t stream);
+size_t bf16_backward_workspace(const fipa_desc &d);
+hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream);
+
+}  // namespace fipa

@@ -1,0 +1,60 @@
+// Per-batch preparation shared by both precisions: centroid of the valid translations and
+// the key-loop bound.  One workgroup per batch element.
+#include "fipa_internal.h"
+
+namespace fipa {
+
+__global__ __launch_bounds__(256) void fipa_prep_kernel(const float *__restrict__ trans,
+                                                        const uint8_t *__restrict__ mask, int L,
+                                                        float *__restrict__ cen,
+                                                        int *__restrict__ kvlen)
+{
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    float sx = 0.f, sy = 0.f, sz = 0.f;
+    int cnt = 0, last = 0;
+    for (int i = tid; i < L; i += 256) {
+        const bool ok = mask ? (mask[(size_t)b * L + i] != 0) : true;
+        if (ok) {
+            const float *t = trans + ((size_t)b * L + i) * 3;
+            sx += t[0];
+            sy += t[1];
+            sz += t[2];
+            cnt += 1;
+            last = i + 1;
+        }
+    }
+    __shared__ float red[4][256];
+    __shared__ int redl[256];
+    red[0][tid] = sx;
+    red[1][tid] = sy;
+    red[2][tid] = sz;
+    red[3][tid] = (float)cnt;
+    redl[tid] = last;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) {
+            for (int a = 0; a < 4; ++a) red[a][tid] += red[a][tid + s];
+            redl[tid] = max(redl[tid], redl[tid + s]);
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const float n = red[3][0] > 0.f ? red[3][0] : 1.f;
+        cen[4 * b + 0] = red[0][0] / n;
+        cen[4 * b + 1] = red[1][0] / n;
+        cen[4 * b + 2] = red[2][0] / n;
+        cen[4 * b + 3] = 0.f;
+        kvlen[b] = redl[0];
+    }
+}
+
+hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, float *cen,
+                       int *kvlen, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fipa_prep_kernel, dim3(d.B), dim3(256), 0, stream, trans, mask, d.L, cen,
+                       kvlen);
+    return hipGetLastError();
+}
+
+}  // namespace fipa

@@ -1,0 +1,44 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C ABI, run the oracle."""
+import numpy as np
+
+from oracle import ipa_oracle
+from paper_2505_11580_amd import binding
+
+NAMES = ("o", "o_pts", "o_pair")
+TOL = {"fp32": 1e-4, "bf16": 2e-2}  # max|gpu - oracle| / max|oracle| per output tensor
+
+
+def run_gpu(inp):
+    import torch
+    desc, dev = binding.upload(inp)
+    out = binding.alloc_outputs(desc)
+    for n in NAMES:
+        out[n].fill_(float("nan"))  # every element must be overwritten
+    binding.forward(desc, dev, out)
+    torch.cuda.synchronize()
+    res = {n: out[n].cpu().numpy().astype(np.float64) for n in NAMES}
+    res["lse"] = out["lse"].cpu().numpy().astype(np.float64)
+    return res
+
+
+def rel_err(got, want):
+    scale = max(float(np.abs(want).max()), 1e-30)
+    return float(np.abs(got - want).max()) / scale
+
+
+def check(inp, rows=None, tol=None, label=""):
+    """Compare the HIP path with the oracle (all rows, or the given row lists)."""
+    tol = TOL[inp["dtype"]] if tol is None else tol
+    got = run_gpu(inp)
+    want = ipa_oracle.forward(inp, rows=rows)
+    errs = {}
+    for n in NAMES:
+        g = got[n]
+        assert np.all(np.isfinite(g)), (label, n, "non-finite output")
+        if rows is not None:
+            g = np.stack([g[b][rows[b]] for b in range(g.shape[0])])
+        errs[n] = rel_err(g, want[n])
+    print(label, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    for n in NAMES:
+        assert errs[n] <= tol, (label, n, errs[n], tol)
+    return errs

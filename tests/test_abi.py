@@ -1,0 +1,68 @@
+"""The C-ABI library loads and exports what include/fipa.h declares; host-side argument
+checks answer with error codes before anything touches a device (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_11580_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fipa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fipa_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = binding.lib()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert binding.lib().fipa_version() >= 100
+    for code in (0, -1, -2, -3, -4, -5):
+        assert binding.status_string(code) != "unknown status"
+    assert binding.status_string(-99) == "unknown status"
+
+
+def test_workspace_is_affine_in_length():
+    # linear memory in L (Section 2.3): equal steps in L give equal steps in bytes
+    for dtype, r in ((binding.FIPA_DTYPE_BF16, 2), (binding.FIPA_DTYPE_F32, 2)):
+        sizes = [binding.workspace_bytes(binding.make_desc(1, L, 12, 16, 4, 8, 128, r, dtype))[0]
+                 for L in (1024, 2048, 3072, 4096, 8192)]
+        steps = [sizes[1] - sizes[0], sizes[2] - sizes[1], sizes[3] - sizes[2], (sizes[4] - sizes[3]) // 4]
+        assert len(set(steps)) == 1 and steps[0] > 0, sizes
+
+
+def test_bad_descriptions_are_rejected_on_the_host():
+    lib = binding.lib()
+    sz = ctypes.c_size_t(0)
+    bad = binding.make_desc(1, 0, 4, 16, 4, 8, 16, 2, binding.FIPA_DTYPE_F32)
+    assert lib.fipa_workspace_bytes(ctypes.byref(bad), ctypes.byref(sz), None) == binding.FIPA_ERR_INVALID_ARG
+    bad = binding.make_desc(1, 64, 4, 16, 4, 8, 16, 2, 7)
+    assert lib.fipa_workspace_bytes(ctypes.byref(bad), ctypes.byref(sz), None) == binding.FIPA_ERR_INVALID_ARG
+    odd = binding.make_desc(1, 64, 4, 16, 4, 8, 24, 2, binding.FIPA_DTYPE_BF16)  # r*cz = 48
+    assert lib.fipa_workspace_bytes(ctypes.byref(odd), ctypes.byref(sz), None) == binding.FIPA_ERR_UNSUPPORTED
+    assert lib.fipa_workspace_bytes(None, ctypes.byref(sz), None) == binding.FIPA_ERR_INVALID_ARG
+
+
+def test_forward_argument_checks_need_no_device():
+    lib = binding.lib()
+    d = binding.make_desc(1, 64, 4, 16, 4, 8, 16, 2, binding.FIPA_DTYPE_F32)
+    nulls = [None] * 17
+    assert lib.fipa_forward(ctypes.byref(d), *nulls, None, 0, None) == binding.FIPA_ERR_INVALID_ARG
+    fake = [ctypes.c_void_p(0x1000)] * 17
+    fake[12] = None  # mask may be NULL
+    assert lib.fipa_forward(ctypes.byref(d), *fake, ctypes.c_void_p(0x1000), 0, None) == binding.FIPA_ERR_WORKSPACE
+    mis = list(fake)
+    mis[0] = ctypes.c_void_p(0x1004)
+    assert lib.fipa_forward(ctypes.byref(d), *mis, ctypes.c_void_p(0x1000), 1 << 30, None) == binding.FIPA_ERR_ALIGNMENT
+    with pytest.raises(binding.FipaError):
+        binding.workspace_bytes(binding.make_desc(1, -5, 4, 16, 4, 8, 16, 2, 0))

@@ -1,0 +1,104 @@
+"""GPU parity of fipa_forward (through the C ABI) against the CPU oracle, element by element
+on the same seeded inputs.  Tolerances: 1e-4 (fp32 mode), 2e-2 (bf16 inputs, fp32 accumulate),
+as max|gpu - oracle| / max|oracle| per output tensor."""
+import numpy as np
+import pytest
+
+from paper_2505_11580_amd import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def test_f32_workload0():
+    gu.check(wl.make_inputs(0), label="cfg0 fp32")
+
+
+def test_f32_spread_geometry_and_ragged_length():
+    # shrunken geometry spreads the attention over many keys; L = 77 leaves a ragged tail
+    gu.check(wl.make_inputs(0, L=77, trans_scale=0.1, B=2), label="cfg0 fp32 spread L=77")
+    gu.check(wl.make_inputs(0, L=150, chain=True, H=3, cz=24, r=3), label="fp32 chain L=150 r=3")
+
+
+def test_f32_mask_and_garbage():
+    inp = wl.make_inputs(0, L=96, B=3, varlen=True, min_len=5, trans_scale=0.2)
+    gu.check(inp, label="fp32 varlen")
+    got = gu.run_gpu(inp)
+    for b, ln in enumerate(inp["lengths"]):
+        for n in gu.NAMES:
+            assert np.all(got[n][b, int(ln):] == 0), (n, b)
+    # a non-prefix mask
+    inp = wl.make_inputs(0, L=64, B=1, trans_scale=0.2)
+    m = np.ones((1, 64), dtype=np.uint8)
+    m[0, [0, 5, 6, 33, 63]] = 0
+    inp["mask"] = m
+    gu.check(inp, label="fp32 scattered mask")
+
+
+def test_f32_large_pair_width():
+    gu.check(wl.make_inputs(0, L=80, H=2, cz=128, r=2, chain=True), label="fp32 DZ=256")
+
+
+@pytest.mark.parametrize("cz,r", [(16, 2), (32, 2), (64, 2), (128, 2)])
+def test_bf16_small(cz, r):
+    # several key tiles, two query tiles, ragged tail
+    inp = wl.make_inputs(1, B=2, L=200, H=3, cz=cz, r=r)
+    gu.check(inp, label="bf16 L=200 DZ=%d" % (cz * r))
+    gu.check(wl.make_inputs(1, B=1, L=131, H=2, cz=cz, r=r, trans_scale=0.1),
+             label="bf16 spread L=131 DZ=%d" % (cz * r))
+
+
+def test_bf16_iid_far_apart_geometry():
+    # translations N(0, 10 A) i.i.d.: nearly one-hot attention, large coordinates
+    gu.check(wl.make_inputs(1, B=1, L=256, H=4, chain=False), label="bf16 iid geometry")
+
+
+def test_bf16_mask_and_garbage():
+    inp = wl.make_inputs(1, B=3, L=300, H=2, varlen=True, min_len=10)
+    gu.check(inp, label="bf16 varlen")
+    got = gu.run_gpu(inp)
+    for b, ln in enumerate(inp["lengths"]):
+        for n in gu.NAMES:
+            assert np.all(got[n][b, int(ln):] == 0), (n, b)
+    inp = wl.make_inputs(1, B=1, L=192, H=2, trans_scale=0.2)
+    m = np.ones((1, 192), dtype=np.uint8)
+    m[0, 0:70] = 0           # a whole leading key tile masked
+    m[0, [100, 101, 191]] = 0
+    inp["mask"] = m
+    gu.check(inp, label="bf16 scattered mask")
+
+
+def test_bf16_workload1_full():
+    gu.check(wl.make_inputs(1), label="cfg1 bf16 full")
+
+
+def test_bf16_workload2_sampled_rows():
+    inp = wl.make_inputs(2)
+    gu.check(inp, rows=wl.select_rows(inp, 96), label="cfg2 bf16 sampled rows")
+
+
+def test_bf16_workload4_forward_sampled_rows():
+    inp = wl.make_inputs(4, with_grads=False)
+    gu.check(inp, rows=wl.select_rows(inp, 48), label="cfg4 fwd bf16 sampled rows")
+
+
+def test_se3_invariance_on_gpu():
+    # Section 3.1: outputs unchanged under a global rotation + translation of all frames
+    for cfg, kw, tol in ((0, dict(L=64), 1e-4), (1, dict(B=1, L=256, H=4), 2e-2)):
+        inp = wl.make_inputs(cfg, **kw)
+        rng = np.random.default_rng(5)
+        Rg = wl.random_rotations(rng, ()).astype(np.float32)
+        tg = (30.0 * rng.standard_normal(3)).astype(np.float32)
+        moved = dict(inp)
+        moved["rot"] = np.einsum("xy,blyz->blxz", Rg, inp["rot"]).astype(np.float32)
+        moved["trans"] = (np.einsum("xy,bly->blx", Rg, inp["trans"]) + tg).astype(np.float32)
+        a, b = gu.run_gpu(inp), gu.run_gpu(moved)
+        for n in gu.NAMES:
+            assert gu.rel_err(b[n], a[n]) <= tol, (cfg, n, gu.rel_err(b[n], a[n]))
+
+
+def test_runs_are_bit_identical():
+    inp = wl.make_inputs(1, B=1, L=320, H=4)
+    a, b = gu.run_gpu(inp), gu.run_gpu(inp)
+    for n in gu.NAMES + ("lse",):
+        assert np.array_equal(a[n], b[n]), n
