@@ -1,0 +1,132 @@
+#!/usr/bin/env python3
+"""Benchmark of the factorized-IPA forward hot path on one MI355X.
+
+One "step" = one fipa_forward call (pack -> fused attention -> epilogue) over one batch of
+the long-chain workload (B=2, L=2048, H=12, c=16, N_query=4, N_value=8, c_z=128, r=2; bf16
+inputs, fp32 accumulation), with all inputs resident in HBM before the timed region.
+Prints ONE JSON line: whole-path algorithmic TFLOP/s (`value`), residues/s, the roofline
+of the dominant kernel (fused attention, bf16 MFMA) from HIP events recorded around that
+kernel inside the timed region, and the CPU oracle timed on a bounded sample of the same
+workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def cpu_baseline(inp, flops_per_pair, budget_s=12.0):
+    """Time the oracle (as it stands) on a bounded sample of query rows of the same workload."""
+    import numpy as np
+    from oracle import ipa_oracle
+    d = inp["dims"]
+    L, H, B = d["L"], d["H"], d["B"]
+    rng = np.random.default_rng(1)
+
+    def run(n):
+        rows = [np.sort(rng.choice(L, size=n, replace=False)).astype(np.int32) for _ in range(B)]
+        t0 = time.perf_counter()
+        ipa_oracle.forward(inp, rows=rows)
+        return time.perf_counter() - t0
+
+    pilot_n = 16
+    pilot = run(pilot_n)
+    n = int(min(L, 1024, max(pilot_n, pilot_n * budget_s / max(pilot, 1e-3))))
+    secs = run(n)
+    rows_total = n * B
+    pairs = rows_total * L * H
+    return {
+        "value": pairs * flops_per_pair / secs / 1e12,
+        "unit": "TFLOP/s",
+        "residues_per_s": rows_total / secs,
+        "cores": ipa_oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "%d random query rows of each of the %d chains (all %d keys, all %d heads), "
+                  "fp64 C oracle with OpenMP, %.1f s" % (n, B, L, H, secs),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="workload index (2 = the L=2048 headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; --gpus %d is not supported (run with --gpus 1)"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_11580_amd import binding, workloads
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    inp = workloads.make_inputs(args.workload, with_grads=False)
+    dims = inp["dims"]
+    desc, dev = binding.upload(inp)
+    out = binding.alloc_outputs(desc)
+    pairs = workloads.valid_pairs(inp)
+    fpp = workloads.fwd_flops_per_pair(dims)
+    residues = int(inp["lengths"].sum())
+
+    for _ in range(args.warmup):
+        binding.forward(desc, dev, out)
+    torch.cuda.synchronize()
+
+    binding.fipa_profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        binding.forward(desc, dev, out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stage_ms, n_timed = binding.fipa_profile_end()
+
+    ms_per_step = elapsed / args.steps * 1e3
+    tflops = pairs * fpp / (ms_per_step * 1e-3) / 1e12
+    attn_ms = stage_ms[1]
+    attn_tflops = pairs * fpp / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
+
+    result = {
+        "metric": "factorized-IPA fwd TFLOP/s + residues/s at L=2048; % of bf16 MFMA peak",
+        "value": tflops,
+        "unit": "TFLOP/s",
+        "residues_per_s": residues / (ms_per_step * 1e-3),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "workload %d: B=%d L=%d H=%d c=%d Pq=%d Pv=%d cz=%d r=%d, bf16 in / fp32 "
+                               "accumulate, random-walk chain frames, forward only"
+                               % (args.workload, dims["B"], dims["L"], dims["H"], dims["c"], dims["Pq"],
+                                  dims["Pv"], dims["cz"], dims["r"]),
+                   "valid_pairs": pairs, "flops_per_pair": fpp},
+        "stage_ms": {"pack": stage_ms[0], "attention": stage_ms[1], "epilogue": stage_ms[2],
+                     "timed_calls": n_timed},
+        "roofline": {"kernel": "fipa_attn_fwd_bf16_kernel", "bound": "mfma", "achieved": attn_tflops,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(inp, fpp)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
