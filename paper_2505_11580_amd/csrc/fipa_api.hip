@@ -24,7 +24,9 @@ int check_desc(const fipa_desc *d, bool backward)
         if (backward) return FIPA_ERR_UNSUPPORTED;
         if (DZ > 512 || d->c + 3LL * d->Pv + DZ > 576) return FIPA_ERR_UNSUPPORTED;
     } else {
-        if (d->c % 8 != 0 || d->c + 12 * d->Pq > 64 || d->c + 6 * d->Pv > 64)
+        const int PH = (d->Pv + 1) / 2;  // value points per lane half; see v_pt_col()
+        if (d->c % 8 != 0 || d->cz % 8 != 0 || d->c + 12 * d->Pq > 64 ||
+            d->c + 8 * ((6 * PH + 3) / 4) > 64)
             return FIPA_ERR_UNSUPPORTED;
         if (DZ != 32 && DZ != 64 && DZ != 128 && DZ != 256 && DZ != 512) return FIPA_ERR_UNSUPPORTED;
         if (DZ == 512) return FIPA_ERR_UNSUPPORTED;  // not built yet

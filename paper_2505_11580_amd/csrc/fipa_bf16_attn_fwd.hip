@@ -1,15 +1,30 @@
 // Fused attention on the lifted features (Algorithm 1 step 7) for gfx950: online softmax over
-// key tiles (the recurrences of Algorithm 2: running maximum m, running sum l, rescaled
-// accumulator), bf16 MFMA 32x32x16 for both contractions, fp32 accumulation.
+// key blocks (the recurrences of Algorithm 2: running maximum m, running sum l, rescaled
+// accumulator), bf16 MFMA 32x32x16 for both contractions, fp32 accumulation, and -- for the
+// AlphaFold2-style head shape -- the split / inverse frame / z1 contraction of steps 8-9 on the
+// accumulator registers, so the lifted output never goes to memory.
 //
 // Work split: one workgroup = one (batch, head, 128-query tile); each of its 4 waves owns 32
 // query rows and keeps q^ (as MFMA B fragments) and the 32 x (64+DZ) output accumulator in
-// registers for the whole key loop; K^ and V^ tiles of 64 keys are staged in LDS and shared by
-// the four waves.  Both products are computed transposed,
-//     S^T = K^ Q^T        (A = K^ tile from LDS, B = q^ registers)
-//     O^T += V^T P^T      (A = transposed V^ tile from LDS, B = P^T registers)
+// registers for the whole key loop.  Key blocks of 32 residues are brought into a ring of LDS
+// stages by direct global->LDS loads, two iterations ahead of their first use, and are shared
+// by the four waves.  Both products are computed transposed,
+//     S^T = K^ Q^T        (A = k^ rows from LDS, B = q^ registers)
+//     O^T += V^T P^T      (A = v^ columns, read from the row-major block with the transposing
+//                          LDS read, B = P^T registers)
 // so that a lane owns one query row: the softmax statistics are per-lane scalars and the
-// exponentiated S^T accumulator is already laid out as the B operand of the second product.
+// exponentiated S^T accumulator already has the layout of the B operand of the second
+// product.  The pair-factor block z2 is stored once and read in both roles.
+//
+// The loop is software pipelined over three blocks: iteration n accumulates P V of block n,
+// evaluates the exponentials of block n+1 (whose S^T was formed one iteration earlier) and
+// forms S^T of block n+2.  The 2*KS MFMAs of an iteration are issued in a fixed order with
+// their LDS operands fetched a few MFMAs ahead and the VALU work of the softmax cut into
+// slices placed between them, so that it runs in the shadow of the matrix pipe.
+//
+// The running maximum is only raised when a new logit exceeds it by more than kTau (in log2
+// units); until then the accumulator is not rescaled.  The result is the same softmax:
+// numerator and denominator carry the same factor 2^(m_true - m_ref) <= 2^kTau.
 #include "fipa_bf16_common.h"
 
 namespace fipa {
@@ -17,230 +32,646 @@ namespace fipa {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-template <int DZ>
-struct AttnCfg {
-    static constexpr int DQK = kDH + DZ;
-    static constexpr int DV = kDH + DZ;
-    static constexpr int KS = DQK / 16;         // k-steps of S^T
-    static constexpr int NB = DV / 32;          // 32-row blocks of O^T
-    static constexpr int KSTR = DQK * 2 + 16;   // bytes per key row of the K^ tile (padded)
-    static constexpr int VSTR = kTileK * 2 + 16;  // bytes per feature row of the V^T tile (padded)
-    static constexpr int K_BYTES = kTileK * KSTR;
-    static constexpr int V_BYTES = DV * VSTR;
-    static constexpr int LDS_BYTES = K_BYTES + V_BYTES + kTileK * 4;
-    static constexpr int K_CHUNKS = kTileK * DQK / 8 / 256;  // 16-byte chunks per thread
-    static constexpr int V_CHUNKS = DV * kTileK / 8 / 256;
-};
+constexpr float kTau = 8.0f;
+constexpr int kBlk = 32;           // keys per LDS stage
+constexpr int kHS = kDH * 2 + 16;  // LDS row stride (bytes) of the head-specific k^ / v^ blocks
 
 template <int DZ>
+struct AttnCfg {
+    static constexpr int DV = kDH + DZ;
+    static constexpr int KSZ = DZ / 16;      // k-steps of S^T over the pair part
+    static constexpr int KSH = kDH / 16;     // k-steps over the head-specific part
+    static constexpr int KS = KSZ + KSH;
+    static constexpr int NB = DV / 32;       // 32-row blocks of O^T
+    static constexpr int NBH = kDH / 32;     // of which head specific
+    static constexpr int ZS = DZ * 2 + 48;   // LDS row stride of the z2 block: this pad keeps both
+                                             // the row reads and the transposing reads conflict free
+    static constexpr int Z_SPR = ZS / 16;    // 16-byte slots per row
+    static constexpr int H_SPR = kHS / 16;
+    static constexpr int NZ = (kBlk * Z_SPR + 63) / 64;  // wave-wide 1 KiB loads for the z2 block
+    static constexpr int NH = (kBlk * H_SPR + 63) / 64;  // for one head block
+    static constexpr int NI = NZ + 2 * NH;   // flat list of wave-wide loads: z2 | k^ head | v^ head
+    static constexpr int NIW = (NI + 3) / 4; // per wave
+    static constexpr int Z_OFF = 0;
+    static constexpr int KH_OFF = NZ * 1024;
+    static constexpr int VH_OFF = (NZ + NH) * 1024;
+    static constexpr int KB_OFF = NI * 1024;             // 32 per-key fp32 biases
+    static constexpr int STAGE = KB_OFF + 256;
+    static constexpr int NSTAGE = 5 * STAGE <= 160 * 1024 ? 5 : 4;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    static constexpr int NOPS = 2 * KS;      // MFMAs per pipelined iteration (KS == 2*NB)
+    static_assert(KS == 2 * NB, "S^T and P V use the same number of MFMAs per block");
+    static constexpr int RING = NOPS % 5 == 0 ? 5 : (NOPS % 6 == 0 ? 6 : 8);  // operand buffers; divides NOPS
+    static constexpr int LA = RING - 1;      // MFMAs between the fetch of an LDS operand and its use
+    static_assert(KS > LA && NOPS % RING == 0, "pipeline depth");
+    static constexpr int VM_PER_BLOCK = NIW + 1;          // vector-memory ops one wave issues per block
+};
+
+__device__ __forceinline__ bf16x4 lds_read_tr(const char *ptr)
+{
+    return __builtin_bit_cast(
+        bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ptr)));
+}
+
+// 16 bytes per lane, global -> LDS without passing through registers: lane l fetches
+// base + voff and writes lds_wave_base + 16*l.  Written as inline assembly so that the
+// compiler neither counts these loads nor orders LDS reads after them; completion is
+// awaited explicitly with wait_vmem<N>() before the barrier that publishes the stage.
+__device__ __forceinline__ void dma16(const char *base, int voff, const char *lds_wave_base)
+{
+    const unsigned lds_addr =
+        (unsigned)(uintptr_t)((__attribute__((address_space(3))) const char *)lds_wave_base);
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2"
+        :
+        : "s"(lds_addr), "v"(voff), "s"(base)
+        : "memory", "m0");
+}
+
+// Workgroup barrier without the fence that __syncthreads() adds: the only cross-wave traffic
+// here are the direct loads, whose completion each wave awaits itself.
+__device__ __forceinline__ void wg_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmem()  // s_waitcnt vmcnt(N) only
+{
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+template <int DZ>
+struct Wave {
+    using C = AttnCfg<DZ>;
+    bf16x8 qf[C::KS];
+    f32x16 oacc[C::NB];
+    float m_ref, l_run;
+    int kaddr_h, kaddr_z, vaddr_h, vaddr_z, baddr;  // per-lane LDS offsets inside a stage
+};
+
+// S^T block (32 keys x 32 queries) of the stage at `st`, accumulator preset with the per-key bias.
+template <int DZ>
+__device__ __forceinline__ f32x16 s_block(const Wave<DZ> &w, const char *__restrict__ st)
+{
+    using C = AttnCfg<DZ>;
+    f32x16 sacc;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const f32x4 bias = *reinterpret_cast<const f32x4 *>(st + w.baddr + a * 32);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) sacc[4 * a + x] = bias[x];
+    }
+#pragma unroll
+    for (int ks = 0; ks < C::KSH; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(st + w.kaddr_h + ks * 32);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, w.qf[ks], sacc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < C::KSZ; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(st + w.kaddr_z + ks * 32);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, w.qf[C::KSH + ks], sacc, 0, 0, 0);
+    }
+    return sacc;
+}
+
+// One 32-row block of O^T += V^T P^T for the 32 keys of the stage at `st`.
+template <int DZ>
+__device__ __forceinline__ void pv_block(Wave<DZ> &w, const char *__restrict__ st, const bf16x8 (&pf)[2], int nb)
+{
+    using C = AttnCfg<DZ>;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        const char *src = nb < C::NBH ? st + w.vaddr_h + 16 * tt * kHS + nb * 64
+                                      : st + w.vaddr_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+        const int rs = nb < C::NBH ? kHS : C::ZS;
+        const bf16x4 lo = lds_read_tr(src);
+        const bf16x4 hi = lds_read_tr(src + 8 * rs);
+        bf16x8 a;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            a[x] = lo[x];
+            a[4 + x] = hi[x];
+        }
+        w.oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt], w.oacc[nb], 0, 0, 0);
+    }
+}
+
+// Exponentials of elements [r0, r1) of an S^T block against the reference maximum; the
+// denominator sums the bf16-rounded weights that the MFMA will use.
+__device__ __forceinline__ void exp_range(const f32x16 &sacc, float m_use, bf16x8 (&pf)[2], float &psum, int r0, int r1)
+{
+#pragma unroll
+    for (int r = r0; r < r1; ++r) {
+        const float ex = __builtin_amdgcn_exp2f(sacc[r] - m_use);
+        const __bf16 eb = (__bf16)ex;
+        pf[r >> 3][r & 7] = eb;
+        psum += (float)eb;
+    }
+}
+
+// Source side of the direct global->LDS loads of one wave.
+template <int DZ>
+struct Dma {
+    using C = AttnCfg<DZ>;
+    const char *src[C::NIW];  // wave-uniform: start of the tensor the entry reads (block 0)
+    int stride[C::NIW];       // wave-uniform: bytes from one key block to the next
+    int ldsoff[C::NIW];       // wave-uniform: byte offset of the entry's 1 KiB inside a stage
+    int doff[C::NIW];         // per lane: byte offset inside the global block
+    const char *kbb;
+    int kboff;
+    int lane;
+};
+
+// Enqueue the loads of key block n into the stage at `st` (C::VM_PER_BLOCK vector-memory ops).
+template <int DZ>
+__device__ __forceinline__ void issue_block(const Dma<DZ> &d, int n, char *st)
+{
+    using C = AttnCfg<DZ>;
+#pragma unroll
+    for (int k = 0; k < C::NIW; ++k)
+        dma16(d.src[k] + (size_t)n * d.stride[k], d.doff[k], st + d.ldsoff[k]);
+    if (d.lane < 8) dma16(d.kbb + (size_t)n * kBlk * 4, d.kboff, st + C::KB_OFF);  // 32 floats
+}
+
+// ---- the hand-ordered MFMA sequence of one pipelined iteration -------------------------------
+// Operations 0 .. NOPS-1: the first LA are P V MFMAs (their operands come from a stage
+// that has been visible for a whole iteration, so they can be fetched across the barrier), then
+// S^T and P V MFMAs alternate (the S^T MFMAs form one dependent chain; alternating hides its
+// latency), and the last LA are S^T MFMAs.
+template <int DZ>
+struct Ops {
+    using C = AttnCfg<DZ>;
+    static constexpr int F = C::LA;
+    __host__ __device__ static constexpr bool is_pv(int j)
+    {
+        return j < F ? true : (j >= C::NOPS - F ? false : ((j - F) & 1) == 1);
+    }
+    // index of the operation within its kind: P V -> 2*nb + tt, S^T -> ks
+    __host__ __device__ static constexpr int idx(int j)
+    {
+        return j < F ? j : (j >= C::NOPS - F ? C::KS - (C::NOPS - j) : (((j - F) & 1) ? F + (j - F) / 2 : (j - F) / 2));
+    }
+};
+
+// LDS operand of P V operation `i` (= 2*nb + tt) from the stage at `st`: 32 v^ columns x 16 keys.
+template <int DZ>
+__device__ __forceinline__ bf16x8 load_pv(const Wave<DZ> &w, const char *st, int i)
+{
+    using C = AttnCfg<DZ>;
+    const int nb = i >> 1, tt = i & 1;
+    const char *src = nb < C::NBH ? st + w.vaddr_h + 16 * tt * kHS + nb * 64
+                                  : st + w.vaddr_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+    const int rs = nb < C::NBH ? kHS : C::ZS;
+    const bf16x4 lo = lds_read_tr(src);
+    const bf16x4 hi = lds_read_tr(src + 8 * rs);
+    bf16x8 a;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        a[x] = lo[x];
+        a[4 + x] = hi[x];
+    }
+    return a;
+}
+
+// LDS operand of S^T operation `ks` from the stage at `st`: 32 keys x 16 k^ features.
+template <int DZ>
+__device__ __forceinline__ bf16x8 load_s(const Wave<DZ> &w, const char *st, int ks)
+{
+    using C = AttnCfg<DZ>;
+    const char *src = ks < C::KSH ? st + w.kaddr_h + ks * 32 : st + w.kaddr_z + (ks - C::KSH) * 32;
+    return *reinterpret_cast<const bf16x8 *>(src);
+}
+
+// Per-key bias (norm term, mask) of the stage at `st` in the layout of the S^T accumulator.
+template <int DZ>
+__device__ __forceinline__ f32x16 load_bias(const Wave<DZ> &w, const char *st)
+{
+    f32x16 sacc;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const f32x4 bias = *reinterpret_cast<const f32x4 *>(st + w.baddr + a * 32);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) sacc[4 * a + x] = bias[x];
+    }
+    return sacc;
+}
+
+__device__ __forceinline__ float row_max16(const f32x16 &s)
+{
+    float mx = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    return fmaxf(mx, __shfl_xor(mx, 32));
+}
+
+// Raise the reference maximum to cover mx: rescale everything accumulated so far.
+template <int DZ>
+__device__ __forceinline__ void raise_reference(Wave<DZ> &w, float mx)
+{
+    using C = AttnCfg<DZ>;
+    const float m_new = fmaxf(w.m_ref, mx);
+    const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(w.m_ref - m_new);
+    w.m_ref = m_new;
+    w.l_run *= alpha;
+#pragma unroll
+    for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) w.oacc[nb][r] *= alpha;
+}
+
+// Steady-state iteration n (blocks n, n+1, n+2 exist):
+//   O^T += V^T P^T of block n (stage st_pv, probabilities pf),
+//   exponentials of block n+1 from its S^T accumulator `sacc` -> pf (for the next iteration),
+//   S^T of block n+2 (stage st_s) -> sacc,
+//   and the operand prefetch for the first P V MFMAs of the next iteration (stage st_pv_next).
+// `fr` is the operand ring; on entry it holds the operands of operations 0 .. LA-1.
+template <int DZ>
+__device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f32x16 &sacc, bf16x8 (&fr)[AttnCfg<DZ>::RING],
+                                                 const char *st_pv, const char *st_s, const char *st_pv_next)
+{
+    using C = AttnCfg<DZ>;
+    using O = Ops<DZ>;
+    constexpr int N = C::NOPS;
+    constexpr int kRing = C::RING;
+    constexpr int kLookahead = C::LA;
+    const float m_use = w.m_ref == -INFINITY ? 0.f : w.m_ref;
+    f32x16 snew;
+    bf16x8 pn[2];
+    float ex[16];
+    float psum = 0.f;
+    float t[8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        // operand fetch for operation j + kLookahead (wrapping into the next iteration)
+        {
+            constexpr int dummy = 0;
+            (void)dummy;
+            const int jn = j + kLookahead;
+            if (jn < N) {
+                if (O::is_pv(jn))
+                    fr[jn % kRing] = load_pv<DZ>(w, st_pv, O::idx(jn));
+                else
+                    fr[jn % kRing] = load_s<DZ>(w, st_s, O::idx(jn));
+            } else {
+                fr[jn % kRing] = load_pv<DZ>(w, st_pv_next, O::idx(jn - N));
+            }
+        }
+        if (j == kLookahead - 1) snew = load_bias<DZ>(w, st_s);  // before the first S^T MFMA
+        // the MFMA
+        if (O::is_pv(j)) {
+            const int i = O::idx(j);
+            w.oacc[i >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], pf[i & 1], w.oacc[i >> 1], 0, 0, 0);
+        } else {
+            snew = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], w.qf[O::idx(j)], snew, 0, 0, 0);
+        }
+        // softmax slices of block n+1, spread evenly over the operations: the 16 exponentials
+        // (pairs are rounded to bf16 together) and the row maximum for the check below
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            if ((r * N) / 16 != j) continue;
+            ex[r] = __builtin_amdgcn_exp2f(sacc[r] - m_use);
+            // (the empty asm keeps the value here: the rare path below recomputes it, and the
+            // optimiser would otherwise move this work out of the MFMA shadow)
+            asm volatile("" : "+v"(ex[r]));
+            if (r & 1) {
+                const __bf16 b0 = (__bf16)ex[r - 1], b1 = (__bf16)ex[r];
+                pn[r >> 3][(r & 7) - 1] = b0;
+                pn[r >> 3][r & 7] = b1;
+                psum += (float)b0 + (float)b1;  // the denominator sums the rounded weights the MFMA will use
+                asm volatile("" : "+v"(psum));
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (((2 * k + 1) * N) / 24 != j) continue;
+            if (k < 5) t[k] = fmaxf(fmaxf(sacc[3 * k], sacc[3 * k + 1]), sacc[3 * k + 2]);
+            if (k == 5) t[5] = fmaxf(fmaxf(t[0], t[1]), sacc[15]);
+            if (k == 6) t[6] = fmaxf(fmaxf(t[2], t[3]), t[4]);
+            if (k == 7) t[7] = fmaxf(t[5], t[6]);
+        }
+        if (j == N - 4) mx = __shfl_xor(t[7], 32);
+        if (j == N - 1) mx = fmaxf(mx, t[7]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (__any(mx > w.m_ref + kTau)) {
+        // rare: the exponentials above used too small a reference; redo them after rescaling
+        raise_reference<DZ>(w, mx);
+        const float m_new = w.m_ref == -INFINITY ? 0.f : w.m_ref;
+        psum = 0.f;
+        exp_range(sacc, m_new, pn, psum, 0, 16);
+    }
+    w.l_run += psum;
+    pf[0] = pn[0];
+    pf[1] = pn[1];
+    sacc = snew;
+}
+
+template <int DZ, bool FUSED>
 __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p)
 {
     using C = AttnCfg<DZ>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char *ldsK = smem;
-    char *ldsV = smem + C::K_BYTES;
-    float *ldsB = reinterpret_cast<float *>(smem + C::K_BYTES + C::V_BYTES);
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles
-    // so that the query tiles of one (batch, head) share that XCD's L2 copy of K^ and V^.
+    // so that the query tiles of one (batch, head) share that XCD's L2 copy of k^ and v^.
     const int chunk = (p.total_tiles + 7) / 8;
     const int logical = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
     if (logical >= p.total_tiles) return;
     const int bh = logical / p.nQT, qt = logical - bh * p.nQT;
     const int b = bh / p.H;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, g = lane >> 5;
     const int kvlen = p.kvlen[b];
-    const int ntiles = (kvlen + kTileK - 1) / kTileK;
+    const int nblk = (kvlen + kBlk - 1) / kBlk;
     const int irow = qt * kTileQ + wave * 32 + li;  // < Lp always
 
-    // q^ row fragments: features 16*ks + 8*g .. +7 of row irow
-    bf16x8 qf[C::KS];
+    // ---- direct global->LDS loads ------------------------------------------------------------
+    // A wave-wide load writes 64 consecutive 16-byte slots of a stage; the slot decides which
+    // (row, 16-byte column) of the global block the lane fetches.  Slots in the row padding or
+    // past the last row fetch element 0 of the block again (harmless).  Wave w issues entries
+    // w, w+4, ... of the flat list z2 | k^ head | v^ head; surplus entries repeat entry 0 so that
+    // every wave issues the same number of loads per block.
+    Dma<DZ> dma;
+    dma.lane = lane;
+    {
+        const char *Z2b = reinterpret_cast<const char *>(p.Z2 + (size_t)b * p.Lp * DZ);
+        const char *Khb = reinterpret_cast<const char *>(p.Kh + (size_t)bh * p.Lp * kDH);
+        const char *Vhb = reinterpret_cast<const char *>(p.Vh + (size_t)bh * p.Lp * kDH);
+#pragma unroll
+        for (int k = 0; k < C::NIW; ++k) {
+            int i = wave + 4 * k;
+            if (i >= C::NI) i = 0;
+            const bool isz = i < C::NZ;
+            const bool isk = !isz && i < C::NZ + C::NH;
+            const int first = isz ? 0 : (isk ? C::NZ : C::NZ + C::NH);
+            const int spr = isz ? C::Z_SPR : C::H_SPR;        // 16-byte slots per LDS row
+            const int cols = isz ? DZ / 8 : kDH / 8;          // 16-byte columns of a global row
+            const int s = 64 * (i - first) + lane;
+            const int row = s / spr, col = s - row * spr;
+            dma.doff[k] = (row < kBlk && col < cols) ? row * (cols * 16) + col * 16 : 0;
+            dma.src[k] = isz ? Z2b : (isk ? Khb : Vhb);
+            dma.stride[k] = kBlk * cols * 16;
+            dma.ldsoff[k] = i * 1024;
+        }
+    }
+    dma.kbb = reinterpret_cast<const char *>(p.kbias + (size_t)bh * p.Lp);
+    dma.kboff = lane * 16;
+
+    Wave<DZ> w;
+    if (nblk > 0) {
+        issue_block<DZ>(dma, 0, smem);
+        if (1 < nblk) issue_block<DZ>(dma, 1, smem + C::STAGE);
+        if (2 < nblk) issue_block<DZ>(dma, 2, smem + 2 * C::STAGE);
+        if (3 < nblk) issue_block<DZ>(dma, 3, smem + 3 * C::STAGE);
+    }
+
+    // ---- q^ row fragments: features 16*ks + 8*g .. +7 of row irow ---------------------------
     {
         const bf16_t *qh = p.Qh + ((size_t)bh * p.Lp + irow) * kDH;
         const bf16_t *qz = p.Qz + ((size_t)bh * p.Lp + irow) * DZ;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
-            const bf16_t *src = ks < kDH / 16 ? qh + ks * 16 + 8 * g : qz + (ks - kDH / 16) * 16 + 8 * g;
-            qf[ks] = *reinterpret_cast<const bf16x8 *>(src);
+            const bf16_t *src = ks < C::KSH ? qh + ks * 16 + 8 * g : qz + (ks - C::KSH) * 16 + 8 * g;
+            w.qf[ks] = *reinterpret_cast<const bf16x8 *>(src);
         }
     }
-
-    f32x16 oacc[C::NB];
 #pragma unroll
     for (int nb = 0; nb < C::NB; ++nb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[nb][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    const bf16_t *Kh = p.Kh + (size_t)bh * p.Lp * kDH;
-    const bf16_t *Z2 = p.Z2 + (size_t)b * p.Lp * DZ;
-    const bf16_t *VhT = p.VhT + (size_t)bh * p.Lp * kDH;
-    const bf16_t *Z2T = p.Z2T + (size_t)b * p.Lp * DZ;
-    const float *kbias = p.kbias + (size_t)bh * p.Lp;
-
-    uint4 kreg[C::K_CHUNKS], vreg[C::V_CHUNKS];
-    float kbreg = 0.f;
-
-#define FIPA_LOAD_K(T)                                                                             \
-    do {                                                                                           \
-        const int j0_ = (T) * kTileK;                                                              \
-        _Pragma("unroll") for (int it = 0; it < C::K_CHUNKS; ++it) {                               \
-            const int q_ = it * 256 + tid;                                                         \
-            const int row_ = q_ / (C::DQK / 8), cc_ = q_ - row_ * (C::DQK / 8);                    \
-            const bf16_t *src_ = cc_ < kDH / 8 ? Kh + (size_t)(j0_ + row_) * kDH + cc_ * 8         \
-                                               : Z2 + (size_t)(j0_ + row_) * DZ + (cc_ - kDH / 8) * 8; \
-            kreg[it] = *reinterpret_cast<const uint4 *>(src_);                                     \
-        }                                                                                          \
-        if (tid < kTileK) kbreg = kbias[j0_ + tid];                                                \
-    } while (0)
-#define FIPA_STORE_K()                                                                             \
-    do {                                                                                           \
-        _Pragma("unroll") for (int it = 0; it < C::K_CHUNKS; ++it) {                               \
-            const int q_ = it * 256 + tid;                                                         \
-            const int row_ = q_ / (C::DQK / 8), cc_ = q_ - row_ * (C::DQK / 8);                    \
-            *reinterpret_cast<uint4 *>(ldsK + row_ * C::KSTR + cc_ * 16) = kreg[it];               \
-        }                                                                                          \
-        if (tid < kTileK) ldsB[tid] = kbreg;                                                       \
-    } while (0)
-#define FIPA_LOAD_V(T)                                                                             \
-    do {                                                                                           \
-        const bf16_t *vh_ = VhT + (size_t)(T) * kDH * kTileK;                                      \
-        const bf16_t *zt_ = Z2T + (size_t)(T) * DZ * kTileK;                                       \
-        _Pragma("unroll") for (int it = 0; it < C::V_CHUNKS; ++it) {                               \
-            const int q_ = it * 256 + tid;                                                         \
-            const int row_ = q_ >> 3, cc_ = q_ & 7;                                                \
-            const bf16_t *src_ = row_ < kDH ? vh_ + row_ * kTileK + cc_ * 8                        \
-                                            : zt_ + (row_ - kDH) * kTileK + cc_ * 8;               \
-            vreg[it] = *reinterpret_cast<const uint4 *>(src_);                                     \
-        }                                                                                          \
-    } while (0)
-#define FIPA_STORE_V()                                                                             \
-    do {                                                                                           \
-        _Pragma("unroll") for (int it = 0; it < C::V_CHUNKS; ++it) {                               \
-            const int q_ = it * 256 + tid;                                                         \
-            const int row_ = q_ >> 3, cc_ = q_ & 7;                                                \
-            *reinterpret_cast<uint4 *>(ldsV + row_ * C::VSTR + cc_ * 16) = vreg[it];               \
-        }                                                                                          \
-    } while (0)
-
-    if (ntiles > 0) {
-        FIPA_LOAD_K(0);
-        FIPA_STORE_K();
+        for (int r = 0; r < 16; ++r) w.oacc[nb][r] = 0.f;
+    w.m_ref = -INFINITY;
+    w.l_run = 0.f;
+    {
+        const int l16 = lane & 15, grp2 = (lane >> 4) & 1, e4 = l16 >> 2, j4 = l16 & 3;
+        w.kaddr_h = C::KH_OFF + li * kHS + g * 16;
+        w.kaddr_z = C::Z_OFF + li * C::ZS + g * 16;
+        w.vaddr_h = C::VH_OFF + (4 * g + e4) * kHS + (16 * grp2 + 4 * j4) * 2;
+        w.vaddr_z = C::Z_OFF + (4 * g + e4) * C::ZS + (16 * grp2 + 4 * j4) * 2;
+        w.baddr = C::KB_OFF + 16 * g;
     }
-    __syncthreads();
 
-    for (int t = 0; t < ntiles; ++t) {
-        FIPA_LOAD_V(t);
-
-        // S^T = K^ Q^T, accumulator preset with the per-key bias (norm term, mask)
-        f32x16 sacc[2];
+    // ---- prologue: blocks 0 and 1 ----------------------------------------------------------------
+    bf16x8 pf[2];
+    f32x16 sacc;
+    bf16x8 fr[C::RING];
+    wait_vmem<0>();  // q^ fragments and the first stages; nothing the compiler tracks stays pending
+    if (nblk > 0) {
+        wg_barrier();
+        sacc = s_block<DZ>(w, smem);
+        const float mx = row_max16(sacc);
+        w.m_ref = mx;
+        float psum = 0.f;
+        exp_range(sacc, mx == -INFINITY ? 0.f : mx, pf, psum, 0, 16);
+        w.l_run = psum;
+        if (nblk > 1) sacc = s_block<DZ>(w, smem + C::STAGE);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int j = 0; j < C::LA; ++j) fr[j] = load_pv<DZ>(w, smem, j);
+    }
+
+    // ---- steady state: iteration n works on blocks n (P V), n+1 (exp), n+2 (S^T) ---------------
+    int s0 = 0;  // stage of block n
+    for (int n = 0; n + 2 < nblk; ++n) {
+        // Block n+2 must have landed (block n+3 may still be in flight); the barrier also tells
+        // everyone that the stage of block n-1 is free again.
+        if (n >= 1 && n + 3 < nblk)
+            wait_vmem<C::VM_PER_BLOCK>();
+        else
+            wait_vmem<0>();
+        wg_barrier();
+        const int s1 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
+        const int s2 = s0 + 2 < C::NSTAGE ? s0 + 2 : s0 + 2 - C::NSTAGE;
+        const int s4 = s0 + 4 < C::NSTAGE ? s0 + 4 : s0 + 4 - C::NSTAGE;
+        if (n + 4 < nblk) issue_block<DZ>(dma, n + 4, smem + s4 * C::STAGE);
+        steady_iteration<DZ>(w, pf, sacc, fr, smem + s0 * C::STAGE, smem + s2 * C::STAGE, smem + s1 * C::STAGE);
+        s0 = s1;
+    }
+
+    // ---- drain: the last two blocks -----------------------------------------------------------------
+    if (nblk > 1) {
+        // P V of block nblk-2, exponentials of block nblk-1
+        const char *st = smem + s0 * C::STAGE;
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb) pv_block<DZ>(w, st, pf, nb);
+        const float mx = row_max16(sacc);
+        if (__any(mx > w.m_ref + kTau)) raise_reference<DZ>(w, mx);
+        float psum = 0.f;
+        exp_range(sacc, w.m_ref == -INFINITY ? 0.f : w.m_ref, pf, psum, 0, 16);
+        w.l_run += psum;
+        s0 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
+    }
+    if (nblk > 0) {
+        const char *st = smem + s0 * C::STAGE;
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb) pv_block<DZ>(w, st, pf, nb);
+    }
+
+    const float l_tot = w.l_run + __shfl_xor(w.l_run, 32);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    const float lse2 = l_tot > 0.f ? w.m_ref + __log2f(l_tot) : -INFINITY;
+    f32x16(&oacc)[C::NB] = w.oacc;
+
+    if constexpr (!FUSED) {
+        // write O^ (row irow, columns 32*nb + 8*(r/4) + 4*g + r%4) and the log2 LSE
+        float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::DV;
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-                const f32x4 bias = *reinterpret_cast<const f32x4 *>(&ldsB[32 * kb + 8 * a + 4 * g]);
+                f32x4 out;
 #pragma unroll
-                for (int x = 0; x < 4; ++x) sacc[kb][4 * a + x] = bias[x];
+                for (int x = 0; x < 4; ++x) out[x] = oacc[nb][4 * a + x] * inv;
+                *reinterpret_cast<f32x4 *>(orow + 32 * nb + 8 * a + 4 * g) = out;
             }
+        if (g == 0) p.lse2[(size_t)bh * p.Lp + irow] = lse2;
+    } else {
+        // ---- split, inverse frame, z1 contraction (Algorithm 1 steps 8-9, Eq. 4); c = 16, Pv = 8
+        constexpr int c = 16, Pv = 8;
+        if (irow >= p.L) return;
+        const int h = bh - b * p.H;
+        const bool valid = (p.mask ? p.mask[(size_t)b * p.L + irow] != 0 : true) && l_tot > 0.f;
+        const float sc = valid ? inv : 0.f;
+        const size_t row = ((size_t)b * p.L + irow) * p.H + h;
+        // scalar part: columns 8a + 4g + x, a = 0, 1
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ldsK + (32 * kb + li) * C::KSTR + ks * 32 + g * 16);
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
-            }
-
-        // online softmax for this lane's query row (its keys: 16 per block here, the other 16
-        // in the lane 32 away)
-        float mx = sacc[0][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
-        bf16x8 pf[2][2];
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float e = __builtin_amdgcn_exp2f(sacc[kb][r] - m_use);
-                const __bf16 eb = (__bf16)e;
-                pf[kb][r >> 3][r & 7] = eb;
-                psum += (float)eb;  // the denominator sums the rounded weights the MFMA will use
-            }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[nb][r] *= alpha;
-
-        FIPA_STORE_V();
-        __syncthreads();
-        if (t + 1 < ntiles) FIPA_LOAD_K(t + 1);
-
-        // O^T += V^T P^T
-#pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
-                        ldsV + (32 * nb + li) * C::VSTR + (kb * 32 + tt * 16 + 8 * g) * 2);
-                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][tt], oacc[nb], 0, 0, 0);
-                }
-
-        if (t + 1 < ntiles) FIPA_STORE_K();
-        __syncthreads();
-    }
-
-    // normalise and write O^ (row irow, columns 32*nb + 8*(r/4) + 4*g + r%4) and the log2 LSE
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::DV;
-#pragma unroll
-    for (int nb = 0; nb < C::NB; ++nb)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
+        for (int a = 0; a < 2; ++a) {
             f32x4 out;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) out[x] = oacc[nb][4 * a + x] * inv;
-            *reinterpret_cast<f32x4 *>(orow + 32 * nb + 8 * a + 4 * g) = out;
+            for (int x = 0; x < 4; ++x) out[x] = oacc[0][4 * a + x] * sc;
+            *reinterpret_cast<f32x4 *>(p.o + row * c + 8 * a + 4 * g) = out;
         }
-    if (g == 0) p.lse2[(size_t)bh * p.Lp + irow] = l_tot > 0.f ? m_run + __log2f(l_tot) : -INFINITY;
+        // point part: this half owns points 4g .. 4g+3, hi parts in slots u = 0..11, lo parts in
+        // slots 12..23; slot u sits in column 16 + 8*(u/4) + 4g + u%4 (see v_pt_col)
+        {
+            const float *R = p.rot + ((size_t)b * p.L + irow) * 9;
+            const float *tr = p.trans + ((size_t)b * p.L + irow) * 3;
+            float Rm[9], tc[3];
+#pragma unroll
+            for (int a = 0; a < 9; ++a) Rm[a] = R[a];
+#pragma unroll
+            for (int a = 0; a < 3; ++a) tc[a] = tr[a] - p.cen[4 * b + a];
+            float Gv[12];
+#pragma unroll
+            for (int u = 0; u < 12; ++u) {
+                const int dh = 16 + 8 * (u >> 2) + (u & 3);  // column for g = 0; g = 1 adds 4
+                const int dl = 16 + 8 * ((u + 12) >> 2) + ((u + 12) & 3);
+                const float hi = oacc[dh >> 5][4 * ((dh & 31) >> 3) + (dh & 3)];
+                const float lo = oacc[dl >> 5][4 * ((dl & 31) >> 3) + (dl & 3)];
+                Gv[u] = (hi + lo) * inv;
+            }
+            float outp[12];
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) {
+                const float rx = Gv[3 * pp] - tc[0], ry = Gv[3 * pp + 1] - tc[1], rz = Gv[3 * pp + 2] - tc[2];
+#pragma unroll
+                for (int x = 0; x < 3; ++x) {
+                    const float val = Rm[x] * rx + Rm[3 + x] * ry + Rm[6 + x] * rz;  // R^T
+                    outp[3 * pp + x] = valid ? val : 0.f;
+                }
+            }
+            float *dst = p.o_pts + row * (Pv * 3) + 12 * g;
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+                *reinterpret_cast<f32x4 *>(dst + 4 * a) =
+                    (f32x4){outp[4 * a], outp[4 * a + 1], outp[4 * a + 2], outp[4 * a + 3]};
+        }
+        // pair part: o~[d'] = sum_rho z1[rho, d'] * U[rho, d']; the lane holds columns 8a + 4g + x
+        {
+            const int cz = p.cz;
+            const bf16_t *z1 = p.z1 + ((size_t)b * p.L + irow) * DZ;
+            float *dst = p.o_pair + row * cz;
+#pragma unroll
+            for (int nb = C::NBH; nb < C::NB; ++nb)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const int dz = 32 * (nb - C::NBH) + 8 * a + 4 * g;  // column in [0, DZ)
+                    const uint2 zraw = *reinterpret_cast<const uint2 *>(z1 + dz);
+                    const bf16_t *zb = reinterpret_cast<const bf16_t *>(&zraw);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) oacc[nb][4 * a + x] *= bf2f(zb[x]) * sc;
+                }
+            // sum over rho: column dz of U belongs to output d' = dz % cz
+            if (cz >= 32) {
+                const int bps = cz / 32;  // 32-column blocks per factor slice
+#pragma unroll
+                for (int zb_ = 0; zb_ < C::NB - C::NBH; ++zb_) {
+                    if (zb_ >= bps) break;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4 out;
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) out[x] = oacc[C::NBH + zb_][4 * a + x];
+#pragma unroll
+                        for (int z2_ = zb_ + 1; z2_ < C::NB - C::NBH; ++z2_)
+                            if ((z2_ - zb_) % bps == 0)
+#pragma unroll
+                                for (int x = 0; x < 4; ++x) out[x] += oacc[C::NBH + z2_][4 * a + x];
+                        *reinterpret_cast<f32x4 *>(dst + 32 * zb_ + 8 * a + 4 * g) = out;
+                    }
+                }
+            } else {
+                // cz in {8, 16}: slices are narrower than a block
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    if (8 * a >= cz) break;
+                    f32x4 out = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int nb = C::NBH; nb < C::NB; ++nb)
+#pragma unroll
+                        for (int a2 = 0; a2 < 4; ++a2) {
+                            const int dz = 32 * (nb - C::NBH) + 8 * a2;
+                            if (dz % cz == 8 * a)
+#pragma unroll
+                                for (int x = 0; x < 4; ++x) out[x] += oacc[nb][4 * a2 + x];
+                        }
+                    *reinterpret_cast<f32x4 *>(dst + 8 * a + 4 * g) = out;
+                }
+            }
+        }
+        if (p.lse && g == 0)
+            p.lse[(size_t)bh * p.L + irow] = valid ? lse2 * kLn2 - p.qbias[(size_t)bh * p.Lp + irow] : 0.f;
+    }
 }
 
-template <int DZ>
+template <int DZ, bool FUSED>
 hipError_t launch(const AttnParams &p, hipStream_t stream)
 {
     using C = AttnCfg<DZ>;
-    hipError_t e = hipFuncSetAttribute((const void *)fipa_attn_fwd_bf16_kernel<DZ>,
+    hipError_t e = hipFuncSetAttribute((const void *)fipa_attn_fwd_bf16_kernel<DZ, FUSED>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     const int chunk = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL(fipa_attn_fwd_bf16_kernel<DZ>, dim3(chunk * 8), dim3(256), C::LDS_BYTES,
-                       stream, p);
+    hipLaunchKernelGGL((fipa_attn_fwd_bf16_kernel<DZ, FUSED>), dim3(chunk * 8), dim3(256),
+                       C::LDS_BYTES, stream, p);
     return hipGetLastError();
+}
+
+template <int DZ>
+hipError_t launch_dz(const AttnParams &p, bool fused, hipStream_t stream)
+{
+    return fused ? launch<DZ, true>(p, stream) : launch<DZ, false>(p, stream);
 }
 
 }  // namespace
 
-hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, hipStream_t stream)
+hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream)
 {
     switch (DZ) {
-        case 32: return launch<32>(p, stream);
-        case 64: return launch<64>(p, stream);
-        case 128: return launch<128>(p, stream);
-        case 256: return launch<256>(p, stream);
+        case 32: return launch_dz<32>(p, fused, stream);
+        case 64: return launch_dz<64>(p, fused, stream);
+        case 128: return launch_dz<128>(p, fused, stream);
+        case 256: return launch_dz<256>(p, fused, stream);
         default: return hipErrorInvalidValue;
     }
 }

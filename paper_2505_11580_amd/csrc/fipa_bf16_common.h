@@ -4,13 +4,13 @@
 // Lifted features (Algorithm 1 steps 4-6, rewritten without changing the result):
 //   q^ = [ q | Qhi Qhi Qlo Qlo | log2e * w_L * w_b (.) z1 ]
 //   k^ = [ log2e*w_L/sqrt(c) * k | Khi Klo Khi Klo | z2 ]      K = log2e*gamma*w_L*w_C * (T o k_pts)
-//   v^ = [ v | Vhi | Vlo | z2 ]
+//   v^ = [ v | Vhi, Vlo (interleaved per lane half, see v_pt_col) | z2 ]
 // Global point coordinates are carried as the sum of two bf16 numbers (hi + lo), so that the
 // four partial products Qhi.Khi + Qhi.Klo + Qlo.Khi + Qlo.Klo reproduce the fp32 dot product;
 // the per-key term -|K|^2/2 of the expanded squared distance is added in fp32 (kbias), and the
 // per-query term |Q|^2 is constant along the softmax axis and is dropped (it returns in lse).
-// The first kDH columns are head specific; the pair-factor part is shared by all heads and,
-// on the key side, by k^ and v^.
+// The first kDH columns are head specific; the pair-factor part z2 is stored once per batch
+// element and serves every head, both as key features and as value features.
 #pragma once
 
 #include "fipa_internal.h"
@@ -31,29 +31,32 @@ __device__ __forceinline__ bf16_t f2bf(float f)
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((unsigned)h) << 16); }
 
-// Position of key kk (0..63) inside a transposed value tile row.  Within each group of 16
-// keys the order is the one in which a lane of the S^T accumulator holds its keys, so that the
-// probabilities can be fed to the second MFMA straight from registers.
-__host__ __device__ __forceinline__ int vt_pos(int kk)
+// Column of the head-specific value block that holds part `lo` (0 = hi, 1 = lo) of the global
+// value coordinate (point pt, axis ax).  The transposed output accumulator gives the lanes
+// 0-31 of a wave the columns d with (d/4)%2 == 0 and the lanes 32-63 the others; this layout
+// puts all six numbers of a point into one half, so the inverse frame needs no lane exchange:
+// half g' = pt / PH owns points g'*PH .. g'*PH+PH-1 (PH = ceil(Pv/2)).
+__host__ __device__ __forceinline__ int v_pt_col(int c, int Pv, int pt, int ax, int lo)
 {
-    const int grp = kk & ~15, x = kk & 15;
-    const int g = (x >> 2) & 1, s = ((x >> 3) << 2) | (x & 3);
-    return grp + 8 * g + s;
+    const int PH = (Pv + 1) / 2;
+    const int gh = pt / PH;
+    const int u = 3 * (pt - gh * PH) + ax + 3 * PH * lo;
+    return c + 8 * (u >> 2) + 4 * gh + (u & 3);
 }
-
-// Column of the head-specific value block holding part `lo` (0 = hi, 1 = lo) of global value
-// coordinate cc (= 3*point + axis).
-__host__ __device__ __forceinline__ int v_pt_col(int c, int Pv, int cc, int lo)
+// Largest column index + 1 that v_pt_col can return.
+__host__ __device__ __forceinline__ int v_cols_needed(int c, int Pv)
 {
-    return c + lo * 3 * Pv + cc;
+    const int PH = (Pv + 1) / 2;
+    return c + 8 * ((6 * PH + 3) / 4);
 }
 
 struct Bf16Layout {
     int Lp, NT, DZ;
-    size_t cen, kvlen, Qh, Qz, Kh, Z2, kbias, qbias, VhT, Z2T, Ohat, lse2, total;
+    size_t cen, kvlen, Qh, Qz, Kh, Vh, Z2, kbias, qbias, Ohat, lse2, total;
 };
 
-inline Bf16Layout bf16_layout(const fipa_desc &d)
+// with_ohat: the unfused epilogue needs the lifted output O^ in memory.
+inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
 {
     Bf16Layout w;
     w.Lp = (int)align_up((size_t)d.L, kTileQ);
@@ -71,33 +74,40 @@ inline Bf16Layout bf16_layout(const fipa_desc &d)
     w.Qh = take(BH * w.Lp * kDH * 2);
     w.Qz = take(BH * w.Lp * (size_t)w.DZ * 2);
     w.Kh = take(BH * w.Lp * kDH * 2);
+    w.Vh = take(BH * w.Lp * kDH * 2);
     w.Z2 = take((size_t)d.B * w.Lp * w.DZ * 2);
     w.kbias = take(BH * w.Lp * sizeof(float));
     w.qbias = take(BH * w.Lp * sizeof(float));
-    w.VhT = take(BH * w.Lp * kDH * 2);
-    w.Z2T = take((size_t)d.B * w.Lp * w.DZ * 2);
-    w.Ohat = take(BH * w.Lp * (size_t)(kDH + w.DZ) * sizeof(float));
     w.lse2 = take(BH * w.Lp * sizeof(float));
+    w.Ohat = with_ohat ? take(BH * w.Lp * (size_t)(kDH + w.DZ) * sizeof(float)) : 0;
     w.total = off;
     return w;
 }
+
+// The fused epilogue is compiled for the AlphaFold2-style head shape only.
+inline bool bf16_fused_epilogue(const fipa_desc &d) { return d.c == 16 && d.Pv == 8; }
 
 struct PackParams {
     const bf16_t *q, *k, *v, *q_pts, *k_pts, *v_pts, *z1, *z2;
     const float *rot, *trans, *w_b, *gamma, *cen;
     const uint8_t *mask;
-    bf16_t *Qh, *Qz, *Kh, *Z2, *VhT, *Z2T;
+    bf16_t *Qh, *Qz, *Kh, *Vh, *Z2;
     float *kbias, *qbias;
     int B, L, Lp, NT, H, c, Pq, Pv, cz, r, DZ;
     float w_L, w_C, qk_scale;
 };
 
 struct AttnParams {
-    const bf16_t *Qh, *Qz, *Kh, *Z2, *VhT, *Z2T;
-    const float *kbias;
+    const bf16_t *Qh, *Qz, *Kh, *Vh, *Z2;
+    const float *kbias, *qbias;
     const int *kvlen;
-    float *Ohat, *lse2;
-    int B, L, Lp, H, NT, nQT, total_tiles;
+    float *Ohat, *lse2;  // unfused epilogue only
+    // fused epilogue: final outputs and what they need
+    const float *rot, *trans, *cen;
+    const bf16_t *z1;
+    const uint8_t *mask;
+    float *o, *o_pts, *o_pair, *lse;
+    int B, L, Lp, H, NT, nQT, total_tiles, cz, r;
 };
 
 struct EpiParams {
@@ -109,7 +119,7 @@ struct EpiParams {
 };
 
 hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream);
-hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, hipStream_t stream);
+hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream);
 hipError_t launch_epilogue_bf16(const EpiParams &p, hipStream_t stream);
 
 }  // namespace fipa

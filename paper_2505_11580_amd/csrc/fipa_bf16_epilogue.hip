@@ -29,8 +29,7 @@ __global__ __launch_bounds__(256) void fipa_epilogue_bf16_kernel(EpiParams p)
         float val = 0.f;
         if (valid) {
             for (int y = 0; y < 3; ++y) {
-                const int cc = 3 * pp + y;
-                const float G = oh[v_pt_col(c, p.Pv, cc, 0)] + oh[v_pt_col(c, p.Pv, cc, 1)];
+                const float G = oh[v_pt_col(c, p.Pv, pp, y, 0)] + oh[v_pt_col(c, p.Pv, pp, y, 1)];
                 val += R[3 * y + x] * (G - (t[y] - p.cen[4 * b + y]));
             }
         }

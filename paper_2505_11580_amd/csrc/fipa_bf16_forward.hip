@@ -3,11 +3,12 @@
 
 namespace fipa {
 
-size_t bf16_forward_workspace(const fipa_desc &d) { return bf16_layout(d).total; }
+size_t bf16_forward_workspace(const fipa_desc &d) { return bf16_layout(d, !bf16_fused_epilogue(d)).total; }
 
 hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream_t stream)
 {
-    const Bf16Layout w = bf16_layout(d);
+    const bool fused = bf16_fused_epilogue(d);
+    const Bf16Layout w = bf16_layout(d, !fused);
     char *base = static_cast<char *>(ws);
     float *cen = reinterpret_cast<float *>(base + w.cen);
     int *kvlen = reinterpret_cast<int *>(base + w.kvlen);
@@ -26,7 +27,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     pk.mask = a.mask;
     pk.Qh = (bf16_t *)(base + w.Qh); pk.Qz = (bf16_t *)(base + w.Qz);
     pk.Kh = (bf16_t *)(base + w.Kh); pk.Z2 = (bf16_t *)(base + w.Z2);
-    pk.VhT = (bf16_t *)(base + w.VhT); pk.Z2T = (bf16_t *)(base + w.Z2T);
+    pk.Vh = (bf16_t *)(base + w.Vh);
     pk.kbias = (float *)(base + w.kbias); pk.qbias = (float *)(base + w.qbias);
     pk.B = d.B; pk.L = d.L; pk.Lp = w.Lp; pk.NT = w.NT; pk.H = d.H; pk.c = d.c; pk.Pq = d.Pq;
     pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.DZ;
@@ -36,15 +37,19 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     timer.end(0);
 
     AttnParams at;
-    at.Qh = pk.Qh; at.Qz = pk.Qz; at.Kh = pk.Kh; at.Z2 = pk.Z2; at.VhT = pk.VhT; at.Z2T = pk.Z2T;
-    at.kbias = pk.kbias; at.kvlen = kvlen;
-    at.Ohat = (float *)(base + w.Ohat); at.lse2 = (float *)(base + w.lse2);
+    at.Qh = pk.Qh; at.Qz = pk.Qz; at.Kh = pk.Kh; at.Vh = pk.Vh; at.Z2 = pk.Z2;
+    at.kbias = pk.kbias; at.qbias = pk.qbias; at.kvlen = kvlen;
+    at.Ohat = fused ? nullptr : (float *)(base + w.Ohat);
+    at.lse2 = (float *)(base + w.lse2);
+    at.rot = a.rot; at.trans = a.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.mask;
+    at.o = a.o; at.o_pts = a.o_pts; at.o_pair = a.o_pair; at.lse = a.lse;
     at.B = d.B; at.L = d.L; at.Lp = w.Lp; at.H = d.H; at.NT = w.NT;
-    at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H;
+    at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r;
     timer.begin(1);
-    e = launch_attn_fwd_bf16(at, w.DZ, stream);
+    e = launch_attn_fwd_bf16(at, w.DZ, fused, stream);
     if (e != hipSuccess) return e;
     timer.end(1);
+    if (fused) return hipSuccess;  // steps 8-9 ran inside the attention kernel
 
     EpiParams ep;
     ep.Ohat = at.Ohat; ep.lse2 = at.lse2; ep.qbias = pk.qbias; ep.rot = a.rot; ep.trans = a.trans;

@@ -9,8 +9,8 @@ namespace {
 constexpr int kRowStride = kDH + 8;  // bf16 per staged row; the 16-byte pad spreads LDS banks
 
 // One wave per (batch, head, 64-residue tile); lane <-> residue.  Writes the head-specific
-// columns of q^, k^ (row major) and v^ (tile-transposed), the fp32 per-key bias -|K|^2/2
-// (-inf for masked keys) and the per-query term |Q|^2/2 that the softmax drops.
+// columns of q^, k^ and v^ (row major), the fp32 per-key bias -|K|^2/2 (-inf for masked keys)
+// and the per-query term |Q|^2/2 that the softmax drops.
 __global__ __launch_bounds__(256) void fipa_pack_heads_bf16_kernel(PackParams p)
 {
     extern __shared__ __attribute__((aligned(16))) bf16_t stage_raw[];
@@ -81,8 +81,8 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_bf16_kernel(PackParams p)
                 const float Vg =
                     Rm[3 * a] * vl[0] + Rm[3 * a + 1] * vl[1] + Rm[3 * a + 2] * vl[2] + tc[a];
                 const bf16_t vh = f2bf(Vg), vlo = f2bf(Vg - bf2f(vh));
-                rv[v_pt_col(c, Pv, 3 * pp + a, 0)] = vh;
-                rv[v_pt_col(c, Pv, 3 * pp + a, 1)] = vlo;
+                rv[v_pt_col(c, Pv, pp, a, 0)] = vh;
+                rv[v_pt_col(c, Pv, pp, a, 1)] = vlo;
             }
         }
     }
@@ -91,34 +91,27 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_bf16_kernel(PackParams p)
     if (!head_ok) return;
     p.kbias[bh * p.Lp + i] = kb;
     p.qbias[bh * p.Lp + i] = qb;
-    // rows of q^ and k^: the wave's 64 rows x 128 bytes are contiguous in memory
+    // the wave's 64 rows x 128 bytes of each tensor are contiguous in memory
     const size_t tile_off = (bh * p.Lp + (size_t)tile * kTileK) * kDH;
     uint4 *dq = reinterpret_cast<uint4 *>(p.Qh + tile_off);
     uint4 *dk = reinterpret_cast<uint4 *>(p.Kh + tile_off);
+    uint4 *dv = reinterpret_cast<uint4 *>(p.Vh + tile_off);
     for (int it = 0; it < 8; ++it) {
         const int chunk = it * 64 + lane, r_ = chunk >> 3, cc = chunk & 7;
         dq[chunk] = *reinterpret_cast<const uint4 *>(&stage[wave][0][r_][cc * 8]);
         dk[chunk] = *reinterpret_cast<const uint4 *>(&stage[wave][1][r_][cc * 8]);
+        dv[chunk] = *reinterpret_cast<const uint4 *>(&stage[wave][2][r_][cc * 8]);
     }
-    // head block of v^, transposed to [d][key position]; a wave writes 128 contiguous bytes per d
-    bf16_t *dv = p.VhT + tile_off;
-    const int pos = vt_pos(lane);
-    for (int d = 0; d < kDH; ++d) dv[d * kTileK + pos] = stage[wave][2][lane][d];
 }
 
-constexpr int kZPad = 2;  // bf16 of padding per staged z row (odd dword stride)
-
-// One workgroup per (batch, 64-residue tile): copies z2 (zeroing masked residues), writes its
-// tile-transposed twin, and forms the query-side factor bias vectors
-// b^{h1} = log2e * w_L * w_b[h] (.) z1 for every head (Algorithm 1 steps 2-3; Eq. 3 puts w_L on
-// the bias, the log2e turns exp into exp2).
+// One workgroup per (batch, 64-residue tile): copies z2 (zeroing masked residues) and forms
+// the query-side factor bias vectors b^{h1} = log2e * w_L * w_b[h] (.) z1 for every head
+// (Algorithm 1 steps 2-3; Eq. 3 puts w_L on the bias, the log2e turns exp into exp2).
 __global__ __launch_bounds__(256) void fipa_pack_pair_bf16_kernel(PackParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) bf16_t zs[];  // [64][DZ + kZPad]
     const int tile = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const int DZ = p.DZ, ZS = DZ + kZPad;
+    const int DZ = p.DZ;
     const int chunks_per_row = DZ / 8;
-    // z2 tile -> Z2 (row major) and LDS
     for (int idx = tid; idx < kTileK * chunks_per_row; idx += 256) {
         const int r_ = idx / chunks_per_row, cc = idx - r_ * chunks_per_row;
         const int i = tile * kTileK + r_;
@@ -126,23 +119,6 @@ __global__ __launch_bounds__(256) void fipa_pack_pair_bf16_kernel(PackParams p)
         uint4 val = make_uint4(0, 0, 0, 0);
         if (ok) val = *reinterpret_cast<const uint4 *>(p.z2 + ((size_t)b * p.L + i) * DZ + cc * 8);
         *reinterpret_cast<uint4 *>(p.Z2 + ((size_t)b * p.Lp + i) * DZ + cc * 8) = val;
-        const bf16_t *e = reinterpret_cast<const bf16_t *>(&val);
-        for (int x = 0; x < 8; ++x) zs[r_ * ZS + cc * 8 + x] = e[x];
-    }
-    __syncthreads();
-    // Z2T[b][tile][d][pos]: each thread gathers 8 key positions of one feature row
-    bf16_t *zt = p.Z2T + ((size_t)b * p.NT + tile) * (size_t)DZ * kTileK;
-    for (int idx = tid; idx < DZ * 8; idx += 256) {
-        const int d = idx >> 3, pc = idx & 7;
-        __attribute__((aligned(16))) bf16_t out[8];
-        for (int x = 0; x < 8; ++x) {
-            const int pos = pc * 8 + x;
-            // inverse of vt_pos within the group of 16
-            const int grp = pos & ~15, y = pos & 15, g = y >> 3, s = y & 7;
-            const int kk = grp + 8 * (s >> 2) + 4 * g + (s & 3);
-            out[x] = zs[kk * ZS + d];
-        }
-        *reinterpret_cast<uint4 *>(zt + (size_t)d * kTileK + pc * 8) = *reinterpret_cast<const uint4 *>(out);
     }
     // Qz[b][h][i][x]
     const float bscale = kLog2e * p.w_L;
@@ -178,11 +154,7 @@ hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream)
                        lds_heads, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t lds = (size_t)kTileK * (p.DZ + kZPad) * sizeof(bf16_t);
-    e = hipFuncSetAttribute((const void *)fipa_pack_pair_bf16_kernel,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fipa_pack_pair_bf16_kernel, dim3(p.NT, p.B), dim3(256), lds, stream, p);
+    hipLaunchKernelGGL(fipa_pack_pair_bf16_kernel, dim3(p.NT, p.B), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
