@@ -9,7 +9,8 @@ import math
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfipa.so")
+# FIPA_LIB selects another build of the same library (e.g. one compiled with different flags)
+LIB_PATH = os.environ.get("FIPA_LIB") or os.path.join(_HERE, "libfipa.so")
 
 FIPA_OK = 0
 FIPA_ERR_INVALID_ARG = -1

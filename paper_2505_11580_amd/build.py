@@ -18,25 +18,25 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, jobs: int = 8) -> str:
+def build(verbose: bool = False, jobs: int = 8, csrc: str = CSRC, out: str = LIB, extra=()) -> str:
     """Compile every csrc/*.hip to an object (in parallel) and link libfipa.so."""
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(os.path.dirname(out), "_build_" + os.path.basename(out)) if out != LIB else os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
-    for src in sources():
+    for src in sorted(glob.glob(os.path.join(csrc, "*.hip"))):
         obj = os.path.join(objdir, os.path.basename(src) + ".o")
         objs.append(obj)
-        cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+        cmd = [HIPCC] + [f if f != CSRC else csrc for f in FLAGS] + list(extra) + ["-c", src, "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         if len(procs) >= jobs:
             _drain(procs, verbose)
     _drain(procs, verbose)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if out.returncode != 0:
-        raise RuntimeError("link failed:\n" + out.stdout)
-    return LIB
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link failed:\n" + res.stdout)
+    return out
 
 
 def _drain(procs, verbose):

@@ -36,6 +36,9 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr float kTau = 8.0f;
 constexpr int kBlk = 32;           // keys per LDS stage
@@ -166,17 +169,26 @@ __device__ __forceinline__ void pv_block(Wave<DZ> &w, const char *__restrict__ s
     }
 }
 
-// Exponentials of elements [r0, r1) of an S^T block against the reference maximum; the
-// denominator sums the bf16-rounded weights that the MFMA will use.
-__device__ __forceinline__ void exp_range(const f32x16 &sacc, float m_use, bf16x8 (&pf)[2], float &psum, int r0, int r1)
+// Two probabilities -> one packed bf16 pair (one v_cvt_pk_bf16_f32), and their rounded values
+// added to the running denominator (one v_dot2c_f32_bf16): the denominator must sum exactly
+// the weights the MFMA will use, so that the output stays a convex combination of the values.
+__device__ __forceinline__ unsigned pack_pair(float e0, float e1, float &psum)
 {
+    const bf16x2 b = __builtin_convertvector((f32x2){e0, e1}, bf16x2);
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    psum = __builtin_amdgcn_fdot2_f32_bf16(b, ones, psum, false);
+    return __builtin_bit_cast(unsigned, b);
+}
+
+// All 16 exponentials of an S^T block against the reference maximum -> MFMA B operands.
+__device__ __forceinline__ void exp_block(const f32x16 &sacc, float m_use, bf16x8 (&pf)[2], float &psum)
+{
+    unsigned pp[8];
 #pragma unroll
-    for (int r = r0; r < r1; ++r) {
-        const float ex = __builtin_amdgcn_exp2f(sacc[r] - m_use);
-        const __bf16 eb = (__bf16)ex;
-        pf[r >> 3][r & 7] = eb;
-        psum += (float)eb;
-    }
+    for (int r = 0; r < 16; r += 2)
+        pp[r >> 1] = pack_pair(__builtin_amdgcn_exp2f(sacc[r] - m_use), __builtin_amdgcn_exp2f(sacc[r + 1] - m_use), psum);
+    pf[0] = __builtin_bit_cast(bf16x8, (u32x4){pp[0], pp[1], pp[2], pp[3]});
+    pf[1] = __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]});
 }
 
 // Source side of the direct global->LDS loads of one wave.
@@ -284,9 +296,11 @@ __device__ __forceinline__ void raise_reference(Wave<DZ> &w, float mx)
     w.m_ref = m_new;
     w.l_run *= alpha;
 #pragma unroll
-    for (int nb = 0; nb < C::NB; ++nb)
+    for (int nb = 0; nb < C::NB; ++nb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) w.oacc[nb][r] *= alpha;
+        __builtin_amdgcn_sched_barrier(0);  // one block at a time: keeps the register demand of this rare path small
+    }
 }
 
 // Steady-state iteration n (blocks n, n+1, n+2 exist):
@@ -307,6 +321,7 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
     const float m_use = w.m_ref == -INFINITY ? 0.f : w.m_ref;
     f32x16 snew;
     bf16x8 pn[2];
+    unsigned pp[8];
     float ex[16];
     float psum = 0.f;
     float t[8];
@@ -345,11 +360,8 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
             // optimiser would otherwise move this work out of the MFMA shadow)
             asm volatile("" : "+v"(ex[r]));
             if (r & 1) {
-                const __bf16 b0 = (__bf16)ex[r - 1], b1 = (__bf16)ex[r];
-                pn[r >> 3][(r & 7) - 1] = b0;
-                pn[r >> 3][r & 7] = b1;
-                psum += (float)b0 + (float)b1;  // the denominator sums the rounded weights the MFMA will use
-                asm volatile("" : "+v"(psum));
+                pp[r >> 1] = pack_pair(ex[r - 1], ex[r], psum);
+                asm volatile("" : "+v"(pp[r >> 1]), "+v"(psum));
             }
         }
 #pragma unroll
@@ -364,12 +376,14 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
         if (j == N - 1) mx = fmaxf(mx, t[7]);
         __builtin_amdgcn_sched_barrier(0);
     }
+    pn[0] = __builtin_bit_cast(bf16x8, (u32x4){pp[0], pp[1], pp[2], pp[3]});
+    pn[1] = __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]});
     if (__any(mx > w.m_ref + kTau)) {
         // rare: the exponentials above used too small a reference; redo them after rescaling
         raise_reference<DZ>(w, mx);
         const float m_new = w.m_ref == -INFINITY ? 0.f : w.m_ref;
         psum = 0.f;
-        exp_range(sacc, m_new, pn, psum, 0, 16);
+        exp_block(sacc, m_new, pn, psum);
     }
     w.l_run += psum;
     pf[0] = pn[0];
@@ -429,22 +443,32 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     dma.kbb = reinterpret_cast<const char *>(p.kbias + (size_t)bh * p.Lp);
     dma.kboff = lane * 16;
 
+    // Key blocks are visited starting at the block that holds the tile's own residues and
+    // wrapping around.  With distance-dominated logits the row maximum sits near the diagonal,
+    // so the reference maximum is found in the first blocks and is rarely raised afterwards.
+    const int first_blk = min(qt * (kTileQ / kBlk), max(nblk - 1, 0));
+    auto key_block = [&](int n) { return first_blk + n < nblk ? first_blk + n : first_blk + n - nblk; };
+
     Wave<DZ> w;
     if (nblk > 0) {
-        issue_block<DZ>(dma, 0, smem);
-        if (1 < nblk) issue_block<DZ>(dma, 1, smem + C::STAGE);
-        if (2 < nblk) issue_block<DZ>(dma, 2, smem + 2 * C::STAGE);
-        if (3 < nblk) issue_block<DZ>(dma, 3, smem + 3 * C::STAGE);
+        issue_block<DZ>(dma, key_block(0), smem);
+        if (1 < nblk) issue_block<DZ>(dma, key_block(1), smem + C::STAGE);
+        if (2 < nblk) issue_block<DZ>(dma, key_block(2), smem + 2 * C::STAGE);
+        if (3 < nblk) issue_block<DZ>(dma, key_block(3), smem + 3 * C::STAGE);
     }
 
     // ---- q^ row fragments: features 16*ks + 8*g .. +7 of row irow ---------------------------
+    // They are loaded straight into accumulation registers (the MFMA reads its B operand from
+    // there), which leaves the architectural registers to the operand ring and the softmax.
+    // The loads are invisible to the compiler's wait-count bookkeeping; the wait_vmem<0>()
+    // below covers them, and the empty asm after it orders every use behind that wait.
     {
         const bf16_t *qh = p.Qh + ((size_t)bh * p.Lp + irow) * kDH;
         const bf16_t *qz = p.Qz + ((size_t)bh * p.Lp + irow) * DZ;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
             const bf16_t *src = ks < C::KSH ? qh + ks * 16 + 8 * g : qz + (ks - C::KSH) * 16 + 8 * g;
-            w.qf[ks] = *reinterpret_cast<const bf16x8 *>(src);
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(w.qf[ks]) : "v"(src) : "memory");
         }
     }
 #pragma unroll
@@ -467,13 +491,15 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     f32x16 sacc;
     bf16x8 fr[C::RING];
     wait_vmem<0>();  // q^ fragments and the first stages; nothing the compiler tracks stays pending
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+a"(w.qf[ks]));
     if (nblk > 0) {
         wg_barrier();
         sacc = s_block<DZ>(w, smem);
         const float mx = row_max16(sacc);
         w.m_ref = mx;
         float psum = 0.f;
-        exp_range(sacc, mx == -INFINITY ? 0.f : mx, pf, psum, 0, 16);
+        exp_block(sacc, mx == -INFINITY ? 0.f : mx, pf, psum);
         w.l_run = psum;
         if (nblk > 1) sacc = s_block<DZ>(w, smem + C::STAGE);
 #pragma unroll
@@ -493,7 +519,7 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         const int s1 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
         const int s2 = s0 + 2 < C::NSTAGE ? s0 + 2 : s0 + 2 - C::NSTAGE;
         const int s4 = s0 + 4 < C::NSTAGE ? s0 + 4 : s0 + 4 - C::NSTAGE;
-        if (n + 4 < nblk) issue_block<DZ>(dma, n + 4, smem + s4 * C::STAGE);
+        if (n + 4 < nblk) issue_block<DZ>(dma, key_block(n + 4), smem + s4 * C::STAGE);
         steady_iteration<DZ>(w, pf, sacc, fr, smem + s0 * C::STAGE, smem + s2 * C::STAGE, smem + s1 * C::STAGE);
         s0 = s1;
     }
@@ -507,7 +533,7 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         const float mx = row_max16(sacc);
         if (__any(mx > w.m_ref + kTau)) raise_reference<DZ>(w, mx);
         float psum = 0.f;
-        exp_range(sacc, w.m_ref == -INFINITY ? 0.f : w.m_ref, pf, psum, 0, 16);
+        exp_block(sacc, w.m_ref == -INFINITY ? 0.f : w.m_ref, pf, psum);
         w.l_run += psum;
         s0 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
     }
