@@ -11,6 +11,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the attention kernels rely on full unrolling of long constant-trip-count loops
+         "-mllvm", "-pragma-unroll-threshold=4000000",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 

@@ -63,8 +63,8 @@ struct AttnCfg {
     static constexpr int Z_OFF = 0;
     static constexpr int KH_OFF = NZ * 1024;
     static constexpr int VH_OFF = (NZ + NH) * 1024;
-    static constexpr int KB_OFF = NI * 1024;             // 32 per-key fp32 biases
-    static constexpr int STAGE = KB_OFF + 256;
+    static constexpr int KB_OFF = NIW * 4 * 1024;        // 32 per-key fp32 biases (a full 1 KiB load lands here)
+    static constexpr int STAGE = KB_OFF + 1024;
     static constexpr int NSTAGE = 5 * STAGE <= 160 * 1024 ? 5 : 4;
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
     static constexpr int NOPS = 2 * KS;      // MFMAs per pipelined iteration (KS == 2*NB)
@@ -73,6 +73,7 @@ struct AttnCfg {
     static constexpr int LA = RING - 1;      // MFMAs between the fetch of an LDS operand and its use
     static_assert(KS > LA && NOPS % RING == 0, "pipeline depth");
     static constexpr int VM_PER_BLOCK = NIW + 1;          // vector-memory ops one wave issues per block
+    static constexpr int DMA_EVERY = NOPS / (NIW + 1);   // one load entry every DMA_EVERY MFMAs
 };
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const char *ptr)
@@ -81,21 +82,28 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const char *ptr)
         bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ptr)));
 }
 
-// 16 bytes per lane, global -> LDS without passing through registers: lane l fetches
-// base + voff and writes lds_wave_base + 16*l.  Written as inline assembly so that the
-// compiler neither counts these loads nor orders LDS reads after them; completion is
-// awaited explicitly with wait_vmem<N>() before the barrier that publishes the stage.
-__device__ __forceinline__ void dma16(const char *base, int voff, const char *lds_wave_base)
+// One entry of the direct global -> LDS loads: 16 bytes per lane, not passing through
+// registers.  Lane l fetches base + voff and writes LDS byte (lds_base + LDS_IMM + 16*l); voff
+// is first advanced by `step` (the distance to the next key block).  Written as inline
+// assembly so that the compiler neither counts these loads nor orders LDS reads after them;
+// completion is awaited explicitly with wait_vmem<N>() before the barrier that publishes the
+// stage.  (The vector add between the write of m0 and the load also covers the wait state the
+// hardware wants between the two.)
+template <int LDS_IMM>
+__device__ __forceinline__ void dma16(const char *base, int &voff, int step, unsigned lds_base)
 {
-    const unsigned lds_addr =
-        (unsigned)(uintptr_t)((__attribute__((address_space(3))) const char *)lds_wave_base);
     asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2"
-        :
-        : "s"(lds_addr), "v"(voff), "s"(base)
-        : "memory", "m0");
+        "s_add_u32 m0, %1, %2\n\t"
+        "v_add_u32 %0, %3, %0\n\t"
+        "global_load_lds_dwordx4 %0, %4"
+        : "+v"(voff)
+        : "s"(lds_base), "n"(LDS_IMM), "s"(step), "s"(base)
+        : "memory", "m0", "scc");
+}
+
+__device__ __forceinline__ unsigned lds_address(const char *ptr)
+{
+    return (unsigned)(uintptr_t)((__attribute__((address_space(3))) const char *)ptr);
 }
 
 // Workgroup barrier without the fence that __syncthreads() adds: the only cross-wave traffic
@@ -191,28 +199,50 @@ __device__ __forceinline__ void exp_block(const f32x16 &sacc, float m_use, bf16x
     pf[1] = __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]});
 }
 
-// Source side of the direct global->LDS loads of one wave.
+// The direct global->LDS loads of one wave.  A wave-wide load writes 64 consecutive 16-byte
+// slots of a stage; the slot decides which (row, 16-byte column) of the global block the lane
+// fetches.  Slots in the row padding or past the last row fetch element 0 of the block again
+// (harmless).  Wave w issues entries w, w+4, ... of the flat list z2 | k^ head | v^ head; surplus
+// entries repeat entry 0 so that every wave issues the same number of loads per block.  The
+// per-lane offsets run ahead by one block per call, so the blocks must be requested in the
+// order in which they are stored (wrap-arounds are handled by moving the bases).
 template <int DZ>
 struct Dma {
     using C = AttnCfg<DZ>;
-    const char *src[C::NIW];  // wave-uniform: start of the tensor the entry reads (block 0)
-    int stride[C::NIW];       // wave-uniform: bytes from one key block to the next
-    int ldsoff[C::NIW];       // wave-uniform: byte offset of the entry's 1 KiB inside a stage
-    int doff[C::NIW];         // per lane: byte offset inside the global block
-    const char *kbb;
-    int kboff;
-    int lane;
+    const char *src[C::NIW + 1];  // wave-uniform: tensor the entry reads (the last entry is the bias)
+    int step[C::NIW + 1];         // wave-uniform: bytes from one key block to the next
+    int voff[C::NIW + 1];         // per lane: byte offset of the PREVIOUSLY requested block
+    unsigned wave_lds;            // wave-uniform: 1024 * wave
 };
 
-// Enqueue the loads of key block n into the stage at `st` (C::VM_PER_BLOCK vector-memory ops).
+// Entry k of the loads of the next key block, into the stage whose LDS address is `stage`.
+template <int DZ, int K>
+__device__ __forceinline__ void dma_entry(Dma<DZ> &d, unsigned stage)
+{
+    using C = AttnCfg<DZ>;
+    if constexpr (K < C::NIW)
+        dma16<4096 * K>(d.src[K], d.voff[K], d.step[K], stage + d.wave_lds);
+    else
+        dma16<C::KB_OFF>(d.src[K], d.voff[K], d.step[K], stage);
+}
+
+template <int DZ, int K = 0>
+__device__ __forceinline__ void issue_block(Dma<DZ> &d, unsigned stage)
+{
+    using C = AttnCfg<DZ>;
+    if constexpr (K <= C::NIW) {
+        dma_entry<DZ, K>(d, stage);
+        issue_block<DZ, K + 1>(d, stage);
+    }
+}
+
+// After the block with the highest index has been requested the sequence continues at block 0.
 template <int DZ>
-__device__ __forceinline__ void issue_block(const Dma<DZ> &d, int n, char *st)
+__device__ __forceinline__ void dma_wrap(Dma<DZ> &d, int nblk)
 {
     using C = AttnCfg<DZ>;
 #pragma unroll
-    for (int k = 0; k < C::NIW; ++k)
-        dma16(d.src[k] + (size_t)n * d.stride[k], d.doff[k], st + d.ldsoff[k]);
-    if (d.lane < 8) dma16(d.kbb + (size_t)n * kBlk * 4, d.kboff, st + C::KB_OFF);  // 32 floats
+    for (int k = 0; k <= C::NIW; ++k) d.src[k] -= (size_t)nblk * d.step[k];
 }
 
 // ---- the hand-ordered MFMA sequence of one pipelined iteration -------------------------------
@@ -303,6 +333,19 @@ __device__ __forceinline__ void raise_reference(Wave<DZ> &w, float mx)
     }
 }
 
+// Load entry (j / DMA_EVERY) is issued right after MFMA j when j is a multiple of DMA_EVERY.
+template <int DZ, int K = 0>
+__device__ __forceinline__ void dma_slot(Dma<DZ> &d, unsigned stage, int j)
+{
+    using C = AttnCfg<DZ>;
+    if constexpr (K <= C::NIW) {
+        if (j == K * C::DMA_EVERY)
+            dma_entry<DZ, K>(d, stage);
+        else
+            dma_slot<DZ, K + 1>(d, stage, j);
+    }
+}
+
 // Steady-state iteration n (blocks n, n+1, n+2 exist):
 //   O^T += V^T P^T of block n (stage st_pv, probabilities pf),
 //   exponentials of block n+1 from its S^T accumulator `sacc` -> pf (for the next iteration),
@@ -311,7 +354,8 @@ __device__ __forceinline__ void raise_reference(Wave<DZ> &w, float mx)
 // `fr` is the operand ring; on entry it holds the operands of operations 0 .. LA-1.
 template <int DZ>
 __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f32x16 &sacc, bf16x8 (&fr)[AttnCfg<DZ>::RING],
-                                                 const char *st_pv, const char *st_s, const char *st_pv_next)
+                                                 const char *st_pv, const char *st_s, const char *st_pv_next,
+                                                 Dma<DZ> &dma, unsigned st_dma)
 {
     using C = AttnCfg<DZ>;
     using O = Ops<DZ>;
@@ -330,8 +374,6 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
     for (int j = 0; j < N; ++j) {
         // operand fetch for operation j + kLookahead (wrapping into the next iteration)
         {
-            constexpr int dummy = 0;
-            (void)dummy;
             const int jn = j + kLookahead;
             if (jn < N) {
                 if (O::is_pv(jn))
@@ -343,6 +385,8 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
             }
         }
         if (j == kLookahead - 1) snew = load_bias<DZ>(w, st_s);  // before the first S^T MFMA
+        // one entry of the loads of the block four ahead, every few MFMAs
+        dma_slot<DZ>(dma, st_dma, j);
         // the MFMA
         if (O::is_pv(j)) {
             const int i = O::idx(j);
@@ -417,8 +461,13 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // past the last row fetch element 0 of the block again (harmless).  Wave w issues entries
     // w, w+4, ... of the flat list z2 | k^ head | v^ head; surplus entries repeat entry 0 so that
     // every wave issues the same number of loads per block.
+    // Key blocks are visited starting at the block that holds the tile's own residues and
+    // wrapping around.  With distance-dominated logits the row maximum sits near the diagonal,
+    // so the reference maximum is found in the first blocks and is rarely raised afterwards.
+    const int first_blk = min(qt * (kTileQ / kBlk), max(nblk - 1, 0));
+
     Dma<DZ> dma;
-    dma.lane = lane;
+    dma.wave_lds = 1024u * wave;
     {
         const char *Z2b = reinterpret_cast<const char *>(p.Z2 + (size_t)b * p.Lp * DZ);
         const char *Khb = reinterpret_cast<const char *>(p.Kh + (size_t)bh * p.Lp * kDH);
@@ -434,27 +483,34 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             const int cols = isz ? DZ / 8 : kDH / 8;          // 16-byte columns of a global row
             const int s = 64 * (i - first) + lane;
             const int row = s / spr, col = s - row * spr;
-            dma.doff[k] = (row < kBlk && col < cols) ? row * (cols * 16) + col * 16 : 0;
+            dma.step[k] = kBlk * cols * 16;
             dma.src[k] = isz ? Z2b : (isk ? Khb : Vhb);
-            dma.stride[k] = kBlk * cols * 16;
-            dma.ldsoff[k] = i * 1024;
+            // one block before the first block: every request advances the offset first
+            dma.voff[k] = ((row < kBlk && col < cols) ? row * (cols * 16) + col * 16 : 0) + (first_blk - 1) * dma.step[k];
+            // (entry wave + 4k lands (wave + 4k) KiB into the stage; a surplus entry refetches
+            // entry 0 into the unused KiB that the stage keeps for it)
         }
+        dma.step[C::NIW] = kBlk * 4;
+        dma.src[C::NIW] = reinterpret_cast<const char *>(p.kbias + (size_t)bh * p.Lp);
+        dma.voff[C::NIW] = min(lane, 7) * 16 + (first_blk - 1) * dma.step[C::NIW];
     }
-    dma.kbb = reinterpret_cast<const char *>(p.kbias + (size_t)bh * p.Lp);
-    dma.kboff = lane * 16;
 
-    // Key blocks are visited starting at the block that holds the tile's own residues and
-    // wrapping around.  With distance-dominated logits the row maximum sits near the diagonal,
-    // so the reference maximum is found in the first blocks and is rarely raised afterwards.
-    const int first_blk = min(qt * (kTileQ / kBlk), max(nblk - 1, 0));
-    auto key_block = [&](int n) { return first_blk + n < nblk ? first_blk + n : first_blk + n - nblk; };
+    const unsigned smem_lds = lds_address(smem);
+    int next_blk = first_blk;  // next key block to request
 
     Wave<DZ> w;
     if (nblk > 0) {
-        issue_block<DZ>(dma, key_block(0), smem);
-        if (1 < nblk) issue_block<DZ>(dma, key_block(1), smem + C::STAGE);
-        if (2 < nblk) issue_block<DZ>(dma, key_block(2), smem + 2 * C::STAGE);
-        if (3 < nblk) issue_block<DZ>(dma, key_block(3), smem + 3 * C::STAGE);
+        // the first four blocks of the sequence (beyond the end of a short sequence the
+        // requests simply go round again: every stage they touch is free)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (next_blk == nblk) {
+                dma_wrap<DZ>(dma, nblk);
+                next_blk = 0;
+            }
+            issue_block<DZ>(dma, smem_lds + i * C::STAGE);
+            ++next_blk;
+        }
     }
 
     // ---- q^ row fragments: features 16*ks + 8*g .. +7 of row irow ---------------------------
@@ -509,20 +565,23 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // ---- steady state: iteration n works on blocks n (P V), n+1 (exp), n+2 (S^T) ---------------
     int s0 = 0;  // stage of block n
     for (int n = 0; n + 2 < nblk; ++n) {
-        // Block n+2 must have landed (block n+3 may still be in flight); the barrier also tells
-        // everyone that the stage of block n-1 is free again.
-        if (n >= 1 && n + 3 < nblk)
-            wait_vmem<C::VM_PER_BLOCK>();
-        else
-            wait_vmem<0>();
+        // Block n+2 must have landed (the requests of the previous iteration may still be in
+        // flight); the barrier also tells everyone that the stage of block n-1 is free again.
+        wait_vmem<C::VM_PER_BLOCK>();
         wg_barrier();
         const int s1 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
         const int s2 = s0 + 2 < C::NSTAGE ? s0 + 2 : s0 + 2 - C::NSTAGE;
         const int s4 = s0 + 4 < C::NSTAGE ? s0 + 4 : s0 + 4 - C::NSTAGE;
-        if (n + 4 < nblk) issue_block<DZ>(dma, key_block(n + 4), smem + s4 * C::STAGE);
-        steady_iteration<DZ>(w, pf, sacc, fr, smem + s0 * C::STAGE, smem + s2 * C::STAGE, smem + s1 * C::STAGE);
+        if (next_blk == nblk) {
+            dma_wrap<DZ>(dma, nblk);
+            next_blk = 0;
+        }
+        ++next_blk;
+        steady_iteration<DZ>(w, pf, sacc, fr, smem + s0 * C::STAGE, smem + s2 * C::STAGE, smem + s1 * C::STAGE,
+                             dma, smem_lds + s4 * C::STAGE);
         s0 = s1;
     }
+    wait_vmem<0>();  // requests past the end of the sequence went to free stages; let them finish
 
     // ---- drain: the last two blocks -----------------------------------------------------------------
     if (nblk > 1) {
