@@ -22,9 +22,10 @@
 // their LDS operands fetched a few MFMAs ahead and the VALU work of the softmax cut into
 // slices placed between them, so that it runs in the shadow of the matrix pipe.
 //
-// The running maximum is only raised when a new logit exceeds it by more than kTau (in log2
-// units); until then the accumulator is not rescaled.  The result is the same softmax:
-// numerator and denominator carry the same factor 2^(m_true - m_ref) <= 2^kTau.
+// The softmax reference ("running maximum" m of Algorithm 2) is only raised when the weights of
+// a block, taken against the current reference, sum to more than 2^kTau; until then nothing is
+// rescaled.  The result is the same softmax: numerator and denominator carry the same factor
+// 2^(m_true - m_ref), and fp32 / bf16 keep their relative precision over that range.
 #include "fipa_bf16_common.h"
 
 namespace fipa {
@@ -40,7 +41,8 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-constexpr float kTau = 8.0f;
+constexpr float kTau = 32.0f;
+constexpr float kTauPow = 4294967296.0f;  // 2^kTau
 constexpr int kBlk = 32;           // keys per LDS stage
 constexpr int kHS = kDH * 2 + 16;  // LDS row stride (bytes) of the head-specific k^ / v^ blocks
 
@@ -69,8 +71,8 @@ struct AttnCfg {
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
     static constexpr int NOPS = 2 * KS;      // MFMAs per pipelined iteration (KS == 2*NB)
     static_assert(KS == 2 * NB, "S^T and P V use the same number of MFMAs per block");
-    static constexpr int RING = NOPS % 5 == 0 ? 5 : (NOPS % 6 == 0 ? 6 : 8);  // operand buffers; divides NOPS
-    static constexpr int LA = RING - 1;      // MFMAs between the fetch of an LDS operand and its use
+    static constexpr int LA = NOPS % 8 == 0 ? 4 : 2;  // LDS operands are fetched in groups of LA MFMAs, one group ahead
+    static constexpr int RING = 2 * LA;      // operand buffers
     static_assert(KS > LA && NOPS % RING == 0, "pipeline depth");
     static constexpr int VM_PER_BLOCK = NIW + 1;          // vector-memory ops one wave issues per block
     static constexpr int DMA_EVERY = NOPS / (NIW + 1);   // one load entry every DMA_EVERY MFMAs
@@ -368,20 +370,23 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
     unsigned pp[8];
     float ex[16];
     float psum = 0.f;
-    float t[8];
-    float mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-        // operand fetch for operation j + kLookahead (wrapping into the next iteration)
-        {
-            const int jn = j + kLookahead;
-            if (jn < N) {
-                if (O::is_pv(jn))
-                    fr[jn % kRing] = load_pv<DZ>(w, st_pv, O::idx(jn));
-                else
-                    fr[jn % kRing] = load_s<DZ>(w, st_s, O::idx(jn));
-            } else {
-                fr[jn % kRing] = load_pv<DZ>(w, st_pv_next, O::idx(jn - N));
+        // operand fetch, one group of LA operations ahead (wrapping into the next iteration).
+        // Within a group the operands are requested in reverse order of use: LDS returns data
+        // in order, so the single wait before the group's first MFMA covers the whole group.
+        if (j % kLookahead == 0) {
+#pragma unroll
+            for (int u = kLookahead - 1; u >= 0; --u) {
+                const int jn = j + kLookahead + u;
+                if (jn < N) {
+                    if (O::is_pv(jn))
+                        fr[jn % kRing] = load_pv<DZ>(w, st_pv, O::idx(jn));
+                    else
+                        fr[jn % kRing] = load_s<DZ>(w, st_s, O::idx(jn));
+                } else {
+                    fr[jn % kRing] = load_pv<DZ>(w, st_pv_next, O::idx(jn - N));
+                }
             }
         }
         if (j == kLookahead - 1) snew = load_bias<DZ>(w, st_s);  // before the first S^T MFMA
@@ -395,7 +400,7 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
             snew = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], w.qf[O::idx(j)], snew, 0, 0, 0);
         }
         // softmax slices of block n+1, spread evenly over the operations: the 16 exponentials
-        // (pairs are rounded to bf16 together) and the row maximum for the check below
+        // (pairs are rounded to bf16 together)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             if ((r * N) / 16 != j) continue;
@@ -408,23 +413,15 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
                 asm volatile("" : "+v"(pp[r >> 1]), "+v"(psum));
             }
         }
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            if (((2 * k + 1) * N) / 24 != j) continue;
-            if (k < 5) t[k] = fmaxf(fmaxf(sacc[3 * k], sacc[3 * k + 1]), sacc[3 * k + 2]);
-            if (k == 5) t[5] = fmaxf(fmaxf(t[0], t[1]), sacc[15]);
-            if (k == 6) t[6] = fmaxf(fmaxf(t[2], t[3]), t[4]);
-            if (k == 7) t[7] = fmaxf(t[5], t[6]);
-        }
-        if (j == N - 4) mx = __shfl_xor(t[7], 32);
-        if (j == N - 1) mx = fmaxf(mx, t[7]);
         __builtin_amdgcn_sched_barrier(0);
     }
     pn[0] = __builtin_bit_cast(bf16x8, (u32x4){pp[0], pp[1], pp[2], pp[3]});
     pn[1] = __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]});
-    if (__any(mx > w.m_ref + kTau)) {
-        // rare: the exponentials above used too small a reference; redo them after rescaling
-        raise_reference<DZ>(w, mx);
+    // psum <= 2^kTau bounds every weight of the block; a larger (or infinite) sum means the
+    // reference is too small for this block
+    if (__any(!(psum <= kTauPow) || w.m_ref == -INFINITY)) {  // (no reference yet: take the block's maximum)
+        // rare: redo the exponentials after raising the reference to the block's true maximum
+        raise_reference<DZ>(w, row_max16(sacc));
         const float m_new = w.m_ref == -INFINITY ? 0.f : w.m_ref;
         psum = 0.f;
         exp_block(sacc, m_new, pn, psum);
