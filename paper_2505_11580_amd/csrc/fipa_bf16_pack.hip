@@ -104,57 +104,168 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_bf16_kernel(PackParams p)
     }
 }
 
-// One workgroup per (batch, 64-residue tile): copies z2 (zeroing masked residues) and forms
-// the query-side factor bias vectors b^{h1} = log2e * w_L * w_b[h] (.) z1 for every head
-// (Algorithm 1 steps 2-3; Eq. 3 puts w_L on the bias, the log2e turns exp into exp2).
-__global__ __launch_bounds__(256) void fipa_pack_pair_bf16_kernel(PackParams p)
+// z2 copy (zeroing masked and padded residues): one thread per 8 consecutive features.
+__global__ __launch_bounds__(256) void fipa_pack_z2_bf16_kernel(PackParams p)
 {
-    const int tile = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const int DZ = p.DZ;
-    const int chunks_per_row = DZ / 8;
-    for (int idx = tid; idx < kTileK * chunks_per_row; idx += 256) {
-        const int r_ = idx / chunks_per_row, cc = idx - r_ * chunks_per_row;
-        const int i = tile * kTileK + r_;
-        const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
-        uint4 val = make_uint4(0, 0, 0, 0);
-        if (ok) val = *reinterpret_cast<const uint4 *>(p.z2 + ((size_t)b * p.L + i) * DZ + cc * 8);
-        *reinterpret_cast<uint4 *>(p.Z2 + ((size_t)b * p.Lp + i) * DZ + cc * 8) = val;
+    const int cpr = p.DZ / 8;  // 16-byte chunks per row
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)p.B * p.Lp * cpr) return;
+    const int cc = (int)(idx % cpr);
+    const size_t bi = idx / cpr;
+    const int i = (int)(bi % p.Lp), b = (int)(bi / p.Lp);
+    const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (ok) val = *reinterpret_cast<const uint4 *>(p.z2 + ((size_t)b * p.L + i) * p.DZ + cc * 8);
+    *reinterpret_cast<uint4 *>(p.Z2 + ((size_t)b * p.Lp + i) * p.DZ + cc * 8) = val;
+}
+
+// Query-side factor bias vectors b^{h1} = log2e * w_L * w_b[h] (.) z1 for every head (Algorithm 1
+// steps 2-3; Eq. 3 puts w_L on the bias, the log2e turns exp into exp2): one thread per
+// (batch, head, residue, 8 consecutive features).
+__global__ __launch_bounds__(256) void fipa_pack_qz_bf16_kernel(PackParams p)
+{
+    const int cpr = p.DZ / 8;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)p.B * p.H * p.Lp * cpr) return;
+    const int cc = (int)(idx % cpr);
+    size_t rest = idx / cpr;
+    const int i = (int)(rest % p.Lp);
+    rest /= p.Lp;
+    const int h = (int)(rest % p.H), b = (int)(rest / p.H);
+    const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    __attribute__((aligned(16))) bf16_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (ok) {
+        const float bscale = kLog2e * p.w_L;
+        const uint4 val = *reinterpret_cast<const uint4 *>(p.z1 + ((size_t)b * p.L + i) * p.DZ + cc * 8);
+        const bf16_t *e = reinterpret_cast<const bf16_t *>(&val);
+        const int col0 = (cc * 8) % p.cz;  // cz is a multiple of 8: the chunk stays inside one factor slice
+        const float *wb = p.w_b + (size_t)h * p.cz + col0;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) out[x] = f2bf(bscale * wb[x] * bf2f(e[x]));
     }
-    // Qz[b][h][i][x]
-    const float bscale = kLog2e * p.w_L;
-    for (int idx = tid; idx < p.H * kTileK * chunks_per_row; idx += 256) {
-        const int cc = idx % chunks_per_row;
-        const int rest = idx / chunks_per_row;
-        const int r_ = rest % kTileK, h = rest / kTileK;
-        const int i = tile * kTileK + r_;
-        const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
-        __attribute__((aligned(16))) bf16_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (ok) {
-            const uint4 val = *reinterpret_cast<const uint4 *>(p.z1 + ((size_t)b * p.L + i) * DZ + cc * 8);
-            const bf16_t *e = reinterpret_cast<const bf16_t *>(&val);
-            for (int x = 0; x < 8; ++x) {
-                const int col = (cc * 8 + x) % p.cz;
-                out[x] = f2bf(bscale * p.w_b[(size_t)h * p.cz + col] * bf2f(e[x]));
+    *reinterpret_cast<uint4 *>(p.Qz + (((size_t)b * p.H + h) * p.Lp + i) * p.DZ + cc * 8) =
+        *reinterpret_cast<const uint4 *>(out);
+}
+
+// Head-specific columns for the AlphaFold2-style head shape (c = 16, N_query = 4, N_value = 8):
+// one thread per (batch, residue, head) and per role (blockIdx.y: 0 = q^, 1 = k^, 2 = v^),
+// rows assembled in registers.  Consecutive threads read consecutive (residue, head) records.
+template <int ROLE>
+__device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i, int h)
+{
+    constexpr int c = 16, Pq = 4, Pv = 8;
+    const size_t bh = (size_t)b * p.H + h;
+    const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    __attribute__((aligned(16))) bf16_t row[kDH];
+#pragma unroll
+    for (int x = 0; x < kDH; ++x) row[x] = 0;
+    float bias = ROLE == 1 ? -INFINITY : 0.f;
+    if (ok) {
+        const float *R = p.rot + ((size_t)b * p.L + i) * 9;
+        const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+        float Rm[9], tc[3];
+#pragma unroll
+        for (int a = 0; a < 9; ++a) Rm[a] = R[a];
+#pragma unroll
+        for (int a = 0; a < 3; ++a) tc[a] = t[a] - p.cen[4 * b + a];
+        const size_t rec = ((size_t)b * p.L + i) * p.H + h;
+        const float pscale = p.gamma[h] * p.w_L * p.w_C;  // weight of Q.K in the expanded distance
+        const bf16_t *sc_src = ROLE == 0 ? p.q : (ROLE == 1 ? p.k : p.v);
+        __attribute__((aligned(16))) bf16_t sc[c];
+        *reinterpret_cast<uint4 *>(sc) = *reinterpret_cast<const uint4 *>(sc_src + rec * c);
+        *reinterpret_cast<uint4 *>(sc + 8) = *reinterpret_cast<const uint4 *>(sc_src + rec * c + 8);
+        if (ROLE == 1) {
+            const float sscale = kLog2e * p.w_L * p.qk_scale;
+#pragma unroll
+            for (int x = 0; x < c; ++x) row[x] = f2bf(sscale * bf2f(sc[x]));
+        } else {
+#pragma unroll
+            for (int x = 0; x < c; ++x) row[x] = sc[x];
+        }
+        constexpr int P = ROLE == 2 ? Pv : Pq;
+        const bf16_t *pt_src = (ROLE == 0 ? p.q_pts : (ROLE == 1 ? p.k_pts : p.v_pts)) + rec * P * 3;
+        __attribute__((aligned(8))) bf16_t pts[P * 3];
+#pragma unroll
+        for (int x = 0; x < P * 3 / 4; ++x)
+            *reinterpret_cast<uint2 *>(pts + 4 * x) = *reinterpret_cast<const uint2 *>(pt_src + 4 * x);
+        const float kscale = kLog2e * pscale;
+        float sq = 0.f;
+#pragma unroll
+        for (int pp = 0; pp < P; ++pp) {
+            const float lx = bf2f(pts[3 * pp]), ly = bf2f(pts[3 * pp + 1]), lz = bf2f(pts[3 * pp + 2]);
+#pragma unroll
+            for (int a = 0; a < 3; ++a) {
+                float G = Rm[3 * a] * lx + Rm[3 * a + 1] * ly + Rm[3 * a + 2] * lz + tc[a];
+                if (ROLE == 1) G *= kscale;
+                const bf16_t hi = f2bf(G), lo = f2bf(G - bf2f(hi));
+                const float eff = bf2f(hi) + bf2f(lo);
+                sq += eff * eff;
+                const int cc = 3 * pp + a;
+                if (ROLE == 0) {
+                    row[c + cc] = hi;
+                    row[c + 3 * Pq + cc] = hi;
+                    row[c + 6 * Pq + cc] = lo;
+                    row[c + 9 * Pq + cc] = lo;
+                } else if (ROLE == 1) {
+                    row[c + cc] = hi;
+                    row[c + 3 * Pq + cc] = lo;
+                    row[c + 6 * Pq + cc] = hi;
+                    row[c + 9 * Pq + cc] = lo;
+                } else {
+                    row[v_pt_col(c, Pv, pp, a, 0)] = hi;
+                    row[v_pt_col(c, Pv, pp, a, 1)] = lo;
+                }
             }
         }
-        *reinterpret_cast<uint4 *>(p.Qz + (((size_t)b * p.H + h) * p.Lp + i) * DZ + cc * 8) =
-            *reinterpret_cast<const uint4 *>(out);
+        if (ROLE == 0) bias = 0.5f * pscale * sq;
+        if (ROLE == 1) bias = kscale != 0.f ? -sq / (2.f * kscale) : 0.f;
     }
+    bf16_t *dst = (ROLE == 0 ? p.Qh : (ROLE == 1 ? p.Kh : p.Vh)) + (bh * p.Lp + i) * kDH;
+#pragma unroll
+    for (int x = 0; x < kDH / 8; ++x)
+        reinterpret_cast<uint4 *>(dst)[x] = reinterpret_cast<const uint4 *>(row)[x];
+    if (ROLE == 0) p.qbias[bh * p.Lp + i] = bias;
+    if (ROLE == 1) p.kbias[bh * p.Lp + i] = bias;
+}
+
+__global__ __launch_bounds__(256) void fipa_pack_heads_af2_bf16_kernel(PackParams p)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, i, h), h fastest
+    if (idx >= (size_t)p.B * p.Lp * p.H) return;
+    const int h = (int)(idx % p.H);
+    const size_t bi = idx / p.H;
+    const int i = (int)(bi % p.Lp), b = (int)(bi / p.Lp);
+    if (blockIdx.y == 0)
+        pack_head_row<0>(p, b, i, h);
+    else if (blockIdx.y == 1)
+        pack_head_row<1>(p, b, i, h);
+    else
+        pack_head_row<2>(p, b, i, h);
 }
 
 }  // namespace
 
 hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream)
 {
-    const size_t lds_heads = (size_t)4 * 3 * 64 * kRowStride * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute((const void *)fipa_pack_heads_bf16_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_heads);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fipa_pack_heads_bf16_kernel, dim3(p.NT, (p.H + 3) / 4, p.B), dim3(256),
-                       lds_heads, stream, p);
+    hipError_t e;
+    if (p.c == 16 && p.Pq == 4 && p.Pv == 8) {
+        const unsigned nb = (unsigned)(((size_t)p.B * p.Lp * p.H + 255) / 256);
+        hipLaunchKernelGGL(fipa_pack_heads_af2_bf16_kernel, dim3(nb, 3), dim3(256), 0, stream, p);
+    } else {
+        const size_t lds_heads = (size_t)4 * 3 * 64 * kRowStride * sizeof(bf16_t);
+        e = hipFuncSetAttribute((const void *)fipa_pack_heads_bf16_kernel,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_heads);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(fipa_pack_heads_bf16_kernel, dim3(p.NT, (p.H + 3) / 4, p.B), dim3(256),
+                           lds_heads, stream, p);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fipa_pack_pair_bf16_kernel, dim3(p.NT, p.B), dim3(256), 0, stream, p);
+    const size_t cpr = p.DZ / 8;
+    hipLaunchKernelGGL(fipa_pack_z2_bf16_kernel, dim3((unsigned)(((size_t)p.B * p.Lp * cpr + 255) / 256)),
+                       dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(fipa_pack_qz_bf16_kernel,
+                       dim3((unsigned)(((size_t)p.B * p.H * p.Lp * cpr + 255) / 256)), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
