@@ -171,3 +171,29 @@ def forward(desc, dev, out):
     fipa_forward(desc, dev["q"], dev["k"], dev["v"], dev["q_pts"], dev["k_pts"], dev["v_pts"],
                  dev["rot"], dev["trans"], dev["z1"], dev["z2"], dev["w_b"], dev["gamma"], dev["mask"],
                  out["o"], out["o_pts"], out["o_pair"], out["lse"], out["workspace"])
+
+
+def alloc_grads(desc, device="cuda:0"):
+    """Gradient tensors (dtype of the inputs) and the backward workspace."""
+    import torch
+    B, L, H = desc.B, desc.L, desc.H
+    dt = torch.bfloat16 if desc.dtype == FIPA_DTYPE_BF16 else torch.float32
+    f = dict(dtype=dt, device=device)
+    _, bwd = workspace_bytes(desc)
+    return dict(d_q=torch.empty(B, L, H, desc.c, **f), d_k=torch.empty(B, L, H, desc.c, **f),
+                d_v=torch.empty(B, L, H, desc.c, **f),
+                d_q_pts=torch.empty(B, L, H, desc.Pq, 3, **f), d_k_pts=torch.empty(B, L, H, desc.Pq, 3, **f),
+                d_v_pts=torch.empty(B, L, H, desc.Pv, 3, **f),
+                d_z1=torch.empty(B, L, desc.r, desc.cz, **f), d_z2=torch.empty(B, L, desc.r, desc.cz, **f),
+                d_gamma=torch.empty(H, dtype=torch.float32, device=device),
+                workspace=torch.empty(max(bwd, 16), dtype=torch.uint8, device=device))
+
+
+def backward(desc, dev, out, grads):
+    """dev must hold d_o, d_o_pts, d_o_pair; out the forward results of the same inputs."""
+    fipa_backward(desc, dev["q"], dev["k"], dev["v"], dev["q_pts"], dev["k_pts"], dev["v_pts"],
+                  dev["rot"], dev["trans"], dev["z1"], dev["z2"], dev["w_b"], dev["gamma"], dev["mask"],
+                  out["o"], out["o_pts"], out["o_pair"], out["lse"],
+                  dev["d_o"], dev["d_o_pts"], dev["d_o_pair"],
+                  grads["d_q"], grads["d_k"], grads["d_v"], grads["d_q_pts"], grads["d_k_pts"],
+                  grads["d_v_pts"], grads["d_z1"], grads["d_z2"], grads["d_gamma"], grads["workspace"])

@@ -30,7 +30,6 @@ int check_desc(const fipa_desc *d, bool backward)
             return FIPA_ERR_UNSUPPORTED;
         if (DZ != 32 && DZ != 64 && DZ != 128 && DZ != 256 && DZ != 512) return FIPA_ERR_UNSUPPORTED;
         if (DZ == 512) return FIPA_ERR_UNSUPPORTED;  // not built yet
-        if (backward) return FIPA_ERR_UNSUPPORTED;   // not built yet
     }
     return FIPA_OK;
 }

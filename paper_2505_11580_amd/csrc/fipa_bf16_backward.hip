@@ -1,0 +1,326 @@
+// Backward of the bf16 path: host orchestration and the memory-bound kernels around the MFMA
+// kernels (lifting of the upstream gradients; chain rule through the packing back to the
+// inputs).  The paper gives no backward; formulas follow from Eqs. 3-4 and z_ij = z1_i^T z2_j.
+//
+// Chain: forward pack -> forward attention (unfused, gives O^ and the log-sum-exp) -> lift the
+// upstream gradients (dO^ = [d_o | R_i d_o_pts in the hi and lo columns | z1 (.) d_o_pair],
+// D_i = dO^_i . O^_i) -> dQ^, dK^, dV^ (MFMA kernels) -> unpack.
+#include "fipa_bf16_common.h"
+
+namespace fipa {
+
+namespace {
+
+// One wave per (batch, head, residue < Lp): lifted upstream gradient row, D_i, and -lse.
+__global__ __launch_bounds__(256) void fipa_bwd_pack_bf16_kernel(BwdPackParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t row_id = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // over B*H*Lp, i fastest
+    if (row_id >= (size_t)p.B * p.H * p.Lp) return;
+    const int i = (int)(row_id % p.Lp);
+    const size_t bh = row_id / p.Lp;
+    const int h = (int)(bh % p.H), b = (int)(bh / p.H);
+    const int c = p.c, D = kDH + p.DZ, PH = (p.Pv + 1) / 2;
+    const bool valid = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    const size_t rec = valid ? ((size_t)b * p.L + i) * p.H + h : 0;
+    const float *R = p.rot + (valid ? ((size_t)b * p.L + i) * 9 : 0);
+    const float *oh = p.Ohat + row_id * D;
+    bf16_t *dst = p.dOhat + row_id * D;
+    float dsum = 0.f;
+    for (int col = lane; col < D; col += 64) {
+        float val = 0.f;
+        if (valid) {
+            if (col < c) {
+                val = p.d_o[rec * c + col];
+            } else if (col < kDH) {
+                // inverse of v_pt_col: which (point, axis) lives in this column, if any
+                const int cp = col - c, within = cp & 7;
+                const int gh = within >> 2, u = 4 * (cp >> 3) + (within & 3);
+                const int lo = u / (3 * PH), u2 = u - lo * 3 * PH;
+                const int pt = gh * PH + u2 / 3, ax = u2 % 3;
+                if (lo < 2 && pt < p.Pv) {
+                    const float *g = p.d_o_pts + (rec * p.Pv + pt) * 3;
+                    val = R[3 * ax] * g[0] + R[3 * ax + 1] * g[1] + R[3 * ax + 2] * g[2];  // dG = R_i d_o_pts
+                }
+            } else {
+                const int x = col - kDH;
+                val = bf2f(p.z1[((size_t)b * p.L + i) * p.DZ + x]) * p.d_o_pair[rec * p.cz + x % p.cz];
+            }
+        }
+        const bf16_t bv = f2bf(val);
+        dst[col] = bv;
+        dsum += bf2f(bv) * (valid ? oh[col] : 0.f);  // D uses the rounded gradient the MFMAs will see
+    }
+    for (int off = 32; off > 0; off >>= 1) dsum += __shfl_xor(dsum, off);
+    if (lane == 0) {
+        const float l2 = p.lse2[row_id];
+        p.Dvec[row_id] = dsum;
+        p.nlse[row_id] = (valid && l2 > -INFINITY && l2 < INFINITY) ? -l2 : -INFINITY;
+    }
+}
+
+// One workgroup per (batch, residue): chain rule from dQ^, dK^, dV^ back to the inputs.
+__global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackParams p)
+{
+    __shared__ float gsm[256];
+    const int b = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
+    const int c = p.c, Pq = p.Pq, Pv = p.Pv, nq = 3 * Pq, D = kDH + p.DZ;
+    const int NTASK = 2 * Pq + Pv + 3;
+    const bool valid = p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true;
+    const float *R = p.rot + ((size_t)b * p.L + i) * 9;
+    const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+    float Rm[9], tc[3];
+    for (int a = 0; a < 9; ++a) Rm[a] = R[a];
+    for (int a = 0; a < 3; ++a) tc[a] = t[a] - p.cen[4 * b + a];
+
+    const int HP = 256 / NTASK;  // heads per pass: the tasks of one head stay inside one pass
+    for (int h0 = 0; h0 < p.H; h0 += HP) {
+        float gpartial = 0.f;
+        const int hl = tid / NTASK;
+        const bool active = hl < HP && h0 + hl < p.H;
+        const int h = active ? h0 + hl : 0, tk = active ? tid - hl * NTASK : 0;
+        if (active) {
+            const size_t bh = (size_t)b * p.H + h;
+            const size_t rec = ((size_t)b * p.L + i) * p.H + h;
+            const float *dQ = p.dQhat + (bh * p.Lp + i) * D;
+            const float *dK = p.dKhat + (bh * p.Lp + i) * D;
+            const float *dV = p.dVhat + (bh * p.Lp + i) * D;
+            const float pscale = p.gamma[h] * p.w_L * p.w_C;
+            const float kscale = kLog2e * pscale;
+            if (tk < 2 * Pq) {
+                const bool isq = tk < Pq;
+                const int pt = isq ? tk : tk - Pq;
+                const bf16_t *src = (isq ? p.q_pts : p.k_pts) + (rec * Pq + pt) * 3;
+                const float lx = bf2f(src[0]), ly = bf2f(src[1]), lz = bf2f(src[2]);
+                float grad[3], eff[3];
+                float gacc = 0.f;
+                for (int a = 0; a < 3; ++a) {
+                    const float G0 = Rm[3 * a] * lx + Rm[3 * a + 1] * ly + Rm[3 * a + 2] * lz + tc[a];
+                    const int cc = 3 * pt + a;
+                    if (isq) {
+                        // the effective (hi + lo) global query coordinate the kernels used
+                        const bf16_t hi = f2bf(G0), lo = f2bf(G0 - bf2f(hi));
+                        eff[a] = bf2f(hi) + bf2f(lo);
+                        const float rs = p.rowsum[bh * p.Lp + i];
+                        // d s / dQ = gamma w_L w_C (K - Q) summed with dS; sum_j dS K^ sits in the Khi and Klo columns
+                        grad[a] = kLn2 * (dQ[c + cc] + dQ[c + nq + cc]) - pscale * rs * eff[a];
+                        gacc += rs * eff[a] * eff[a];
+                    } else {
+                        const float Gs = kscale * G0;
+                        const bf16_t hi = f2bf(Gs), lo = f2bf(Gs - bf2f(hi));
+                        eff[a] = kscale != 0.f ? (bf2f(hi) + bf2f(lo)) / kscale : G0;
+                        const float cs = p.colsum[bh * p.Lp + i];
+                        const float X = dK[c + cc] + dK[c + 2 * nq + cc];  // sum_i dS Q (Qhi and Qlo columns)
+                        grad[a] = pscale * (X - cs * eff[a]);
+                        gacc += cs * eff[a] * eff[a] - 2.f * eff[a] * X;
+                    }
+                }
+                gpartial = gacc;
+                bf16_t *dst = (isq ? p.d_q_pts : p.d_k_pts) + (rec * Pq + pt) * 3;
+                for (int x = 0; x < 3; ++x) {
+                    const float val = Rm[x] * grad[0] + Rm[3 + x] * grad[1] + Rm[6 + x] * grad[2];  // R^T
+                    dst[x] = f2bf(valid ? val : 0.f);
+                }
+            } else if (tk < 2 * Pq + Pv) {
+                const int pt = tk - 2 * Pq;
+                float grad[3];
+                for (int a = 0; a < 3; ++a) grad[a] = dV[v_pt_col(c, Pv, pt, a, 0)];
+                bf16_t *dst = p.d_v_pts + (rec * Pv + pt) * 3;
+                for (int x = 0; x < 3; ++x) {
+                    const float val = Rm[x] * grad[0] + Rm[3 + x] * grad[1] + Rm[6 + x] * grad[2];
+                    dst[x] = f2bf(valid ? val : 0.f);
+                }
+            } else {
+                const int which = tk - 2 * Pq - Pv;  // 0: d_q, 1: d_k, 2: d_v
+                const float *src = which == 0 ? dQ : (which == 1 ? dK : dV);
+                const float scale = which == 0 ? kLn2 : (which == 1 ? p.w_L * p.qk_scale : 1.f);
+                bf16_t *dst = (which == 0 ? p.d_q : (which == 1 ? p.d_k : p.d_v)) + rec * c;
+                for (int x = 0; x < c; ++x) dst[x] = f2bf(valid ? scale * src[x] : 0.f);
+            }
+        }
+        // d gamma: this residue's contribution, summed over its query and key points in a fixed order
+        __syncthreads();
+        gsm[tid] = gpartial;
+        __syncthreads();
+        if (active && tk == 0) {
+            float s = 0.f;
+            for (int x = 0; x < 2 * Pq; ++x) s += gsm[tid + x];
+            p.gpart[((size_t)b * p.H + h) * p.Lp + i] = valid ? s : 0.f;
+        }
+    }
+
+    // pair factors: sums over heads
+    for (int x = tid; x < p.DZ; x += 256) {
+        const int d = x % p.cz;
+        float s1 = 0.f, s2 = 0.f;
+        for (int h = 0; h < p.H; ++h) {
+            const size_t bh = (size_t)b * p.H + h;
+            const size_t row = (bh * p.Lp + i) * D + kDH + x;
+            const size_t rec = ((size_t)b * p.L + i) * p.H + h;
+            // z1: through the bias vector b^{h1} = w_L w_b z1, and through o~ = z1^T U
+            s1 += p.w_L * p.w_b[(size_t)h * p.cz + d] * p.dQhat[row] + p.d_o_pair[rec * p.cz + d] * p.Ohat[row];
+            // z2: as key feature (the log2e sits on the query side) and as value feature
+            s2 += kLn2 * p.dKhat[row] + p.dVhat[row];
+        }
+        p.d_z1[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? s1 : 0.f);
+        p.d_z2[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? s2 : 0.f);
+    }
+}
+
+// d gamma^h = -(w_L w_C / 2) * sum over (batch, residue) of the partial sums, in a fixed order.
+__global__ __launch_bounds__(256) void fipa_bwd_gamma_kernel(const float *gpart, float *d_gamma, int B, int H,
+                                                             int L, int Lp, float coef)
+{
+    __shared__ float red[256];
+    const int h = blockIdx.x, tid = threadIdx.x;
+    float s = 0.f;
+    for (int b = 0; b < B; ++b)
+        for (int i = tid; i < L; i += 256) s += gpart[((size_t)b * H + h) * Lp + i];
+    red[tid] = s;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if (tid < st) red[tid] += red[tid + st];
+        __syncthreads();
+    }
+    if (tid == 0) d_gamma[h] = coef * red[0];
+}
+
+struct BwdLayout {
+    Bf16Layout f;
+    size_t dOhat, Dvec, nlse, dQhat, dKhat, dVhat, rowsum, colsum, gpart, total;
+};
+
+BwdLayout bwd_layout(const fipa_desc &d)
+{
+    BwdLayout w;
+    w.f = bf16_layout(d, true);
+    const size_t BHL = (size_t)d.B * d.H * w.f.Lp;
+    const size_t D = kDH + w.f.DZ;
+    size_t off = w.f.total;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    w.dOhat = take(BHL * D * 2);
+    w.Dvec = take(BHL * 4);
+    w.nlse = take(BHL * 4);
+    w.dQhat = take(BHL * D * 4);
+    w.dKhat = take(BHL * D * 4);
+    w.dVhat = take(BHL * D * 4);
+    w.rowsum = take(BHL * 4);
+    w.colsum = take(BHL * 4);
+    w.gpart = take(BHL * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+hipError_t launch_bwd_pack_bf16(const BwdPackParams &p, hipStream_t stream)
+{
+    const size_t rows = (size_t)p.B * p.H * p.Lp;
+    hipLaunchKernelGGL(fipa_bwd_pack_bf16_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fipa_bwd_unpack_bf16_kernel, dim3(p.L, p.B), dim3(256), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fipa_bwd_gamma_kernel, dim3(p.H), dim3(256), 0, stream, p.gpart, p.d_gamma, p.B, p.H, p.L,
+                       p.Lp, -0.5f * p.w_L * p.w_C);
+    return hipGetLastError();
+}
+
+size_t bf16_backward_workspace(const fipa_desc &d) { return bwd_layout(d).total; }
+
+hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream)
+{
+    const BwdLayout w = bwd_layout(d);
+    char *base = static_cast<char *>(ws);
+    float *cen = reinterpret_cast<float *>(base + w.f.cen);
+    int *kvlen = reinterpret_cast<int *>(base + w.f.kvlen);
+    StageTimer timer(stream);
+
+    // ---- forward pack and (unfused) forward attention: lifted tensors, O^, log-sum-exp -------------
+    timer.begin(0);
+    hipError_t e = launch_prep(d, a.f.trans, a.f.mask, cen, kvlen, stream);
+    if (e != hipSuccess) return e;
+    PackParams pk;
+    pk.q = (const bf16_t *)a.f.q; pk.k = (const bf16_t *)a.f.k; pk.v = (const bf16_t *)a.f.v;
+    pk.q_pts = (const bf16_t *)a.f.q_pts; pk.k_pts = (const bf16_t *)a.f.k_pts;
+    pk.v_pts = (const bf16_t *)a.f.v_pts;
+    pk.z1 = (const bf16_t *)a.f.z1; pk.z2 = (const bf16_t *)a.f.z2;
+    pk.rot = a.f.rot; pk.trans = a.f.trans; pk.w_b = a.f.w_b; pk.gamma = a.f.gamma; pk.cen = cen;
+    pk.mask = a.f.mask;
+    pk.Qh = (bf16_t *)(base + w.f.Qh); pk.Qz = (bf16_t *)(base + w.f.Qz);
+    pk.Kh = (bf16_t *)(base + w.f.Kh); pk.Vh = (bf16_t *)(base + w.f.Vh); pk.Z2 = (bf16_t *)(base + w.f.Z2);
+    pk.kbias = (float *)(base + w.f.kbias); pk.qbias = (float *)(base + w.f.qbias);
+    pk.B = d.B; pk.L = d.L; pk.Lp = w.f.Lp; pk.NT = w.f.NT; pk.H = d.H; pk.c = d.c; pk.Pq = d.Pq;
+    pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.f.DZ;
+    pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
+    e = launch_pack_bf16(pk, stream);
+    if (e != hipSuccess) return e;
+
+    AttnParams at;
+    at.Qh = pk.Qh; at.Qz = pk.Qz; at.Kh = pk.Kh; at.Vh = pk.Vh; at.Z2 = pk.Z2;
+    at.kbias = pk.kbias; at.qbias = pk.qbias; at.kvlen = kvlen;
+    at.Ohat = (float *)(base + w.f.Ohat); at.lse2 = (float *)(base + w.f.lse2);
+    at.rot = a.f.rot; at.trans = a.f.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.f.mask;
+    at.o = nullptr; at.o_pts = nullptr; at.o_pair = nullptr; at.lse = nullptr;
+    at.B = d.B; at.L = d.L; at.Lp = w.f.Lp; at.H = d.H; at.NT = w.f.NT;
+    at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r;
+    e = launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
+    if (e != hipSuccess) return e;
+
+    BwdPackParams bp;
+    bp.d_o = a.d_o; bp.d_o_pts = a.d_o_pts; bp.d_o_pair = a.d_o_pair; bp.rot = a.f.rot;
+    bp.Ohat = at.Ohat; bp.lse2 = at.lse2; bp.z1 = pk.z1; bp.mask = a.f.mask;
+    bp.dOhat = (bf16_t *)(base + w.dOhat); bp.Dvec = (float *)(base + w.Dvec); bp.nlse = (float *)(base + w.nlse);
+    bp.B = d.B; bp.L = d.L; bp.Lp = w.f.Lp; bp.H = d.H; bp.c = d.c; bp.Pv = d.Pv; bp.cz = d.cz; bp.r = d.r;
+    bp.DZ = w.f.DZ;
+    e = launch_bwd_pack_bf16(bp, stream);
+    if (e != hipSuccess) return e;
+    timer.end(0);
+
+    // ---- dQ^, dK^, dV^ --------------------------------------------------------------------------------
+    timer.begin(1);
+    BwdParams bw;
+    bw.Qh = pk.Qh; bw.Qz = pk.Qz; bw.Kh = pk.Kh; bw.Vh = pk.Vh; bw.Z2 = pk.Z2; bw.dOhat = bp.dOhat;
+    bw.kbias = pk.kbias; bw.nlse = bp.nlse; bw.Dvec = bp.Dvec; bw.kvlen = kvlen;
+    bw.B = d.B; bw.Lp = w.f.Lp; bw.H = d.H; bw.total_tiles = at.total_tiles;
+    bw.out = (float *)(base + w.dQhat); bw.wsum = (float *)(base + w.rowsum);
+    e = launch_bwd_bf16(bw, w.f.DZ, FIPA_BWD_DQ, stream);
+    if (e != hipSuccess) return e;
+    bw.out = (float *)(base + w.dKhat); bw.wsum = (float *)(base + w.colsum);
+    e = launch_bwd_bf16(bw, w.f.DZ, FIPA_BWD_DK, stream);
+    if (e != hipSuccess) return e;
+    bw.out = (float *)(base + w.dVhat); bw.wsum = nullptr;
+    e = launch_bwd_bf16(bw, w.f.DZ, FIPA_BWD_DV, stream);
+    if (e != hipSuccess) return e;
+    timer.end(1);
+
+    // ---- back to the inputs ----------------------------------------------------------------------------
+    timer.begin(2);
+    BwdUnpackParams up;
+    up.q_pts = pk.q_pts; up.k_pts = pk.k_pts; up.z1 = pk.z1;
+    up.rot = a.f.rot; up.trans = a.f.trans; up.cen = cen; up.gamma = a.f.gamma; up.w_b = a.f.w_b;
+    up.d_o_pair = a.d_o_pair; up.mask = a.f.mask;
+    up.dQhat = (const float *)(base + w.dQhat); up.dKhat = (const float *)(base + w.dKhat);
+    up.dVhat = (const float *)(base + w.dVhat); up.Ohat = at.Ohat;
+    up.rowsum = (const float *)(base + w.rowsum); up.colsum = (const float *)(base + w.colsum);
+    up.d_q = (bf16_t *)a.d_q; up.d_k = (bf16_t *)a.d_k; up.d_v = (bf16_t *)a.d_v;
+    up.d_q_pts = (bf16_t *)a.d_q_pts; up.d_k_pts = (bf16_t *)a.d_k_pts; up.d_v_pts = (bf16_t *)a.d_v_pts;
+    up.d_z1 = (bf16_t *)a.d_z1; up.d_z2 = (bf16_t *)a.d_z2;
+    up.gpart = (float *)(base + w.gpart); up.d_gamma = a.d_gamma;
+    up.B = d.B; up.L = d.L; up.Lp = w.f.Lp; up.H = d.H; up.c = d.c; up.Pq = d.Pq; up.Pv = d.Pv; up.cz = d.cz;
+    up.r = d.r; up.DZ = w.f.DZ;
+    up.w_L = d.w_L; up.w_C = d.w_C; up.qk_scale = d.qk_scale;
+    e = launch_bwd_unpack_bf16(up, stream);
+    timer.end(2);
+    return e;
+}
+
+}  // namespace fipa

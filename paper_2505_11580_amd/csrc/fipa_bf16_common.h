@@ -118,6 +118,45 @@ struct EpiParams {
     int B, L, Lp, H, c, Pv, cz, r, DZ;
 };
 
+// ---- backward -----------------------------------------------------------------------------------
+enum { FIPA_BWD_DQ = 0, FIPA_BWD_DK = 1, FIPA_BWD_DV = 2 };
+
+struct BwdParams {
+    const bf16_t *Qh, *Qz, *Kh, *Vh, *Z2, *dOhat;  // lifted tensors (dOhat: [B,H,Lp,64+DZ])
+    const float *kbias;   // [B,H,Lp] per-key logit term (log2 units; -inf = masked)
+    const float *nlse;    // [B,H,Lp] minus the log2 log-sum-exp of the kernel's logits (-inf = invalid query)
+    const float *Dvec;    // [B,H,Lp] D_i = dO^_i . O^_i
+    const int *kvlen;
+    float *out;           // [B,H,Lp,64+DZ] dQ^ / dK^ / dV^
+    float *wsum;          // [B,H,Lp] sum of the rounded dS over the streamed side, or NULL
+    int B, Lp, H, total_tiles;
+};
+
+struct BwdPackParams {
+    const float *d_o, *d_o_pts, *d_o_pair, *rot, *Ohat, *lse2;
+    const bf16_t *z1;
+    const uint8_t *mask;
+    bf16_t *dOhat;
+    float *Dvec, *nlse;
+    int B, L, Lp, H, c, Pv, cz, r, DZ;
+};
+
+struct BwdUnpackParams {
+    const bf16_t *q_pts, *k_pts, *z1;
+    const float *rot, *trans, *cen, *gamma, *w_b, *d_o_pair;
+    const uint8_t *mask;
+    const float *dQhat, *dKhat, *dVhat, *Ohat, *rowsum, *colsum;
+    bf16_t *d_q, *d_k, *d_v, *d_q_pts, *d_k_pts, *d_v_pts, *d_z1, *d_z2;
+    float *gpart;   // [B,H,Lp] per-(b,h,i) contribution to d gamma
+    float *d_gamma; // [H]
+    int B, L, Lp, H, c, Pq, Pv, cz, r, DZ;
+    float w_L, w_C, qk_scale;
+};
+
+hipError_t launch_bwd_bf16(const BwdParams &p, int DZ, int mode, hipStream_t stream);
+hipError_t launch_bwd_pack_bf16(const BwdPackParams &p, hipStream_t stream);
+hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream);
+
 hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream);
 hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream);
 hipError_t launch_epilogue_bf16(const EpiParams &p, hipStream_t stream);

@@ -63,7 +63,5 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     return e;
 }
 
-size_t bf16_backward_workspace(const fipa_desc &) { return 0; }
-hipError_t bf16_backward(const fipa_desc &, const BwdArgs &, void *, hipStream_t) { return hipErrorNotSupported; }
 
 }  // namespace fipa
