@@ -85,7 +85,7 @@ inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
 }
 
 // The fused epilogue is compiled for the AlphaFold2-style head shape only.
-inline bool bf16_fused_epilogue(const fipa_desc &d) { return d.c == 16 && d.Pv == 8; }
+inline bool bf16_fused_epilogue(const fipa_desc &d) { return d.c == 16 && d.Pv == 8 && d.r * d.cz <= 256; }
 
 struct PackParams {
     const bf16_t *q, *k, *v, *q_pts, *k_pts, *v_pts, *z1, *z2;
@@ -159,6 +159,7 @@ hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream);
 
 hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream);
 hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream);
+hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, hipStream_t stream);  // r*cz = 512
 hipError_t launch_epilogue_bf16(const EpiParams &p, hipStream_t stream);
 
 }  // namespace fipa

@@ -46,7 +46,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     at.B = d.B; at.L = d.L; at.Lp = w.Lp; at.H = d.H; at.NT = w.NT;
     at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r;
     timer.begin(1);
-    e = launch_attn_fwd_bf16(at, w.DZ, fused, stream);
+    e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream) : launch_attn_fwd_bf16(at, w.DZ, fused, stream);
     if (e != hipSuccess) return e;
     timer.end(1);
     if (fused) return hipSuccess;  // steps 8-9 ran inside the attention kernel

@@ -77,6 +77,23 @@ def test_bf16_workload2_sampled_rows():
     gu.check(inp, rows=wl.select_rows(inp, 96), label="cfg2 bf16 sampled rows")
 
 
+def test_bf16_rank4_small():
+    # r*c_z = 512 (lifted width 576): the windowed kernel
+    gu.check(wl.make_inputs(3, B=1, L=200, H=2, varlen=False), label="bf16 r=4 L=200")
+    gu.check(wl.make_inputs(3, B=2, L=300, H=2, min_len=40, trans_scale=0.2), label="bf16 r=4 varlen spread")
+
+
+def test_bf16_workload3_sampled_rows():
+    # variable-length padded batch, lengths U[1024, 8192], r = 4: first / last valid / first padded /
+    # random rows of every batch element against the oracle's row-subset form
+    inp = wl.make_inputs(3)
+    gu.check(inp, rows=wl.select_rows(inp, 24), label="cfg3 bf16 sampled rows")
+    got = gu.run_gpu(inp)
+    for b, ln in enumerate(inp["lengths"]):
+        for n in gu.NAMES:
+            assert np.all(got[n][b, int(ln):] == 0), (n, b)
+
+
 def test_bf16_workload4_forward_sampled_rows():
     inp = wl.make_inputs(4, with_grads=False)
     gu.check(inp, rows=wl.select_rows(inp, 48), label="cfg4 fwd bf16 sampled rows")
