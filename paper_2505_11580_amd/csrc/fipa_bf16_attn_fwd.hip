@@ -68,7 +68,9 @@ struct AttnCfg {
     static constexpr int KB_OFF = NIW * 4 * 1024;        // 32 per-key fp32 biases (a full 1 KiB load lands here)
     static constexpr int STAGE = KB_OFF + 1024;
     static constexpr int NSTAGE = 5 * STAGE <= 160 * 1024 ? 5 : 4;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    static constexpr int CW_OFF = NSTAGE * STAGE;        // per-head scale vector of the query-side factors (DZ floats)
+    static constexpr int LDS_BYTES = CW_OFF + DZ * 4;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static constexpr int NOPS = 2 * KS;      // MFMAs per pipelined iteration (KS == 2*NB)
     static_assert(KS == 2 * NB, "S^T and P V use the same number of MFMAs per block");
     static constexpr int LA = NOPS % 8 == 0 ? 4 : 2;  // LDS operands are fetched in groups of LA MFMAs, one group ahead
@@ -461,6 +463,8 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // Key blocks are visited starting at the block that holds the tile's own residues and
     // wrapping around.  With distance-dominated logits the row maximum sits near the diagonal,
     // so the reference maximum is found in the first blocks and is rarely raised afterwards.
+    // (The staggered starts also spread the tiles of a head over different blocks at any one
+    // time; visiting the blocks in the same order everywhere measured slower.)
     const int first_blk = min(qt * (kTileQ / kBlk), max(nblk - 1, 0));
 
     Dma<DZ> dma;
@@ -495,12 +499,12 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     const unsigned smem_lds = lds_address(smem);
     int next_blk = first_blk;  // next key block to request
 
-    Wave<DZ> w;
     if (nblk > 0) {
-        // the first four blocks of the sequence (beyond the end of a short sequence the
-        // requests simply go round again: every stage they touch is free)
+        // the first two blocks of the sequence; the next two follow once the query fragments
+        // have been requested, so that what the first products need arrives first.  (Beyond the
+        // end of a short sequence the requests simply go round again: every stage they touch is free.)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             if (next_blk == nblk) {
                 dma_wrap<DZ>(dma, nblk);
                 next_blk = 0;
@@ -515,13 +519,40 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // there), which leaves the architectural registers to the operand ring and the softmax.
     // The loads are invisible to the compiler's wait-count bookkeeping; the wait_vmem<0>()
     // below covers them, and the empty asm after it orders every use behind that wait.
+    // With the fused epilogue (AlphaFold2 head shape) the pair part of q^ -- the bias vector
+    // b^{h1} = log2e * w_L * w_b[h] (.) z1 of Algorithm 1 steps 2-3 -- is formed here from z1,
+    // which all heads of a residue share, instead of being read per head from memory.
+    Wave<DZ> w;
+    uint4 zraw[FUSED ? C::KSZ : 1];
     {
         const bf16_t *qh = p.Qh + ((size_t)bh * p.Lp + irow) * kDH;
-        const bf16_t *qz = p.Qz + ((size_t)bh * p.Lp + irow) * DZ;
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const bf16_t *src = ks < C::KSH ? qh + ks * 16 + 8 * g : qz + (ks - C::KSH) * 16 + 8 * g;
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(w.qf[ks]) : "v"(src) : "memory");
+        for (int ks = 0; ks < C::KSH; ++ks)
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(w.qf[ks]) : "v"(qh + ks * 16 + 8 * g) : "memory");
+        if constexpr (!FUSED) {
+            const bf16_t *qz = p.Qz + ((size_t)bh * p.Lp + irow) * DZ;
+#pragma unroll
+            for (int ks = 0; ks < C::KSZ; ++ks)
+                asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(w.qf[C::KSH + ks]) : "v"(qz + ks * 16 + 8 * g) : "memory");
+            if (nblk > 0) {
+#pragma unroll
+                for (int i = 2; i < 4; ++i) {
+                    if (next_blk == nblk) {
+                        dma_wrap<DZ>(dma, nblk);
+                        next_blk = 0;
+                    }
+                    issue_block<DZ>(dma, smem_lds + i * C::STAGE);
+                    ++next_blk;
+                }
+            }
+        } else {
+            // this lane's 8-feature chunks of the z1 row; the per-head scale vector goes to LDS
+            const bf16_t *z1row = p.z1 + ((size_t)b * p.L + min(irow, p.L - 1)) * DZ + 8 * g;
+#pragma unroll
+            for (int ks = 0; ks < C::KSZ; ++ks) zraw[ks] = *reinterpret_cast<const uint4 *>(z1row + 16 * ks);
+            if (tid < DZ)
+                reinterpret_cast<float *>(smem + C::CW_OFF)[tid] =
+                    kLog2e * p.w_L * p.w_b[(size_t)(bh - b * p.H) * p.cz + tid % p.cz];
         }
     }
 #pragma unroll
@@ -543,11 +574,49 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     bf16x8 pf[2];
     f32x16 sacc;
     bf16x8 fr[C::RING];
-    wait_vmem<0>();  // q^ fragments and the first stages; nothing the compiler tracks stays pending
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+a"(w.qf[ks]));
+    // q^ fragments and the first two stages.  (Unfused: blocks 2 and 3 may still be on their way;
+    // the steady loop waits for them.)  Nothing the compiler tracks stays pending.
+    if (!FUSED && nblk > 0)
+        wait_vmem<2 * C::VM_PER_BLOCK>();
+    else
+        wait_vmem<0>();
     if (nblk > 0) {
-        wg_barrier();
+        if constexpr (FUSED)
+            __syncthreads();  // (with its fence: the scale vector written above is read by every wave)
+        else
+            wg_barrier();
+        if constexpr (FUSED) {
+            // q^ pair part: bf16(scale[col] * z1[row, col]); rows that do not exist or are masked get 0
+            const bool ok = irow < p.L && (p.mask ? p.mask[(size_t)b * p.L + irow] != 0 : true);
+            const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
+            const float *cw = reinterpret_cast<const float *>(smem + C::CW_OFF) + 8 * g;
+#pragma unroll
+            for (int ks = 0; ks < C::KSZ; ++ks) {
+                const f32x4 w0 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks);
+                const f32x4 w1 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks + 4);
+                const bf16_t *e = reinterpret_cast<const bf16_t *>(&zraw[ks]);
+                unsigned pk[4];
+#pragma unroll
+                for (int x = 0; x < 8; x += 2) {
+                    const unsigned lo = f2bf((x < 4 ? w0[x & 3] : w1[x & 3]) * bf2f(e[x]));
+                    const unsigned hi = f2bf((x < 4 ? w0[(x & 3) + 1] : w1[(x & 3) + 1]) * bf2f(e[x + 1]));
+                    pk[x >> 1] = (lo | (hi << 16)) & keep;
+                }
+                w.qf[C::KSH + ks] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
+            }
+            // blocks 2 and 3 of the sequence (the steady loop waits for them)
+#pragma unroll
+            for (int i = 2; i < 4; ++i) {
+                if (next_blk == nblk) {
+                    dma_wrap<DZ>(dma, nblk);
+                    next_blk = 0;
+                }
+                issue_block<DZ>(dma, smem_lds + i * C::STAGE);
+                ++next_blk;
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+a"(w.qf[ks]));
         sacc = s_block<DZ>(w, smem);
         const float mx = row_max16(sacc);
         w.m_ref = mx;
@@ -582,7 +651,7 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
 
     // ---- drain: the last two blocks -----------------------------------------------------------------
     if (nblk > 1) {
-        // P V of block nblk-2, exponentials of block nblk-1
+        // P V of the last block but one, exponentials of the last block
         const char *st = smem + s0 * C::STAGE;
 #pragma unroll
         for (int nb = 0; nb < C::NB; ++nb) pv_block<DZ>(w, st, pf, nb);

@@ -261,6 +261,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     pk.B = d.B; pk.L = d.L; pk.Lp = w.f.Lp; pk.NT = w.f.NT; pk.H = d.H; pk.c = d.c; pk.Pq = d.Pq;
     pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.f.DZ;
     pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
+    pk.skip_qz = false;
     e = launch_pack_bf16(pk, stream);
     if (e != hipSuccess) return e;
 
@@ -271,7 +272,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     at.rot = a.f.rot; at.trans = a.f.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.f.mask;
     at.o = nullptr; at.o_pts = nullptr; at.o_pair = nullptr; at.lse = nullptr;
     at.B = d.B; at.L = d.L; at.Lp = w.f.Lp; at.H = d.H; at.NT = w.f.NT;
-    at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r;
+    at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.f.w_b; at.w_L = d.w_L;
     e = launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
     if (e != hipSuccess) return e;
 

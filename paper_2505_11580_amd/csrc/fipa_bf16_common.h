@@ -95,6 +95,7 @@ struct PackParams {
     float *kbias, *qbias;
     int B, L, Lp, NT, H, c, Pq, Pv, cz, r, DZ;
     float w_L, w_C, qk_scale;
+    bool skip_qz;  // the attention kernel forms the query-side factor vectors itself
 };
 
 struct AttnParams {
@@ -103,11 +104,12 @@ struct AttnParams {
     const int *kvlen;
     float *Ohat, *lse2;  // unfused epilogue only
     // fused epilogue: final outputs and what they need
-    const float *rot, *trans, *cen;
+    const float *rot, *trans, *cen, *w_b;
     const bf16_t *z1;
     const uint8_t *mask;
     float *o, *o_pts, *o_pair, *lse;
     int B, L, Lp, H, NT, nQT, total_tiles, cz, r;
+    float w_L;
 };
 
 struct EpiParams {

@@ -32,6 +32,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     pk.B = d.B; pk.L = d.L; pk.Lp = w.Lp; pk.NT = w.NT; pk.H = d.H; pk.c = d.c; pk.Pq = d.Pq;
     pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.DZ;
     pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
+    pk.skip_qz = fused && w.DZ <= 256;
     e = launch_pack_bf16(pk, stream);
     if (e != hipSuccess) return e;
     timer.end(0);
@@ -44,7 +45,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     at.rot = a.rot; at.trans = a.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.mask;
     at.o = a.o; at.o_pts = a.o_pts; at.o_pair = a.o_pair; at.lse = a.lse;
     at.B = d.B; at.L = d.L; at.Lp = w.Lp; at.H = d.H; at.NT = w.NT;
-    at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r;
+    at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.w_b; at.w_L = d.w_L;
     timer.begin(1);
     e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream) : launch_attn_fwd_bf16(at, w.DZ, fused, stream);
     if (e != hipSuccess) return e;

@@ -264,8 +264,9 @@ hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream)
     const size_t cpr = p.DZ / 8;
     hipLaunchKernelGGL(fipa_pack_z2_bf16_kernel, dim3((unsigned)(((size_t)p.B * p.Lp * cpr + 255) / 256)),
                        dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(fipa_pack_qz_bf16_kernel,
-                       dim3((unsigned)(((size_t)p.B * p.H * p.Lp * cpr + 255) / 256)), dim3(256), 0, stream, p);
+    if (!p.skip_qz)
+        hipLaunchKernelGGL(fipa_pack_qz_bf16_kernel,
+                           dim3((unsigned)(((size_t)p.B * p.H * p.Lp * cpr + 255) / 256)), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 

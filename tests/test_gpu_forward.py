@@ -68,6 +68,15 @@ def test_bf16_mask_and_garbage():
     gu.check(inp, label="bf16 scattered mask")
 
 
+@pytest.mark.parametrize("B,H,L", [(2, 4, 512), (5, 4, 512), (3, 8, 640)])
+def test_bf16_medium_ragged(B, H, L):
+    # several query tiles per head, ragged lengths down to a chain shorter than one tile
+    inp = wl.make_inputs(1, B=B, L=L, H=H, varlen=True, min_len=40)
+    gu.check(inp, label="bf16 ragged B=%d H=%d L=%d lengths=%s" % (B, H, L, list(inp["lengths"])))
+    inp = wl.make_inputs(1, B=B, L=L, H=H, trans_scale=0.05)  # spread attention: every key matters
+    gu.check(inp, label="bf16 spread B=%d H=%d L=%d" % (B, H, L))
+
+
 def test_bf16_workload1_full():
     gu.check(wl.make_inputs(1), label="cfg1 bf16 full")
 
