@@ -26,20 +26,11 @@
 // a block, taken against the current reference, sum to more than 2^kTau; until then nothing is
 // rescaled.  The result is the same softmax: numerator and denominator carry the same factor
 // 2^(m_true - m_ref), and fp32 / bf16 keep their relative precision over that range.
-#include "fipa_bf16_common.h"
+#include "fipa_gfx950.h"
 
 namespace fipa {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr float kTau = 32.0f;
 constexpr float kTauPow = 4294967296.0f;  // 2^kTau
@@ -79,51 +70,6 @@ struct AttnCfg {
     static constexpr int VM_PER_BLOCK = NIW + 1;          // vector-memory ops one wave issues per block
     static constexpr int DMA_EVERY = NOPS / (NIW + 1);   // one load entry every DMA_EVERY MFMAs
 };
-
-__device__ __forceinline__ bf16x4 lds_read_tr(const char *ptr)
-{
-    return __builtin_bit_cast(
-        bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ptr)));
-}
-
-// One entry of the direct global -> LDS loads: 16 bytes per lane, not passing through
-// registers.  Lane l fetches base + voff and writes LDS byte (lds_base + LDS_IMM + 16*l); voff
-// is first advanced by `step` (the distance to the next key block).  Written as inline
-// assembly so that the compiler neither counts these loads nor orders LDS reads after them;
-// completion is awaited explicitly with wait_vmem<N>() before the barrier that publishes the
-// stage.  (The vector add between the write of m0 and the load also covers the wait state the
-// hardware wants between the two.)
-template <int LDS_IMM>
-__device__ __forceinline__ void dma16(const char *base, int &voff, int step, unsigned lds_base)
-{
-    asm volatile(
-        "s_add_u32 m0, %1, %2\n\t"
-        "v_add_u32 %0, %3, %0\n\t"
-        "global_load_lds_dwordx4 %0, %4"
-        : "+v"(voff)
-        : "s"(lds_base), "n"(LDS_IMM), "s"(step), "s"(base)
-        : "memory", "m0", "scc");
-}
-
-__device__ __forceinline__ unsigned lds_address(const char *ptr)
-{
-    return (unsigned)(uintptr_t)((__attribute__((address_space(3))) const char *)ptr);
-}
-
-// Workgroup barrier without the fence that __syncthreads() adds: the only cross-wave traffic
-// here are the direct loads, whose completion each wave awaits itself.
-__device__ __forceinline__ void wg_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmem()  // s_waitcnt vmcnt(N) only
-{
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
-}
 
 template <int DZ>
 struct Wave {
@@ -179,17 +125,6 @@ __device__ __forceinline__ void pv_block(Wave<DZ> &w, const char *__restrict__ s
         }
         w.oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt], w.oacc[nb], 0, 0, 0);
     }
-}
-
-// Two probabilities -> one packed bf16 pair (one v_cvt_pk_bf16_f32), and their rounded values
-// added to the running denominator (one v_dot2c_f32_bf16): the denominator must sum exactly
-// the weights the MFMA will use, so that the output stays a convex combination of the values.
-__device__ __forceinline__ unsigned pack_pair(float e0, float e1, float &psum)
-{
-    const bf16x2 b = __builtin_convertvector((f32x2){e0, e1}, bf16x2);
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    psum = __builtin_amdgcn_fdot2_f32_bf16(b, ones, psum, false);
-    return __builtin_bit_cast(unsigned, b);
 }
 
 // All 16 exponentials of an S^T block against the reference maximum -> MFMA B operands.

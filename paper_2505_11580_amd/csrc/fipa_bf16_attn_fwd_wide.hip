@@ -5,20 +5,11 @@
 // Plain structure: one LDS stage filled through registers, online softmax with the running
 // maximum of Algorithm 2 (raised lazily), unfused epilogue.  First correct version for this
 // width, not pipelined.
-#include "fipa_bf16_common.h"
+#include "fipa_gfx950.h"
 
 namespace fipa {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int kKB = 32;      // keys per block
 constexpr float kTauW = 8.f;
@@ -40,20 +31,6 @@ struct WideCfg {
     static constexpr int VCH = kKB * kDH / 8;    // of the v^ head tile
     static constexpr int KCT = (KCH + 255) / 256, VCT = (VCH + 255) / 256;
 };
-
-__device__ __forceinline__ bf16x4 lds_read_tr(const char *ptr)
-{
-    return __builtin_bit_cast(
-        bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ptr)));
-}
-
-__device__ __forceinline__ unsigned pack_pair(float e0, float e1, float &sum)
-{
-    const bf16x2 b = __builtin_convertvector((f32x2){e0, e1}, bf16x2);
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    sum = __builtin_amdgcn_fdot2_f32_bf16(b, ones, sum, false);
-    return __builtin_bit_cast(unsigned, b);
-}
 
 template <int DZ, int NWIN>
 __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p)

@@ -14,60 +14,78 @@
 // Both small products are formed transposed (streamed row = MFMA row, stationary row = lane), so
 // the per-stationary-row scalars are per-lane values and the weights are already laid out as the
 // B operand of the accumulating MFMA, whose A operand is read from the row-major streamed tile
-// with the transposing LDS read.  Plain structure (one LDS stage, loads through registers): this
-// is the first correct version, not yet pipelined like the forward kernel.
-#include "fipa_bf16_common.h"
+// with the transposing LDS read.
+//
+// The streamed blocks arrive in a ring of three LDS stages by direct global -> LDS loads issued
+// two blocks ahead, so the memory latency is covered by the MFMAs of the two blocks in between;
+// one barrier per block publishes the new stage and releases the oldest.
+#include "fipa_gfx950.h"
 
 namespace fipa {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+constexpr int kSB = 32;              // streamed rows per block
+constexpr int kHS = kDH * 2 + 16;    // LDS row stride (bytes) of a 64-column head-specific tile
 
-constexpr int kSB = 32;  // streamed rows per block
-
-template <int DZ>
+template <int DZ, int MODE>
 struct BwdCfg {
     static constexpr int D = kDH + DZ;           // lifted width
     static constexpr int KS = D / 16;            // k-steps of the small products
     static constexpr int KSH = kDH / 16;
     static constexpr int NB = D / 32;            // 32-row blocks of the accumulator
-    static constexpr int RS = D * 2 + 48;        // LDS row stride (bytes): conflict free for row reads and transposing reads
-    static constexpr int X_BYTES = kSB * RS;
-    static constexpr int X1_OFF = 0;
-    static constexpr int X2_OFF = X_BYTES;
-    static constexpr int SROW_OFF = 2 * X_BYTES;        // 32 floats: per-streamed-row logit term
-    static constexpr int DROW_OFF = SROW_OFF + 128;     // 32 floats: per-streamed-row D (DK only)
-    static constexpr int LDS_BYTES = DROW_OFF + 128;
-    static constexpr int NCHUNK = kSB * D / 8;          // 16-byte chunks per tile
-    static constexpr int CHUNKS = (NCHUNK + 255) / 256; // per thread
+    static constexpr int NBH = kDH / 32;
+    static constexpr int ZS = DZ * 2 + 48;       // LDS row stride of a pair-part tile: conflict free for row reads and transposing reads
+    static constexpr int Z_SPR = ZS / 16, H_SPR = kHS / 16;   // 16-byte slots per row
+    static constexpr int NZ = (kSB * Z_SPR + 63) / 64;         // wave-wide 1 KiB loads per pair-part tile
+    static constexpr int NH = (kSB * H_SPR + 63) / 64;         // per head-part tile
+    // DQ streams k^ and v^, whose pair parts are the same z2 rows: one copy serves both
+    static constexpr bool kSharedZ = MODE == FIPA_BWD_DQ;
+    // flat list of the wave-wide loads of one block: X1 pair | X1 head | X2 pair (unless shared) | X2 head
+    static constexpr int X1Z_OFF = 0;
+    static constexpr int X1H_OFF = NZ * 1024;
+    static constexpr int X2Z_OFF = kSharedZ ? X1Z_OFF : (NZ + NH) * 1024;
+    static constexpr int X2H_OFF = kSharedZ ? (NZ + NH) * 1024 : (2 * NZ + NH) * 1024;
+    static constexpr int NI = (kSharedZ ? NZ : 2 * NZ) + 2 * NH;
+    static constexpr int NIW = (NI + 3) / 4;     // per wave
+    static constexpr int NSC = MODE == FIPA_BWD_DK ? 2 : 1;   // per-streamed-row scalars: logit term (+ D for DK)
+    static constexpr int SC_OFF = NIW * 4 * 1024;              // each scalar load covers 1 KiB (its first 128 bytes are data)
+    static constexpr int STAGE = SC_OFF + 2 * 1024;
+    static constexpr int NSTAGE = 3;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static constexpr int VM_PER_BLOCK = NIW + NSC;             // vector-memory ops one wave issues per block
 };
 
-__device__ __forceinline__ bf16x4 lds_read_tr(const char *ptr)
-{
-    return __builtin_bit_cast(
-        bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(ptr)));
-}
+// The direct loads of one wave (see dma16): wave w issues entries w, w+4, ... of the flat list;
+// surplus entries repeat entry 0 into the spare KiB the stage keeps for them.  Lanes whose slot
+// lies in the row padding or past the last row fetch element 0 of the tile again (harmless).
+template <int DZ, int MODE>
+struct BwdDma {
+    using C = BwdCfg<DZ, MODE>;
+    const char *src[C::NIW + C::NSC];  // wave-uniform
+    int step[C::NIW + C::NSC];         // wave-uniform: bytes from one block to the next
+    int voff[C::NIW + C::NSC];         // per lane: byte offset of the previously requested block
+    unsigned wave_lds;
+};
 
-__device__ __forceinline__ unsigned pack_pair(float e0, float e1, float &sum)
+template <int DZ, int MODE, int K = 0>
+__device__ __forceinline__ void bwd_issue_block(BwdDma<DZ, MODE> &d, unsigned stage)
 {
-    const bf16x2 b = __builtin_convertvector((f32x2){e0, e1}, bf16x2);
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    sum = __builtin_amdgcn_fdot2_f32_bf16(b, ones, sum, false);
-    return __builtin_bit_cast(unsigned, b);
+    using C = BwdCfg<DZ, MODE>;
+    if constexpr (K < C::NIW) {
+        dma16<4096 * K>(d.src[K], d.voff[K], d.step[K], stage + d.wave_lds);
+        bwd_issue_block<DZ, MODE, K + 1>(d, stage);
+    } else if constexpr (K < C::NIW + C::NSC) {
+        dma16<C::SC_OFF + 1024 * (K - C::NIW)>(d.src[K], d.voff[K], d.step[K], stage);
+        bwd_issue_block<DZ, MODE, K + 1>(d, stage);
+    }
 }
 
 template <int DZ, int MODE>
 __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
 {
-    using C = BwdCfg<DZ>;
+    using C = BwdCfg<DZ, MODE>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
 
@@ -77,20 +95,21 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     const int nT = p.Lp / kTileQ;
     const int bh = logical / nT, tile = logical - bh * nT;
     const int b = bh / p.H;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, g = lane >> 5;
     const int kvlen = p.kvlen[b];
     const int nblk = (kvlen + kSB - 1) / kSB;       // streamed blocks: residues past the last valid one contribute nothing
     const int srow = tile * kTileQ + wave * 32 + li;  // stationary row of this lane, < Lp
 
-    // streamed sources (row pointers of block 0) and stationary sources, by mode
-    const bf16_t *x1h, *x1z, *x2h, *x2z, *y1h, *y1z, *y2h, *y2z;
-    int x1hp, x1zp, x2hp, x2zp, y1hp, y1zp, y2hp, y2zp;  // row pitches in elements
-    const float *srow_src, *slane_src, *drow_src = nullptr, *dlane_src = nullptr;
+    // streamed tiles (row 0 of block 0, row pitch in bytes) and stationary sources, by mode
     const bf16_t *Qh = p.Qh + (size_t)bh * p.Lp * kDH, *Qz = p.Qz + (size_t)bh * p.Lp * DZ;
     const bf16_t *Kh = p.Kh + (size_t)bh * p.Lp * kDH, *Vh = p.Vh + (size_t)bh * p.Lp * kDH;
     const bf16_t *Z2 = p.Z2 + (size_t)b * p.Lp * DZ;
     const bf16_t *dO = p.dOhat + (size_t)bh * p.Lp * C::D;
+    const bf16_t *x1z, *x1h, *x2z, *x2h, *y1h, *y1z, *y2h, *y2z;
+    int x1zp, x1hp, x2zp, x2hp, y1hp, y1zp, y2hp, y2zp;  // row pitches in elements
+    const float *srow_src, *slane_src, *drow_src = nullptr, *dlane_src = nullptr;
     if (MODE == FIPA_BWD_DQ) {
         x1h = Kh; x1hp = kDH; x1z = Z2; x1zp = DZ; x2h = Vh; x2hp = kDH; x2z = Z2; x2zp = DZ;
         y1h = Qh; y1hp = kDH; y1z = Qz; y1zp = DZ; y2h = dO; y2hp = C::D; y2z = dO + kDH; y2zp = C::D;
@@ -104,6 +123,40 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
         slane_src = p.kbias + (size_t)bh * p.Lp;
         drow_src = p.Dvec + (size_t)bh * p.Lp;
     }
+
+    // ---- direct global -> LDS loads of the streamed blocks -------------------------------------
+    BwdDma<DZ, MODE> dma;
+    dma.wave_lds = 1024u * wave;
+#pragma unroll
+    for (int k = 0; k < C::NIW; ++k) {
+        int i = wave + 4 * k;
+        if (i >= C::NI) i = 0;
+        // region of flat entry i
+        const int r1 = C::NZ, r2 = C::NZ + C::NH, r3 = C::kSharedZ ? r2 : r2 + C::NZ;
+        const bool is_z = i < r1 || (!C::kSharedZ && i >= r2 && i < r3);
+        const bool is_x1 = i < r2;
+        const int first = i < r1 ? 0 : (i < r2 ? r1 : (i < r3 ? r2 : r3));
+        const bf16_t *base = is_x1 ? (is_z ? x1z : x1h) : (is_z ? x2z : x2h);
+        const int pitch = 2 * (is_x1 ? (is_z ? x1zp : x1hp) : (is_z ? x2zp : x2hp));  // bytes
+        const int spr = is_z ? C::Z_SPR : C::H_SPR;
+        const int cols = is_z ? DZ / 8 : kDH / 8;  // 16-byte columns of a tile row
+        const int s = 64 * (i - first) + lane;
+        const int row = s / spr, col = s - row * spr;
+        dma.src[k] = reinterpret_cast<const char *>(base);
+        dma.step[k] = kSB * pitch;
+        dma.voff[k] = ((row < kSB && col < cols) ? row * pitch + col * 16 : 0) - dma.step[k];
+    }
+    dma.src[C::NIW] = reinterpret_cast<const char *>(srow_src);
+    dma.step[C::NIW] = kSB * 4;
+    dma.voff[C::NIW] = min(lane, 7) * 16 - dma.step[C::NIW];
+    if constexpr (C::NSC == 2) {
+        dma.src[C::NIW + 1] = reinterpret_cast<const char *>(drow_src);
+        dma.step[C::NIW + 1] = kSB * 4;
+        dma.voff[C::NIW + 1] = min(lane, 7) * 16 - dma.step[C::NIW + 1];
+    }
+    const unsigned smem_lds = lds_address(smem);
+    if (nblk > 0) bwd_issue_block<DZ, MODE>(dma, smem_lds);
+    if (nblk > 1) bwd_issue_block<DZ, MODE>(dma, smem_lds + C::STAGE);
 
     // stationary fragments: features 16*ks + 8*g .. +7 of row srow
     bf16x8 y1f[C::KS], y2f[kNeedDP ? C::KS : 1];
@@ -128,62 +181,54 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
         for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
     float wsum = 0.f;  // sum over streamed rows of the rounded dS (DQ: row sums, DK: column sums)
 
-    const int kaddr = li * C::RS + g * 16;
+    // per-lane LDS offsets inside a stage
     const int l16 = lane & 15, grp2 = (lane >> 4) & 1, e4 = l16 >> 2, j4 = l16 & 3;
-    const int vaddr = (4 * g + e4) * C::RS + (16 * grp2 + 4 * j4) * 2;
+    const int ka_h = li * kHS + g * 16, ka_z = li * C::ZS + g * 16;                    // row reads (small products)
+    const int va_h = (4 * g + e4) * kHS + (16 * grp2 + 4 * j4) * 2;                     // transposing reads
+    const int va_z = (4 * g + e4) * C::ZS + (16 * grp2 + 4 * j4) * 2;
+    constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;               // tile the accumulation reads
+    constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
 
-    for (int blk = 0; blk < nblk; ++blk) {
-        const int r0 = blk * kSB;
-        // ---- stage the streamed block: two row-major tiles [32][D] and the per-row scalars ----
-        uint4 st1[C::CHUNKS], st2[C::CHUNKS];
-#pragma unroll
-        for (int it = 0; it < C::CHUNKS; ++it) {
-            const int q = min(it * 256 + tid, C::NCHUNK - 1);
-            const int row = q / (C::D / 8), cc = q - row * (C::D / 8);
-            const bf16_t *s1 = cc < kDH / 8 ? x1h + (size_t)(r0 + row) * x1hp + cc * 8
-                                            : x1z + (size_t)(r0 + row) * x1zp + (cc - kDH / 8) * 8;
-            const bf16_t *s2 = cc < kDH / 8 ? x2h + (size_t)(r0 + row) * x2hp + cc * 8
-                                            : x2z + (size_t)(r0 + row) * x2zp + (cc - kDH / 8) * 8;
-            st1[it] = *reinterpret_cast<const uint4 *>(s1);
-            st2[it] = *reinterpret_cast<const uint4 *>(s2);
+    int sidx = 0;  // stage of block n
+    for (int n = 0; n < nblk; ++n) {
+        // block n must have landed (the loads of block n+1 may still be in flight); the barrier
+        // also tells everyone that the stage of block n-1 is free again
+        if (n + 1 < nblk)
+            wait_vmem<C::VM_PER_BLOCK>();
+        else
+            wait_vmem<0>();
+        wg_barrier();
+        if (n + 2 < nblk) {
+            const int s2 = sidx + 2 < C::NSTAGE ? sidx + 2 : sidx + 2 - C::NSTAGE;
+            bwd_issue_block<DZ, MODE>(dma, smem_lds + s2 * C::STAGE);
         }
-        float sr = 0.f, dr = 0.f;
-        if (tid < kSB) {
-            sr = srow_src[r0 + tid];
-            dr = drow_src ? drow_src[r0 + tid] : 0.f;
-        }
-        __syncthreads();  // everyone is done with the previous block
-#pragma unroll
-        for (int it = 0; it < C::CHUNKS; ++it) {
-            const int q = min(it * 256 + tid, C::NCHUNK - 1);  // (surplus threads rewrite the last chunk)
-            const int row = q / (C::D / 8), cc = q - row * (C::D / 8);
-            *reinterpret_cast<uint4 *>(smem + C::X1_OFF + row * C::RS + cc * 16) = st1[it];
-            *reinterpret_cast<uint4 *>(smem + C::X2_OFF + row * C::RS + cc * 16) = st2[it];
-        }
-        if (tid < kSB) {
-            *reinterpret_cast<float *>(smem + C::SROW_OFF + tid * 4) = sr;
-            *reinterpret_cast<float *>(smem + C::DROW_OFF + tid * 4) = dr;
-        }
-        __syncthreads();
+        const char *st = smem + sidx * C::STAGE;
+        sidx = sidx + 1 < C::NSTAGE ? sidx + 1 : 0;
 
         // ---- S and dP blocks: [32 streamed rows] x [32 stationary rows (lanes)] ----------------
         f32x16 sacc, dpacc;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            const f32x4 sb = *reinterpret_cast<const f32x4 *>(smem + C::SROW_OFF + (8 * a + 4 * g) * 4);
-            const f32x4 db = *reinterpret_cast<const f32x4 *>(smem + C::DROW_OFF + (8 * a + 4 * g) * 4);
+            const f32x4 sb = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + (8 * a + 4 * g) * 4);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                sacc[4 * a + x] = sb[x] + slane;
-                dpacc[4 * a + x] = -(db[x] + dlane);
+            for (int x = 0; x < 4; ++x) sacc[4 * a + x] = sb[x] + slane;
+            if constexpr (C::NSC == 2) {
+                const f32x4 db = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + 1024 + (8 * a + 4 * g) * 4);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -(db[x] + dlane);
+            } else {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -dlane;
             }
         }
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(smem + C::X1_OFF + kaddr + ks * 32);
+            const char *s1 = ks < C::KSH ? st + C::X1H_OFF + ka_h + ks * 32 : st + C::X1Z_OFF + ka_z + (ks - C::KSH) * 32;
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(s1);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, y1f[ks], sacc, 0, 0, 0);
             if (kNeedDP) {
-                const bf16x8 a2 = *reinterpret_cast<const bf16x8 *>(smem + C::X2_OFF + kaddr + ks * 32);
+                const char *s2 = ks < C::KSH ? st + C::X2H_OFF + ka_h + ks * 32 : st + C::X2Z_OFF + ka_z + (ks - C::KSH) * 32;
+                const bf16x8 a2 = *reinterpret_cast<const bf16x8 *>(s2);
                 dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, y2f[ks], dpacc, 0, 0, 0);
             }
         }
@@ -201,14 +246,15 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
         const bf16x8 wf[2] = {__builtin_bit_cast(bf16x8, (u32x4){wp[0], wp[1], wp[2], wp[3]}),
                               __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]})};
         // ---- acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
-        constexpr int XOFF = MODE == FIPA_BWD_DV ? C::X2_OFF : C::X1_OFF;
 #pragma unroll
         for (int nb = 0; nb < C::NB; ++nb)
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
-                const char *src = smem + XOFF + vaddr + 16 * tt * C::RS + nb * 64;
+                const char *src = nb < C::NBH ? st + AH_OFF + va_h + 16 * tt * kHS + nb * 64
+                                              : st + AZ_OFF + va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+                const int rs = nb < C::NBH ? kHS : C::ZS;
                 const bf16x4 lo = lds_read_tr(src);
-                const bf16x4 hi = lds_read_tr(src + 8 * C::RS);
+                const bf16x4 hi = lds_read_tr(src + 8 * rs);
                 bf16x8 a;
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
@@ -239,7 +285,7 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
 template <int DZ, int MODE>
 hipError_t launch(const BwdParams &p, hipStream_t stream)
 {
-    using C = BwdCfg<DZ>;
+    using C = BwdCfg<DZ, MODE>;
     hipError_t e = hipFuncSetAttribute((const void *)fipa_bwd_kernel<DZ, MODE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
