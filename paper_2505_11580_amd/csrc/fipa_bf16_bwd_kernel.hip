@@ -17,8 +17,7 @@
 // with the transposing LDS read.
 //
 // The streamed blocks arrive in a ring of three LDS stages by direct global -> LDS loads issued
-// two blocks ahead, so the memory latency is covered by the MFMAs of the two blocks in between;
-// one barrier per block publishes the new stage and releases the oldest.
+// one block ahead; one barrier per block publishes the new stage and releases the oldest.
 #include "fipa_gfx950.h"
 
 namespace fipa {
@@ -79,6 +78,88 @@ __device__ __forceinline__ void bwd_issue_block(BwdDma<DZ, MODE> &d, unsigned st
     } else if constexpr (K < C::NIW + C::NSC) {
         dma16<C::SC_OFF + 1024 * (K - C::NIW)>(d.src[K], d.voff[K], d.step[K], stage);
         bwd_issue_block<DZ, MODE, K + 1>(d, stage);
+    }
+}
+
+struct BwdLane {
+    int ka_h, ka_z, va_h, va_z, g;  // per-lane LDS offsets inside a stage, lane half
+    float slane, dlane;             // per-stationary-row logit term and D
+};
+
+// One step of the pipeline: the small products and the weights of the block in stage `st`
+// (CUR), interleaved with the accumulation of the previous block (stage `st_prev`, weights `wf`
+// on entry) (PREV).  On exit `wf` holds the weights of the current block.
+template <int DZ, int MODE, bool CUR, bool PREV>
+__device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char *__restrict__ st_prev, const BwdLane &ln,
+                                         const bf16x8 (&y1f)[BwdCfg<DZ, MODE>::KS],
+                                         const bf16x8 (&y2f)[MODE != FIPA_BWD_DV ? BwdCfg<DZ, MODE>::KS : 1],
+                                         f32x16 (&acc)[BwdCfg<DZ, MODE>::NB], bf16x8 (&wf)[2], float &wsum)
+{
+    using C = BwdCfg<DZ, MODE>;
+    constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
+    constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;  // tile the accumulation reads
+    constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
+    f32x16 sacc, dpacc;
+    if constexpr (CUR) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const f32x4 sb = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + (8 * a + 4 * ln.g) * 4);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) sacc[4 * a + x] = sb[x] + ln.slane;
+            if constexpr (C::NSC == 2) {
+                const f32x4 db = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + 1024 + (8 * a + 4 * ln.g) * 4);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -(db[x] + ln.dlane);
+            } else {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -ln.dlane;
+            }
+        }
+    }
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) {
+        if constexpr (CUR) {
+            // S (and dP) of the current block: [32 streamed rows] x [32 stationary rows (lanes)]
+            const char *s1 = ks < C::KSH ? st + C::X1H_OFF + ln.ka_h + ks * 32 : st + C::X1Z_OFF + ln.ka_z + (ks - C::KSH) * 32;
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(s1);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, y1f[ks], sacc, 0, 0, 0);
+            if constexpr (kNeedDP) {
+                const char *s2 = ks < C::KSH ? st + C::X2H_OFF + ln.ka_h + ks * 32 : st + C::X2Z_OFF + ln.ka_z + (ks - C::KSH) * 32;
+                const bf16x8 a2 = *reinterpret_cast<const bf16x8 *>(s2);
+                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, y2f[ks], dpacc, 0, 0, 0);
+            }
+        }
+        if constexpr (PREV) {
+            // acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
+            const int nb = ks >> 1, tt = ks & 1;
+            const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
+                                          : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+            const int rs = nb < C::NBH ? kHS : C::ZS;
+            const bf16x4 lo = lds_read_tr(src);
+            const bf16x4 hi = lds_read_tr(src + 8 * rs);
+            bf16x8 a;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                a[x] = lo[x];
+                a[4 + x] = hi[x];
+            }
+            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wf[tt], acc[nb], 0, 0, 0);
+        }
+    }
+    if constexpr (CUR) {
+        // weights of the accumulating product: P (DV) or dS = P (dP - D) (DQ, DK)
+        unsigned wp[8];
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            float w0 = __builtin_amdgcn_exp2f(sacc[r]), w1 = __builtin_amdgcn_exp2f(sacc[r + 1]);
+            if constexpr (kNeedDP) {
+                w0 *= dpacc[r];
+                w1 *= dpacc[r + 1];
+            }
+            wp[r >> 1] = pack_pair(w0, w1, wsum);
+        }
+        wf[0] = __builtin_bit_cast(bf16x8, (u32x4){wp[0], wp[1], wp[2], wp[3]});
+        wf[1] = __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]});
     }
 }
 
@@ -156,7 +237,6 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     }
     const unsigned smem_lds = lds_address(smem);
     if (nblk > 0) bwd_issue_block<DZ, MODE>(dma, smem_lds);
-    if (nblk > 1) bwd_issue_block<DZ, MODE>(dma, smem_lds + C::STAGE);
 
     // stationary fragments: features 16*ks + 8*g .. +7 of row srow
     bf16x8 y1f[C::KS], y2f[kNeedDP ? C::KS : 1];
@@ -186,84 +266,32 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     const int ka_h = li * kHS + g * 16, ka_z = li * C::ZS + g * 16;                    // row reads (small products)
     const int va_h = (4 * g + e4) * kHS + (16 * grp2 + 4 * j4) * 2;                     // transposing reads
     const int va_z = (4 * g + e4) * C::ZS + (16 * grp2 + 4 * j4) * 2;
-    constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;               // tile the accumulation reads
-    constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
 
-    int sidx = 0;  // stage of block n
+    // Software pipeline over the streamed blocks: iteration n forms the small products S and dP
+    // of block n and, interleaved with them, accumulates block n-1 with the weights computed
+    // one iteration earlier -- two independent streams of MFMAs, so the matrix pipe does not
+    // wait on either's operands.  The weights of block n follow.  Blocks n-1 and n are resident,
+    // block n+1 is on its way into the third stage.
+    bf16x8 wf[2] = {};         // weights of the previous block (B operands of the accumulation)
+    BwdLane ln;
+    ln.ka_h = ka_h; ln.ka_z = ka_z; ln.va_h = va_h; ln.va_z = va_z; ln.g = g; ln.slane = slane; ln.dlane = dlane;
+    int sidx = 0;              // stage of block n
+    const char *st_prev = smem;
     for (int n = 0; n < nblk; ++n) {
-        // block n must have landed (the loads of block n+1 may still be in flight); the barrier
-        // also tells everyone that the stage of block n-1 is free again
-        if (n + 1 < nblk)
-            wait_vmem<C::VM_PER_BLOCK>();
-        else
-            wait_vmem<0>();
-        wg_barrier();
-        if (n + 2 < nblk) {
-            const int s2 = sidx + 2 < C::NSTAGE ? sidx + 2 : sidx + 2 - C::NSTAGE;
-            bwd_issue_block<DZ, MODE>(dma, smem_lds + s2 * C::STAGE);
-        }
         const char *st = smem + sidx * C::STAGE;
+        // block n must have landed; the barrier also tells everyone that the stage of block n-2
+        // is free again
+        wait_vmem<0>();
+        wg_barrier();
         sidx = sidx + 1 < C::NSTAGE ? sidx + 1 : 0;
-
-        // ---- S and dP blocks: [32 streamed rows] x [32 stationary rows (lanes)] ----------------
-        f32x16 sacc, dpacc;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const f32x4 sb = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + (8 * a + 4 * g) * 4);
-#pragma unroll
-            for (int x = 0; x < 4; ++x) sacc[4 * a + x] = sb[x] + slane;
-            if constexpr (C::NSC == 2) {
-                const f32x4 db = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + 1024 + (8 * a + 4 * g) * 4);
-#pragma unroll
-                for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -(db[x] + dlane);
-            } else {
-#pragma unroll
-                for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -dlane;
-            }
-        }
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const char *s1 = ks < C::KSH ? st + C::X1H_OFF + ka_h + ks * 32 : st + C::X1Z_OFF + ka_z + (ks - C::KSH) * 32;
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(s1);
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, y1f[ks], sacc, 0, 0, 0);
-            if (kNeedDP) {
-                const char *s2 = ks < C::KSH ? st + C::X2H_OFF + ka_h + ks * 32 : st + C::X2Z_OFF + ka_z + (ks - C::KSH) * 32;
-                const bf16x8 a2 = *reinterpret_cast<const bf16x8 *>(s2);
-                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, y2f[ks], dpacc, 0, 0, 0);
-            }
-        }
-        // ---- weights of the accumulating product: P (DV) or dS = P (dP - D) (DQ, DK) -----------
-        unsigned wp[8];
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-            float w0 = __builtin_amdgcn_exp2f(sacc[r]), w1 = __builtin_amdgcn_exp2f(sacc[r + 1]);
-            if (kNeedDP) {
-                w0 *= dpacc[r];
-                w1 *= dpacc[r + 1];
-            }
-            wp[r >> 1] = pack_pair(w0, w1, wsum);
-        }
-        const bf16x8 wf[2] = {__builtin_bit_cast(bf16x8, (u32x4){wp[0], wp[1], wp[2], wp[3]}),
-                              __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]})};
-        // ---- acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
-#pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb)
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                const char *src = nb < C::NBH ? st + AH_OFF + va_h + 16 * tt * kHS + nb * 64
-                                              : st + AZ_OFF + va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
-                const int rs = nb < C::NBH ? kHS : C::ZS;
-                const bf16x4 lo = lds_read_tr(src);
-                const bf16x4 hi = lds_read_tr(src + 8 * rs);
-                bf16x8 a;
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    a[x] = lo[x];
-                    a[4 + x] = hi[x];
-                }
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wf[tt], acc[nb], 0, 0, 0);
-            }
+        if (n + 1 < nblk) bwd_issue_block<DZ, MODE>(dma, smem_lds + sidx * C::STAGE);
+        if (n == 0)
+            bwd_step<DZ, MODE, true, false>(st, st_prev, ln, y1f, y2f, acc, wf, wsum);
+        else
+            bwd_step<DZ, MODE, true, true>(st, st_prev, ln, y1f, y2f, acc, wf, wsum);
+        st_prev = st;
     }
+    if (nblk > 0) bwd_step<DZ, MODE, false, true>(st_prev, st_prev, ln, y1f, y2f, acc, wf, wsum);
 
     // ---- write acc^T: row srow, columns 32*nb + 8*(r/4) + 4*g + r%4 -------------------------------
     float *orow = p.out + ((size_t)bh * p.Lp + srow) * C::D;
