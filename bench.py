@@ -48,6 +48,38 @@ def cpu_baseline(inp, flops_per_pair, budget_s=12.0):
     }
 
 
+def backward_leg(workload, steps=10, warmup=3):
+    """fipa_backward (recomputation of the lifted forward + the three gradient kernels + unpack) on
+    the gradient workload; reported beside the headline forward number, not part of `value`."""
+    import torch
+    from paper_2505_11580_amd import binding, workloads
+    inp = workloads.make_inputs(workload, with_grads=True)
+    dims = inp["dims"]
+    desc, dev = binding.upload(inp)
+    out = binding.alloc_outputs(desc)
+    grads = binding.alloc_grads(desc)
+    binding.forward(desc, dev, out)
+    for _ in range(warmup):
+        binding.backward(desc, dev, out, grads)
+    torch.cuda.synchronize()
+    binding.fipa_profile_begin(steps)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        binding.backward(desc, dev, out, grads)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    stage_ms, _ = binding.fipa_profile_end()
+    pairs = workloads.valid_pairs(inp)
+    fpp = workloads.bwd_flops_per_pair(dims)
+    return {
+        "workload": "workload %d: B=%d L=%d H=%d cz=%d r=%d, bf16" % (workload, dims["B"], dims["L"], dims["H"],
+                                                                    dims["cz"], dims["r"]),
+        "ms_per_call": ms, "value": pairs * fpp / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "valid_pairs": pairs, "flops_per_pair": fpp, "steps": steps,
+        "stage_ms": {"recompute_forward": stage_ms[0], "gradient_kernels": stage_ms[1], "unpack": stage_ms[2]},
+    }
+
+
 def calibrate_copy(nbytes=256 << 20):
     """A plain elementwise copy of known size (reads nbytes, writes nbytes), so that a counter run of
     this script sees a kernel whose HBM traffic is known next to the attention kernel."""
@@ -71,6 +103,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="workload index (2 = the L=2048 headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true", help="skip the fipa_backward leg (workload 4)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB copy kernel (for scaling hardware counters)")
     args = ap.parse_args()
@@ -139,6 +172,10 @@ def main():
     }
     if args.calibrate_copy:
         calibrate_copy()
+    if not args.no_backward:
+        del out, dev
+        torch.cuda.empty_cache()
+        result["backward"] = backward_leg(4)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, fpp)
     print(json.dumps(result), flush=True)
