@@ -175,7 +175,8 @@ __device__ __forceinline__ void issue_block(Dma<DZ> &d, unsigned stage)
     }
 }
 
-// After the block with the highest index has been requested the sequence continues at block 0.
+// After the last block in walking direction has been requested the sequence continues at the
+// other end (the steps are signed).
 template <int DZ>
 __device__ __forceinline__ void dma_wrap(Dma<DZ> &d, int nblk)
 {
@@ -369,24 +370,53 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
     sacc = snew;
 }
 
+// Accesses to the exchange buffer of the key-range split: 16-byte buffer accesses with the sc1
+// cache-policy bit, which makes a store write through to, and a load read from, the device's
+// coherence point instead of the non-coherent caches, so that a part sees what a part on
+// another compute unit (or XCD) wrote once that part's stores have completed.
+constexpr int kXchgPolicy = 16;  // sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t xchg_resource(float *base)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7fffffff, 0x00020000);  // raw dword buffer
+}
+__device__ __forceinline__ void xchg_store(__amdgpu_buffer_rsrc_t rs, int off, f32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, off, 0, kXchgPolicy);
+}
+__device__ __forceinline__ f32x4 xchg_load(__amdgpu_buffer_rsrc_t rs, int off)
+{
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, kXchgPolicy));
+}
+
 template <int DZ, bool FUSED>
 __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p)
 {
     using C = AttnCfg<DZ>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles
-    // so that the query tiles of one (batch, head) share that XCD's L2 copy of k^ and v^.
-    const int chunk = (p.total_tiles + 7) / 8;
-    const int logical = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
-    if (logical >= p.total_tiles) return;
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of work
+    // units so that the query tiles of one (batch, head) share that XCD's L2 copy of k^ and v^.
+    // The first plan.full workgroups take whole tiles; the others take one of the plan.S key-range
+    // parts of a remaining tile (the parts of a tile are neighbours in the launch order).
+    int logical, part = 0, tile_local = 0, nparts = 1;
+    if ((int)blockIdx.x < p.plan.full) {
+        logical = (blockIdx.x % 8) * (p.plan.full / 8) + blockIdx.x / 8;
+    } else {
+        nparts = p.plan.S;
+        const int u = blockIdx.x - p.plan.full, n_units = p.plan.rem * nparts;
+        if (u >= n_units) return;
+        const int lin = n_units % 8 == 0 ? (u % 8) * (n_units / 8) + u / 8 : u;
+        tile_local = lin / nparts;
+        part = lin - tile_local * nparts;
+        logical = p.plan.full + tile_local;
+    }
     const int bh = logical / p.nQT, qt = logical - bh * p.nQT;
     const int b = bh / p.H;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, g = lane >> 5;
     const int kvlen = p.kvlen[b];
-    const int nblk = (kvlen + kBlk - 1) / kBlk;
+    const int nkb = (kvlen + kBlk - 1) / kBlk;      // key blocks of this chain
     const int irow = qt * kTileQ + wave * 32 + li;  // < Lp always
 
     // ---- direct global->LDS loads ------------------------------------------------------------
@@ -400,7 +430,17 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // so the reference maximum is found in the first blocks and is rarely raised afterwards.
     // (The staggered starts also spread the tiles of a head over different blocks at any one
     // time; visiting the blocks in the same order everywhere measured slower.)
-    const int first_blk = min(qt * (kTileQ / kBlk), max(nblk - 1, 0));
+    // A key-range part takes its share of that rotated sequence: positions pos0 .. pos0 + nblk - 1.
+    const int pos0 = part * nkb / nparts;
+    const int nblk = (part + 1) * nkb / nparts - pos0;  // key blocks this workgroup processes
+    // A part walks its range away from the diagonal too: upwards from its first position when
+    // that end is the nearer one (always so for a whole tile), downwards from its last otherwise;
+    // a range that approached the diagonal would raise the reference at every block.
+    const bool downwards = pos0 > nkb - (pos0 + nblk);
+    const int dir = downwards ? -1 : 1;
+    int first_blk = min(qt * (kTileQ / kBlk), max(nkb - 1, 0)) + (downwards ? pos0 + nblk - 1 : pos0);
+    if (first_blk >= nkb) first_blk -= nkb;  // (nkb = 0: stays 0 and is never used)
+    const int wrap_at = downwards ? -1 : nkb, wrap_to = downwards ? nkb - 1 : 0;
 
     Dma<DZ> dma;
     dma.wave_lds = 1024u * wave;
@@ -419,16 +459,27 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             const int cols = isz ? DZ / 8 : kDH / 8;          // 16-byte columns of a global row
             const int s = 64 * (i - first) + lane;
             const int row = s / spr, col = s - row * spr;
-            dma.step[k] = kBlk * cols * 16;
+            dma.step[k] = dir * kBlk * cols * 16;
             dma.src[k] = isz ? Z2b : (isk ? Khb : Vhb);
             // one block before the first block: every request advances the offset first
-            dma.voff[k] = ((row < kBlk && col < cols) ? row * (cols * 16) + col * 16 : 0) + (first_blk - 1) * dma.step[k];
+            dma.voff[k] = ((row < kBlk && col < cols) ? row * (cols * 16) + col * 16 : 0) + (first_blk * dir - 1) * dma.step[k];
             // (entry wave + 4k lands (wave + 4k) KiB into the stage; a surplus entry refetches
             // entry 0 into the unused KiB that the stage keeps for it)
         }
-        dma.step[C::NIW] = kBlk * 4;
+        dma.step[C::NIW] = dir * kBlk * 4;
         dma.src[C::NIW] = reinterpret_cast<const char *>(p.kbias + (size_t)bh * p.Lp);
-        dma.voff[C::NIW] = min(lane, 7) * 16 + (first_blk - 1) * dma.step[C::NIW];
+        dma.voff[C::NIW] = min(lane, 7) * 16 + (first_blk * dir - 1) * dma.step[C::NIW];
+        if (downwards) {
+            // the hardware adds the per-lane offset as an unsigned number: when walking downwards
+            // keep it positive over the whole walk (at most nkb + 4 requests) by moving a bias
+            // from the offset into the base
+#pragma unroll
+            for (int k = 0; k <= C::NIW; ++k) {
+                const int bias = -(nkb + 8) * dma.step[k];
+                dma.voff[k] += bias;
+                dma.src[k] -= bias;
+            }
+        }
     }
 
     const unsigned smem_lds = lds_address(smem);
@@ -440,12 +491,12 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         // end of a short sequence the requests simply go round again: every stage they touch is free.)
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            if (next_blk == nblk) {
-                dma_wrap<DZ>(dma, nblk);
-                next_blk = 0;
+            if (next_blk == wrap_at) {
+                dma_wrap<DZ>(dma, nkb);
+                next_blk = wrap_to;
             }
             issue_block<DZ>(dma, smem_lds + i * C::STAGE);
-            ++next_blk;
+            next_blk += dir;
         }
     }
 
@@ -472,12 +523,12 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             if (nblk > 0) {
 #pragma unroll
                 for (int i = 2; i < 4; ++i) {
-                    if (next_blk == nblk) {
-                        dma_wrap<DZ>(dma, nblk);
-                        next_blk = 0;
+                    if (next_blk == wrap_at) {
+                        dma_wrap<DZ>(dma, nkb);
+                        next_blk = wrap_to;
                     }
                     issue_block<DZ>(dma, smem_lds + i * C::STAGE);
-                    ++next_blk;
+                    next_blk += dir;
                 }
             }
         } else {
@@ -542,12 +593,12 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             // blocks 2 and 3 of the sequence (the steady loop waits for them)
 #pragma unroll
             for (int i = 2; i < 4; ++i) {
-                if (next_blk == nblk) {
-                    dma_wrap<DZ>(dma, nblk);
-                    next_blk = 0;
+                if (next_blk == wrap_at) {
+                    dma_wrap<DZ>(dma, nkb);
+                    next_blk = wrap_to;
                 }
                 issue_block<DZ>(dma, smem_lds + i * C::STAGE);
-                ++next_blk;
+                next_blk += dir;
             }
         }
 #pragma unroll
@@ -573,11 +624,11 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         const int s1 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
         const int s2 = s0 + 2 < C::NSTAGE ? s0 + 2 : s0 + 2 - C::NSTAGE;
         const int s4 = s0 + 4 < C::NSTAGE ? s0 + 4 : s0 + 4 - C::NSTAGE;
-        if (next_blk == nblk) {
-            dma_wrap<DZ>(dma, nblk);
-            next_blk = 0;
+        if (next_blk == wrap_at) {
+            dma_wrap<DZ>(dma, nkb);
+            next_blk = wrap_to;
         }
-        ++next_blk;
+        next_blk += dir;
         steady_iteration<DZ>(w, pf, sacc, fr, smem + s0 * C::STAGE, smem + s2 * C::STAGE, smem + s1 * C::STAGE,
                              dma, smem_lds + s4 * C::STAGE);
         s0 = s1;
@@ -603,13 +654,13 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         for (int nb = 0; nb < C::NB; ++nb) pv_block<DZ>(w, st, pf, nb);
     }
 
-    const float l_tot = w.l_run + __shfl_xor(w.l_run, 32);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    const float lse2 = l_tot > 0.f ? w.m_ref + __log2f(l_tot) : -INFINITY;
+    float l_tot = w.l_run + __shfl_xor(w.l_run, 32);
     f32x16(&oacc)[C::NB] = w.oacc;
 
     if constexpr (!FUSED) {
         // write O^ (row irow, columns 32*nb + 8*(r/4) + 4*g + r%4) and the log2 LSE
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        const float lse2 = l_tot > 0.f ? w.m_ref + __log2f(l_tot) : -INFINITY;
         float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::DV;
 #pragma unroll
         for (int nb = 0; nb < C::NB; ++nb)
@@ -623,110 +674,211 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         if (g == 0) p.lse2[(size_t)bh * p.Lp + irow] = lse2;
     } else {
         // ---- split, inverse frame, z1 contraction (Algorithm 1 steps 8-9, Eq. 4); c = 16, Pv = 8
+        // First everything that is linear in the accumulator, still unnormalised:
+        //   the scalar columns, the global points (hi + lo parts), and the contraction with z1.
         constexpr int c = 16, Pv = 8;
-        if (irow >= p.L) return;
-        const int h = bh - b * p.H;
-        const bool valid = (p.mask ? p.mask[(size_t)b * p.L + irow] != 0 : true) && l_tot > 0.f;
-        const float sc = valid ? inv : 0.f;
-        const size_t row = ((size_t)b * p.L + irow) * p.H + h;
-        // scalar part: columns 8a + 4g + x, a = 0, 1
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            f32x4 out;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) out[x] = oacc[0][4 * a + x] * sc;
-            *reinterpret_cast<f32x4 *>(p.o + row * c + 8 * a + 4 * g) = out;
-        }
+        constexpr int NZB = C::NB - C::NBH;  // 32-column blocks of the pair part
+        const bool in_range = irow < p.L;
+        const int irow_c = min(irow, p.L - 1);  // rows past the end compute on a valid address and store nothing
+        const int cz = p.cz;
+        const int bps = cz / 32;                // 32-column blocks per factor slice (cz >= 32)
         // point part: this half owns points 4g .. 4g+3, hi parts in slots u = 0..11, lo parts in
         // slots 12..23; slot u sits in column 16 + 8*(u/4) + 4g + u%4 (see v_pt_col)
+        float Gv[12];
+#pragma unroll
+        for (int u = 0; u < 12; ++u) {
+            const int dh = 16 + 8 * (u >> 2) + (u & 3);  // column for g = 0; g = 1 adds 4
+            const int dl = 16 + 8 * ((u + 12) >> 2) + ((u + 12) & 3);
+            const float hi = oacc[dh >> 5][4 * ((dh & 31) >> 3) + (dh & 3)];
+            const float lo = oacc[dl >> 5][4 * ((dl & 31) >> 3) + (dl & 3)];
+            Gv[u] = hi + lo;
+        }
+        // pair part: o~[d'] = sum_rho z1[rho, d'] * U[rho, d']; the lane holds columns 8a + 4g + x
         {
-            const float *R = p.rot + ((size_t)b * p.L + irow) * 9;
-            const float *tr = p.trans + ((size_t)b * p.L + irow) * 3;
+            const bf16_t *z1 = p.z1 + ((size_t)b * p.L + irow_c) * DZ;
+#pragma unroll
+            for (int zb = 0; zb < NZB; ++zb)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const int dz = 32 * zb + 8 * a + 4 * g;  // column in [0, DZ)
+                    const uint2 zraw = *reinterpret_cast<const uint2 *>(z1 + dz);
+                    const bf16_t *zb16 = reinterpret_cast<const bf16_t *>(&zraw);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) oacc[C::NBH + zb][4 * a + x] *= bf2f(zb16[x]);
+                }
+            // sum over rho: column dz of U belongs to output d' = dz % cz.  For cz >= 32 the sums
+            // end up in blocks 0 .. bps-1 of the pair part.
+            if (cz >= 32) {
+#pragma unroll
+                for (int zb = 0; zb < NZB; ++zb) {
+                    if (zb >= bps) break;
+#pragma unroll
+                    for (int z2_ = zb + 1; z2_ < NZB; ++z2_)
+                        if ((z2_ - zb) % bps == 0)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) oacc[C::NBH + zb][r] += oacc[C::NBH + z2_][r];
+                }
+            }
+        }
+
+        // ---- key-range split: leave this part's unnormalised row in memory; the part that
+        // arrives last merges all parts of the tile.  Every exchanged word is written and read
+        // with device-scope atomic accesses (which go to the coherence point, not through the
+        // non-coherent caches); a part's words are complete (vmcnt = 0) before it takes its ticket.
+        if (nparts > 1) {
+            // per lane: 2 groups of scalars, 3 of point coordinates, 4 per pair block, 1 of (m, l)
+            constexpr int kGroups = 6 + 4 * NZB;
+            // wave-uniform base: this wave's rows in part 0 of the tile; byte offsets within 32 bits
+            const __amdgpu_buffer_rsrc_t xr =
+                xchg_resource(p.partial + ((size_t)tile_local * nparts * 4 + wave) * (kGroups * 64 * 4));
+            constexpr int kPartBytes = 4 * kGroups * 64 * 16;
+            const int mine = part * kPartBytes + lane * 16;
+            xchg_store(xr, mine + 0 * 1024, (f32x4){oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]});
+            xchg_store(xr, mine + 1 * 1024, (f32x4){oacc[0][4], oacc[0][5], oacc[0][6], oacc[0][7]});
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+                xchg_store(xr, mine + (2 + a) * 1024, (f32x4){Gv[4 * a], Gv[4 * a + 1], Gv[4 * a + 2], Gv[4 * a + 3]});
+            xchg_store(xr, mine + 5 * 1024, (f32x4){w.m_ref, l_tot, 0.f, 0.f});
+#pragma unroll
+            for (int zb = 0; zb < NZB; ++zb) {
+                if (zb >= bps) break;
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    xchg_store(xr, mine + (6 + 4 * zb + a) * 1024,
+                               (f32x4){oacc[C::NBH + zb][4 * a], oacc[C::NBH + zb][4 * a + 1],
+                                       oacc[C::NBH + zb][4 * a + 2], oacc[C::NBH + zb][4 * a + 3]});
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            int ticket = 0;
+            if (lane == 0)
+                ticket = __hip_atomic_fetch_add(p.counters + tile_local * 4 + wave, 1, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+            ticket = __builtin_amdgcn_readfirstlane(ticket);
+            if (ticket != nparts - 1) return;
+            asm volatile("" ::: "memory");
+            // Merge all parts in the order of their key ranges, this wave's own included (read
+            // back), so that the result does not depend on which part happened to come last.
+            float m_acc = -INFINITY;
+            l_tot = 0.f;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) oacc[0][r] = 0.f;
+#pragma unroll
+            for (int u = 0; u < 12; ++u) Gv[u] = 0.f;
+#pragma unroll
+            for (int zb = 0; zb < NZB; ++zb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[C::NBH + zb][r] = 0.f;
+            for (int q = 0; q < nparts; ++q) {
+                const int other = q * kPartBytes + lane * 16;
+                f32x4 head[6], pair[NZB][4];
+#pragma unroll
+                for (int k = 0; k < 6; ++k) head[k] = xchg_load(xr, other + k * 1024);
+#pragma unroll
+                for (int zb = 0; zb < NZB; ++zb) {
+                    if (zb >= bps) break;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) pair[zb][a] = xchg_load(xr, other + (6 + 4 * zb + a) * 1024);
+                }
+                const float m_o = head[5][0], l_o = head[5][1];
+                const float m_new = fmaxf(m_acc, m_o);
+                const float a_own = m_acc == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_acc - m_new);
+                const float a_oth = m_o == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_o - m_new);
+                m_acc = m_new;
+                l_tot = l_tot * a_own + l_o * a_oth;
+#pragma unroll
+                for (int r = 0; r < 8; ++r) oacc[0][r] = oacc[0][r] * a_own + head[r >> 2][r & 3] * a_oth;
+#pragma unroll
+                for (int u = 0; u < 12; ++u) Gv[u] = Gv[u] * a_own + head[2 + (u >> 2)][u & 3] * a_oth;
+#pragma unroll
+                for (int zb = 0; zb < NZB; ++zb) {
+                    if (zb >= bps) break;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        oacc[C::NBH + zb][r] = oacc[C::NBH + zb][r] * a_own + pair[zb][r >> 2][r & 3] * a_oth;
+                }
+            }
+            w.m_ref = m_acc;
+        }
+
+        // ---- normalise, apply the inverse frame, store ---------------------------------------------
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        const float lse2 = l_tot > 0.f ? w.m_ref + __log2f(l_tot) : -INFINITY;
+        const int h = bh - b * p.H;
+        const bool valid = (p.mask ? p.mask[(size_t)b * p.L + irow_c] != 0 : true) && l_tot > 0.f;
+        const float sc = valid ? inv : 0.f;
+        const size_t row = ((size_t)b * p.L + irow_c) * p.H + h;
+        if (in_range) {
+            // scalar part: columns 8a + 4g + x, a = 0, 1
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                f32x4 out;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) out[x] = oacc[0][4 * a + x] * sc;
+                *reinterpret_cast<f32x4 *>(p.o + row * c + 8 * a + 4 * g) = out;
+            }
+        }
+        {
+            const float *R = p.rot + ((size_t)b * p.L + irow_c) * 9;
+            const float *tr = p.trans + ((size_t)b * p.L + irow_c) * 3;
             float Rm[9], tc[3];
 #pragma unroll
             for (int a = 0; a < 9; ++a) Rm[a] = R[a];
 #pragma unroll
             for (int a = 0; a < 3; ++a) tc[a] = tr[a] - p.cen[4 * b + a];
-            float Gv[12];
-#pragma unroll
-            for (int u = 0; u < 12; ++u) {
-                const int dh = 16 + 8 * (u >> 2) + (u & 3);  // column for g = 0; g = 1 adds 4
-                const int dl = 16 + 8 * ((u + 12) >> 2) + ((u + 12) & 3);
-                const float hi = oacc[dh >> 5][4 * ((dh & 31) >> 3) + (dh & 3)];
-                const float lo = oacc[dl >> 5][4 * ((dl & 31) >> 3) + (dl & 3)];
-                Gv[u] = (hi + lo) * inv;
-            }
             float outp[12];
 #pragma unroll
             for (int pp = 0; pp < 4; ++pp) {
-                const float rx = Gv[3 * pp] - tc[0], ry = Gv[3 * pp + 1] - tc[1], rz = Gv[3 * pp + 2] - tc[2];
+                const float rx = Gv[3 * pp] * inv - tc[0], ry = Gv[3 * pp + 1] * inv - tc[1],
+                            rz = Gv[3 * pp + 2] * inv - tc[2];
 #pragma unroll
                 for (int x = 0; x < 3; ++x) {
                     const float val = Rm[x] * rx + Rm[3 + x] * ry + Rm[6 + x] * rz;  // R^T
                     outp[3 * pp + x] = valid ? val : 0.f;
                 }
             }
-            float *dst = p.o_pts + row * (Pv * 3) + 12 * g;
+            if (in_range) {
+                float *dst = p.o_pts + row * (Pv * 3) + 12 * g;
 #pragma unroll
-            for (int a = 0; a < 3; ++a)
-                *reinterpret_cast<f32x4 *>(dst + 4 * a) =
-                    (f32x4){outp[4 * a], outp[4 * a + 1], outp[4 * a + 2], outp[4 * a + 3]};
+                for (int a = 0; a < 3; ++a)
+                    *reinterpret_cast<f32x4 *>(dst + 4 * a) =
+                        (f32x4){outp[4 * a], outp[4 * a + 1], outp[4 * a + 2], outp[4 * a + 3]};
+            }
         }
-        // pair part: o~[d'] = sum_rho z1[rho, d'] * U[rho, d']; the lane holds columns 8a + 4g + x
-        {
-            const int cz = p.cz;
-            const bf16_t *z1 = p.z1 + ((size_t)b * p.L + irow) * DZ;
+        if (in_range) {
             float *dst = p.o_pair + row * cz;
-#pragma unroll
-            for (int nb = C::NBH; nb < C::NB; ++nb)
-#pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const int dz = 32 * (nb - C::NBH) + 8 * a + 4 * g;  // column in [0, DZ)
-                    const uint2 zraw = *reinterpret_cast<const uint2 *>(z1 + dz);
-                    const bf16_t *zb = reinterpret_cast<const bf16_t *>(&zraw);
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) oacc[nb][4 * a + x] *= bf2f(zb[x]) * sc;
-                }
-            // sum over rho: column dz of U belongs to output d' = dz % cz
             if (cz >= 32) {
-                const int bps = cz / 32;  // 32-column blocks per factor slice
 #pragma unroll
-                for (int zb_ = 0; zb_ < C::NB - C::NBH; ++zb_) {
-                    if (zb_ >= bps) break;
+                for (int zb = 0; zb < NZB; ++zb) {
+                    if (zb >= bps) break;
 #pragma unroll
                     for (int a = 0; a < 4; ++a) {
                         f32x4 out;
 #pragma unroll
-                        for (int x = 0; x < 4; ++x) out[x] = oacc[C::NBH + zb_][4 * a + x];
-#pragma unroll
-                        for (int z2_ = zb_ + 1; z2_ < C::NB - C::NBH; ++z2_)
-                            if ((z2_ - zb_) % bps == 0)
-#pragma unroll
-                                for (int x = 0; x < 4; ++x) out[x] += oacc[C::NBH + z2_][4 * a + x];
-                        *reinterpret_cast<f32x4 *>(dst + 32 * zb_ + 8 * a + 4 * g) = out;
+                        for (int x = 0; x < 4; ++x) out[x] = oacc[C::NBH + zb][4 * a + x] * sc;
+                        *reinterpret_cast<f32x4 *>(dst + 32 * zb + 8 * a + 4 * g) = out;
                     }
                 }
             } else {
-                // cz in {8, 16}: slices are narrower than a block
+                // cz in {8, 16}: slices are narrower than a block (such launches are never split)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
                     if (8 * a >= cz) break;
                     f32x4 out = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int nb = C::NBH; nb < C::NB; ++nb)
+                    for (int zb = 0; zb < NZB; ++zb)
 #pragma unroll
                         for (int a2 = 0; a2 < 4; ++a2) {
-                            const int dz = 32 * (nb - C::NBH) + 8 * a2;
+                            const int dz = 32 * zb + 8 * a2;
                             if (dz % cz == 8 * a)
 #pragma unroll
-                                for (int x = 0; x < 4; ++x) out[x] += oacc[nb][4 * a2 + x];
+                                for (int x = 0; x < 4; ++x) out[x] += oacc[C::NBH + zb][4 * a2 + x] * sc;
                         }
                     *reinterpret_cast<f32x4 *>(dst + 8 * a + 4 * g) = out;
                 }
             }
+            if (p.lse && g == 0)
+                p.lse[(size_t)bh * p.L + irow] = valid ? lse2 * kLn2 - p.qbias[(size_t)bh * p.Lp + irow] : 0.f;
         }
-        if (p.lse && g == 0)
-            p.lse[(size_t)bh * p.L + irow] = valid ? lse2 * kLn2 - p.qbias[(size_t)bh * p.Lp + irow] : 0.f;
     }
 }
 
@@ -737,8 +889,10 @@ hipError_t launch(const AttnParams &p, hipStream_t stream)
     hipError_t e = hipFuncSetAttribute((const void *)fipa_attn_fwd_bf16_kernel<DZ, FUSED>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
-    const int chunk = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL((fipa_attn_fwd_bf16_kernel<DZ, FUSED>), dim3(chunk * 8), dim3(256),
+    if (p.plan.full % 8 != 0 || p.plan.full + p.plan.rem != p.total_tiles || p.plan.S < 1 ||
+        (p.plan.S > 1 && (!FUSED || p.cz < 32)))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL((fipa_attn_fwd_bf16_kernel<DZ, FUSED>), dim3(p.plan.units()), dim3(256),
                        C::LDS_BYTES, stream, p);
     return hipGetLastError();
 }

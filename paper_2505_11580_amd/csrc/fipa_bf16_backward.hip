@@ -246,7 +246,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
 
     // ---- forward pack and (unfused) forward attention: lifted tensors, O^, log-sum-exp -------------
     timer.begin(0);
-    hipError_t e = launch_prep(d, a.f.trans, a.f.mask, cen, kvlen, stream);
+    hipError_t e = launch_prep(d, a.f.trans, a.f.mask, cen, kvlen, nullptr, 0, stream);
     if (e != hipSuccess) return e;
     PackParams pk;
     pk.q = (const bf16_t *)a.f.q; pk.k = (const bf16_t *)a.f.k; pk.v = (const bf16_t *)a.f.v;
@@ -273,6 +273,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     at.o = nullptr; at.o_pts = nullptr; at.o_pair = nullptr; at.lse = nullptr;
     at.B = d.B; at.L = d.L; at.Lp = w.f.Lp; at.H = d.H; at.NT = w.f.NT;
     at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.f.w_b; at.w_L = d.w_L;
+    at.plan = w.f.plan; at.partial = nullptr; at.counters = nullptr;  // (unfused: never split)
     e = launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
     if (e != hipSuccess) return e;
 

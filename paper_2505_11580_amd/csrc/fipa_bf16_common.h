@@ -50,9 +50,45 @@ __host__ __device__ __forceinline__ int v_cols_needed(int c, int Pv)
     return c + 8 * ((6 * PH + 3) / 4);
 }
 
+// Key-range split of the fused attention launch.  A launch of T query tiles runs in ceil(T/256)
+// rounds on the 256 compute units of the chip; when the last round would be at most half full,
+// its tiles are cut into S parts along the key axis (each part one workgroup), so that the last
+// round lasts about 1/S as long.  Each part reduces its accumulator to the unnormalised output
+// row (scalars, global points, z1-contracted pair part: 20 + c_z floats per lane pair instead of
+// 64 + r c_z) and leaves it in memory with its softmax reference and weight sum; the part that
+// arrives last merges them.
+struct SplitPlan {
+    int full;  // leading tiles that run whole (a multiple of 256)
+    int rem;   // remaining tiles
+    int S;     // parts per remaining tile (1 = not split)
+    int units() const { return full + rem * S; }
+};
+
+inline SplitPlan attn_split_plan(int total_tiles, int Lp, int DZ, int cz, bool fused)
+{
+    constexpr int kCU = 256;
+    SplitPlan s;
+    s.full = (total_tiles / kCU) * kCU;
+    s.rem = total_tiles - s.full;
+    s.S = 1;
+    if (fused && DZ <= 256 && cz >= 32 && s.rem > 0 && s.rem <= kCU / 2) {
+        const int by_blocks = (Lp / 32) / 4;  // at least four 32-key blocks per part
+        s.S = kCU / s.rem;
+        if (s.S > 4) s.S = 4;
+        if (s.S > by_blocks) s.S = by_blocks;
+        if (s.S < 1) s.S = 1;
+    }
+    return s;
+}
+
+// Floats one wave of one part leaves for the merge: per lane 16-byte groups -- 2 of scalars, 3 of
+// point coordinates, 1 of (reference maximum, weight sum), 4 per 32-column block of the pair part.
+inline size_t attn_partial_floats(int DZ) { return (size_t)(6 + 4 * (DZ / 32)) * 64 * 4; }
+
 struct Bf16Layout {
     int Lp, NT, DZ;
-    size_t cen, kvlen, Qh, Qz, Kh, Vh, Z2, kbias, qbias, Ohat, lse2, total;
+    SplitPlan plan;
+    size_t cen, kvlen, Qh, Qz, Kh, Vh, Z2, kbias, qbias, Ohat, lse2, partial, counters, total;
 };
 
 // with_ohat: the unfused epilogue needs the lifted output O^ in memory.
@@ -80,6 +116,10 @@ inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
     w.qbias = take(BH * w.Lp * sizeof(float));
     w.lse2 = take(BH * w.Lp * sizeof(float));
     w.Ohat = with_ohat ? take(BH * w.Lp * (size_t)(kDH + w.DZ) * sizeof(float)) : 0;
+    w.plan = attn_split_plan((int)(BH * (w.Lp / kTileQ)), w.Lp, w.DZ, d.cz, !with_ohat);
+    const bool split = w.plan.S > 1;
+    w.partial = split ? take((size_t)w.plan.rem * w.plan.S * 4 * attn_partial_floats(w.DZ) * sizeof(float)) : 0;
+    w.counters = split ? take((size_t)w.plan.rem * 4 * sizeof(int)) : 0;
     w.total = off;
     return w;
 }
@@ -110,6 +150,10 @@ struct AttnParams {
     float *o, *o_pts, *o_pair, *lse;
     int B, L, Lp, H, NT, nQT, total_tiles, cz, r;
     float w_L;
+    // key-range split (see SplitPlan): exchange buffer and one arrival counter per (split tile, wave)
+    SplitPlan plan;
+    float *partial;
+    int *counters;
 };
 
 struct EpiParams {

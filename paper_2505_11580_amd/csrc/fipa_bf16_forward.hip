@@ -15,7 +15,9 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
 
     StageTimer timer(stream);
     timer.begin(0);
-    hipError_t e = launch_prep(d, a.trans, a.mask, cen, kvlen, stream);
+    int *counters = reinterpret_cast<int *>(base + w.counters);
+    const int n_counters = w.plan.S > 1 ? w.plan.rem * 4 : 0;
+    hipError_t e = launch_prep(d, a.trans, a.mask, cen, kvlen, counters, n_counters, stream);
     if (e != hipSuccess) return e;
 
     PackParams pk;
@@ -46,6 +48,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     at.o = a.o; at.o_pts = a.o_pts; at.o_pair = a.o_pair; at.lse = a.lse;
     at.B = d.B; at.L = d.L; at.Lp = w.Lp; at.H = d.H; at.NT = w.NT;
     at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.w_b; at.w_L = d.w_L;
+    at.plan = w.plan; at.partial = (float *)(base + w.partial); at.counters = counters;
     timer.begin(1);
     e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream) : launch_attn_fwd_bf16(at, w.DZ, fused, stream);
     if (e != hipSuccess) return e;

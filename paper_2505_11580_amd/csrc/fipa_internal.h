@@ -48,8 +48,9 @@ class StageTimer {
 // result unchanged, Section 2; subtracting it keeps global coordinates small) and the number
 // of leading key slots that must be visited (1 + index of the last valid residue).
 //   cen   [B,4] floats (x, y, z, unused),  kvlen [B] ints
+// Also sets counters[0 .. n_counters) to zero (n_counters may be 0).
 hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, float *cen,
-                       int *kvlen, hipStream_t stream);
+                       int *kvlen, int *counters, int n_counters, hipStream_t stream);
 
 // fp32 direct path (fipa_f32.hip)
 size_t f32_forward_workspace(const fipa_desc &d);

@@ -1,5 +1,6 @@
 // Per-batch preparation shared by both precisions: centroid of the valid translations and
-// the key-loop bound.  One workgroup per batch element.
+// the key-loop bound.  One workgroup per batch element.  The launch also clears the arrival
+// counters of the attention kernel's key-range split, when there are any.
 #include "fipa_internal.h"
 
 namespace fipa {
@@ -7,10 +8,12 @@ namespace fipa {
 __global__ __launch_bounds__(256) void fipa_prep_kernel(const float *__restrict__ trans,
                                                         const uint8_t *__restrict__ mask, int L,
                                                         float *__restrict__ cen,
-                                                        int *__restrict__ kvlen)
+                                                        int *__restrict__ kvlen,
+                                                        int *__restrict__ counters, int n_counters)
 {
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
+    for (int i = b * 256 + tid; i < n_counters; i += gridDim.x * 256) counters[i] = 0;
     float sx = 0.f, sy = 0.f, sz = 0.f;
     int cnt = 0, last = 0;
     for (int i = tid; i < L; i += 256) {
@@ -50,10 +53,10 @@ __global__ __launch_bounds__(256) void fipa_prep_kernel(const float *__restrict_
 }
 
 hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, float *cen,
-                       int *kvlen, hipStream_t stream)
+                       int *kvlen, int *counters, int n_counters, hipStream_t stream)
 {
     hipLaunchKernelGGL(fipa_prep_kernel, dim3(d.B), dim3(256), 0, stream, trans, mask, d.L, cen,
-                       kvlen);
+                       kvlen, counters, n_counters);
     return hipGetLastError();
 }
 

@@ -68,13 +68,18 @@ def test_bf16_mask_and_garbage():
     gu.check(inp, label="bf16 scattered mask")
 
 
-@pytest.mark.parametrize("B,H,L", [(2, 4, 512), (5, 4, 512), (3, 8, 640)])
-def test_bf16_medium_ragged(B, H, L):
-    # several query tiles per head, ragged lengths down to a chain shorter than one tile
+@pytest.mark.parametrize("B,H,L", [(2, 4, 512), (5, 4, 512), (3, 8, 640), (1, 5, 640)])
+def test_bf16_key_range_split(B, H, L):
+    # few enough tiles that each is cut into 4 / 3 / 2 / 4 key-range parts whose partial rows are
+    # merged by the last part to arrive (the last shape puts the parts of a tile on different
+    # XCDs); ragged lengths leave some parts short or empty
     inp = wl.make_inputs(1, B=B, L=L, H=H, varlen=True, min_len=40)
-    gu.check(inp, label="bf16 ragged B=%d H=%d L=%d lengths=%s" % (B, H, L, list(inp["lengths"])))
-    inp = wl.make_inputs(1, B=B, L=L, H=H, trans_scale=0.05)  # spread attention: every key matters
-    gu.check(inp, label="bf16 spread B=%d H=%d L=%d" % (B, H, L))
+    gu.check(inp, label="bf16 split B=%d H=%d L=%d lengths=%s" % (B, H, L, list(inp["lengths"])))
+    inp = wl.make_inputs(1, B=B, L=L, H=H, trans_scale=0.05)  # spread attention: every part matters
+    gu.check(inp, label="bf16 split spread B=%d H=%d L=%d" % (B, H, L))
+    got = [gu.run_gpu(inp) for _ in range(3)]                 # the merge order is fixed: bit-identical reruns
+    for n in gu.NAMES + ("lse",):
+        assert np.array_equal(got[0][n], got[1][n]) and np.array_equal(got[0][n], got[2][n]), n
 
 
 def test_bf16_workload1_full():
