@@ -419,6 +419,30 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     const int nkb = (kvlen + kBlk - 1) / kBlk;      // key blocks of this chain
     const int irow = qt * kTileQ + wave * 32 + li;  // < Lp always
 
+    // A tile whose rows all lie past the last valid residue of its chain (padding of a ragged
+    // batch) has nothing to attend from: its outputs are zero by definition.
+    if (qt * kTileQ >= kvlen) {
+        if constexpr (!FUSED) {
+            float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::DV;
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    *reinterpret_cast<f32x4 *>(orow + 32 * nb + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (g == 0) p.lse2[(size_t)bh * p.Lp + irow] = -INFINITY;
+        } else if (irow < p.L && part == 0) {
+            const size_t row = ((size_t)b * p.L + irow) * p.H + (bh - b * p.H);
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int a = 0; a < 2; ++a) *reinterpret_cast<f32x4 *>(p.o + row * 16 + 8 * a + 4 * g) = zero;
+#pragma unroll
+            for (int a = 0; a < 3; ++a) *reinterpret_cast<f32x4 *>(p.o_pts + row * 24 + 12 * g + 4 * a) = zero;
+            for (int d = 4 * g; d < p.cz; d += 8) *reinterpret_cast<f32x4 *>(p.o_pair + row * p.cz + d) = zero;
+            if (p.lse && g == 0) p.lse[(size_t)bh * p.L + irow] = 0.f;
+        }
+        return;
+    }
+
     // ---- direct global->LDS loads ------------------------------------------------------------
     // A wave-wide load writes 64 consecutive 16-byte slots of a stage; the slot decides which
     // (row, 16-byte column) of the global block the lane fetches.  Slots in the row padding or

@@ -2,16 +2,19 @@
 // lifted width 576): same mathematics and register layout as the main kernel, but the output
 // accumulator of 32 x 576 fp32 per wave does not fit the register file, so the value columns are
 // cut into windows and each workgroup computes one window (recomputing S^T and the softmax).
-// Plain structure: one LDS stage filled through registers, online softmax with the running
-// maximum of Algorithm 2 (raised lazily), unfused epilogue.  First correct version for this
-// width, not pipelined.
+// Key blocks of 32 residues arrive in a ring of three LDS stages by direct global -> LDS loads
+// issued one block ahead (the z2 block is stored once and read in both roles, as in the main
+// kernel).  The loop is software pipelined over two blocks: iteration n forms S^T of block n and,
+// interleaved with it, accumulates P V of block n-1; the softmax of block n (running maximum of
+// Algorithm 2, raised lazily) follows.  Unfused epilogue.
 #include "fipa_gfx950.h"
 
 namespace fipa {
 
 namespace {
 
-constexpr int kKB = 32;      // keys per block
+constexpr int kKB = 32;              // keys per block
+constexpr int kHS = kDH * 2 + 16;    // LDS row stride (bytes) of the head-specific k^ / v^ blocks
 constexpr float kTauW = 8.f;
 
 template <int DZ, int NWIN>
@@ -21,109 +24,92 @@ struct WideCfg {
     static constexpr int NB = D / 32, NBH = kDH / 32;
     static constexpr int NBW = NB / NWIN;
     static_assert(NB % NWIN == 0, "windows must tile the value columns");
-    static constexpr int RS = D * 2 + 48;     // k^ tile row stride (bytes)
-    static constexpr int VS = kDH * 2 + 48;   // v^ head tile row stride
-    static constexpr int K_OFF = 0;
-    static constexpr int V_OFF = kKB * RS;
-    static constexpr int B_OFF = V_OFF + kKB * VS;
-    static constexpr int LDS_BYTES = B_OFF + kKB * 4;
-    static constexpr int KCH = kKB * D / 8;      // 16-byte chunks of the k^ tile
-    static constexpr int VCH = kKB * kDH / 8;    // of the v^ head tile
-    static constexpr int KCT = (KCH + 255) / 256, VCT = (VCH + 255) / 256;
+    static_assert(KS == 4 * NBW, "one P V MFMA per two S^T MFMAs");
+    static constexpr int ZS = DZ * 2 + 48;       // LDS row stride of the z2 block (conflict free for both read patterns)
+    static constexpr int Z_SPR = ZS / 16, H_SPR = kHS / 16;
+    static constexpr int NZ = (kKB * Z_SPR + 63) / 64;   // wave-wide 1 KiB loads for the z2 block
+    static constexpr int NH = (kKB * H_SPR + 63) / 64;   // for one head block
+    static constexpr int NI = NZ + 2 * NH;               // flat list: z2 | k^ head | v^ head
+    static constexpr int NIW = (NI + 3) / 4;             // per wave
+    static constexpr int Z_OFF = 0, KH_OFF = NZ * 1024, VH_OFF = (NZ + NH) * 1024;
+    static constexpr int KB_OFF = NIW * 4 * 1024;        // 32 per-key fp32 biases (a full 1 KiB load lands here)
+    static constexpr int STAGE = KB_OFF + 1024;
+    static constexpr int NSTAGE = 3;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
-template <int DZ, int NWIN>
-__global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p)
+// The direct loads of one wave (see dma16): wave w issues entries w, w+4, ... of the flat list,
+// then the bias entry; surplus entries repeat entry 0 into the spare KiB of the stage.
+template <class C>
+struct WideDma {
+    const char *src[C::NIW + 1];
+    int step[C::NIW + 1];
+    int voff[C::NIW + 1];
+    unsigned wave_lds;
+};
+
+template <class C, int K = 0>
+__device__ __forceinline__ void wide_issue_block(WideDma<C> &d, unsigned stage)
+{
+    if constexpr (K < C::NIW) {
+        dma16<4096 * K>(d.src[K], d.voff[K], d.step[K], stage + d.wave_lds);
+        wide_issue_block<C, K + 1>(d, stage);
+    } else if constexpr (K == C::NIW) {
+        dma16<C::KB_OFF>(d.src[K], d.voff[K], d.step[K], stage);
+    }
+}
+
+struct WideLane {
+    int kaddr_h, kaddr_z, vaddr_h, vaddr_z, g, win;
+};
+
+// One step of the pipeline: S^T and the softmax of the block in stage `st` (CUR), interleaved
+// with P V of the previous block (stage `st_prev`, probabilities `pf` on entry) (PREV).  On exit
+// `pf` holds the probabilities of the current block.
+template <int DZ, int NWIN, bool CUR, bool PREV>
+__device__ __forceinline__ void wide_step(const char *__restrict__ st, const char *__restrict__ st_prev, const WideLane &ln,
+                                          const bf16x8 (&qf)[WideCfg<DZ, NWIN>::KS], f32x16 (&acc)[WideCfg<DZ, NWIN>::NBW],
+                                          bf16x8 (&pf)[2], float &m_run, float &l_run)
 {
     using C = WideCfg<DZ, NWIN>;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int chunk = (p.total_tiles + 7) / 8;
-    const int logical = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
-    if (logical >= p.total_tiles) return;
-    const int win = blockIdx.y;
-    const int bh = logical / p.nQT, qt = logical - bh * p.nQT;
-    const int b = bh / p.H;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 31, g = lane >> 5;
-    const int kvlen = p.kvlen[b];
-    const int nblk = (kvlen + kKB - 1) / kKB;
-    const int irow = qt * kTileQ + wave * 32 + li;
-
-    const bf16_t *Kh = p.Kh + (size_t)bh * p.Lp * kDH, *Vh = p.Vh + (size_t)bh * p.Lp * kDH;
-    const bf16_t *Z2 = p.Z2 + (size_t)b * p.Lp * DZ;
-    const float *kbias = p.kbias + (size_t)bh * p.Lp;
-
-    bf16x8 qf[C::KS];
-    {
-        const bf16_t *qh = p.Qh + ((size_t)bh * p.Lp + irow) * kDH;
-        const bf16_t *qz = p.Qz + ((size_t)bh * p.Lp + irow) * DZ;
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const bf16_t *src = ks < C::KSH ? qh + ks * 16 + 8 * g : qz + (ks - C::KSH) * 16 + 8 * g;
-            qf[ks] = *reinterpret_cast<const bf16x8 *>(src);
-        }
-    }
-    f32x16 acc[C::NBW];
-#pragma unroll
-    for (int nb = 0; nb < C::NBW; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    const int kaddr = C::K_OFF + li * C::RS + g * 16;
-    const int l16 = lane & 15, grp2 = (lane >> 4) & 1, e4 = l16 >> 2, j4 = l16 & 3;
-    const int vaddr_z = C::K_OFF + (4 * g + e4) * C::RS + (16 * grp2 + 4 * j4) * 2 + kDH * 2;  // pair part of the k^ tile
-    const int vaddr_h = C::V_OFF + (4 * g + e4) * C::VS + (16 * grp2 + 4 * j4) * 2;
-
-    // start at the block holding the tile's own residues (see the main kernel) and wrap around
-    const int first_blk = min(qt * (kTileQ / kKB), max(nblk - 1, 0));
-    for (int n = 0; n < nblk; ++n) {
-        const int blk = first_blk + n < nblk ? first_blk + n : first_blk + n - nblk;
-        const int r0 = blk * kKB;
-        uint4 kst[C::KCT], vst[C::VCT];
-#pragma unroll
-        for (int it = 0; it < C::KCT; ++it) {
-            const int q = min(it * 256 + tid, C::KCH - 1);
-            const int row = q / (C::D / 8), cc = q - row * (C::D / 8);
-            const bf16_t *src = cc < kDH / 8 ? Kh + (size_t)(r0 + row) * kDH + cc * 8
-                                             : Z2 + (size_t)(r0 + row) * DZ + (cc - kDH / 8) * 8;
-            kst[it] = *reinterpret_cast<const uint4 *>(src);
-        }
-#pragma unroll
-        for (int it = 0; it < C::VCT; ++it) {
-            const int q = min(it * 256 + tid, C::VCH - 1);
-            vst[it] = *reinterpret_cast<const uint4 *>(Vh + (size_t)r0 * kDH + q * 8);
-        }
-        float kb = 0.f;
-        if (tid < kKB) kb = kbias[r0 + tid];
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < C::KCT; ++it) {
-            const int q = min(it * 256 + tid, C::KCH - 1);
-            const int row = q / (C::D / 8), cc = q - row * (C::D / 8);
-            *reinterpret_cast<uint4 *>(smem + C::K_OFF + row * C::RS + cc * 16) = kst[it];
-        }
-#pragma unroll
-        for (int it = 0; it < C::VCT; ++it) {
-            const int q = min(it * 256 + tid, C::VCH - 1);
-            const int row = q / (kDH / 8), cc = q - row * (kDH / 8);
-            *reinterpret_cast<uint4 *>(smem + C::V_OFF + row * C::VS + cc * 16) = vst[it];
-        }
-        if (tid < kKB) *reinterpret_cast<float *>(smem + C::B_OFF + tid * 4) = kb;
-        __syncthreads();
-
-        f32x16 sacc;
+    f32x16 sacc;
+    if constexpr (CUR) {
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            const f32x4 bias = *reinterpret_cast<const f32x4 *>(smem + C::B_OFF + (8 * a + 4 * g) * 4);
+            const f32x4 bias = *reinterpret_cast<const f32x4 *>(st + C::KB_OFF + (8 * a + 4 * ln.g) * 4);
 #pragma unroll
             for (int x = 0; x < 4; ++x) sacc[4 * a + x] = bias[x];
         }
+    }
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(smem + kaddr + ks * 32);
+    for (int ks = 0; ks < C::KS; ++ks) {
+        if constexpr (CUR) {
+            const char *src = ks < C::KSH ? st + C::KH_OFF + ln.kaddr_h + ks * 32 : st + C::Z_OFF + ln.kaddr_z + (ks - C::KSH) * 32;
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(src);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
         }
+        if constexpr (PREV) {
+            if ((ks & 1) == 0) {
+                const int i = ks >> 1, nbw = i >> 1, tt = i & 1;
+                const int nb = ln.win * C::NBW + nbw;  // global 32-column block (win is uniform)
+                const bool head = nb < C::NBH;
+                const char *src = head ? st_prev + C::VH_OFF + ln.vaddr_h + 16 * tt * kHS + nb * 64
+                                       : st_prev + C::Z_OFF + ln.vaddr_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+                const int rs = head ? kHS : C::ZS;
+                const bf16x4 lo = lds_read_tr(src);
+                const bf16x4 hi = lds_read_tr(src + 8 * rs);
+                bf16x8 a;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    a[x] = lo[x];
+                    a[4 + x] = hi[x];
+                }
+                acc[nbw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt], acc[nbw], 0, 0, 0);
+            }
+        }
+    }
+    if constexpr (CUR) {
         float mx = sacc[0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
@@ -143,29 +129,132 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
 #pragma unroll
         for (int r = 0; r < 16; r += 2)
             pp[r >> 1] = pack_pair(__builtin_amdgcn_exp2f(sacc[r] - m_use), __builtin_amdgcn_exp2f(sacc[r + 1] - m_use), l_run);
-        const bf16x8 pf[2] = {__builtin_bit_cast(bf16x8, (u32x4){pp[0], pp[1], pp[2], pp[3]}),
-                              __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]})};
+        pf[0] = __builtin_bit_cast(bf16x8, (u32x4){pp[0], pp[1], pp[2], pp[3]});
+        pf[1] = __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]});
+    }
+}
+
+template <int DZ, int NWIN>
+__global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p)
+{
+    using C = WideCfg<DZ, NWIN>;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int chunk = (p.total_tiles + 7) / 8;
+    const int logical = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
+    if (logical >= p.total_tiles) return;
+    const int win = blockIdx.y;
+    const int bh = logical / p.nQT, qt = logical - bh * p.nQT;
+    const int b = bh / p.H;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, g = lane >> 5;
+    const int kvlen = p.kvlen[b];
+    const int nblk = (kvlen + kKB - 1) / kKB;
+    const int irow = qt * kTileQ + wave * 32 + li;
+
+    // A tile whose rows all lie past the last valid residue of its chain has nothing to attend
+    // from: zero output.
+    if (qt * kTileQ >= kvlen) {
+        float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::D + win * C::NBW * 32;
 #pragma unroll
-        for (int nbw = 0; nbw < C::NBW; ++nbw) {
-            const int nb = win * C::NBW + nbw;  // global 32-column block (win is uniform)
+        for (int nbw = 0; nbw < C::NBW; ++nbw)
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                const bool head = nb < C::NBH;
-                const char *src = head ? smem + vaddr_h + 16 * tt * C::VS + nb * 64
-                                       : smem + vaddr_z + 16 * tt * C::RS + (nb - C::NBH) * 64;
-                const int rs = head ? C::VS : C::RS;
-                const bf16x4 lo = lds_read_tr(src);
-                const bf16x4 hi = lds_read_tr(src + 8 * rs);
-                bf16x8 a;
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<f32x4 *>(orow + 32 * nbw + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (win == 0 && g == 0) p.lse2[(size_t)bh * p.Lp + irow] = -INFINITY;
+        return;
+    }
+
+    // start at the block holding the tile's own residues (see the main kernel) and wrap around
+    const int first_blk = min(qt * (kTileQ / kKB), max(nblk - 1, 0));
+
+    WideDma<C> dma;
+    dma.wave_lds = 1024u * wave;
+    {
+        const char *Z2b = reinterpret_cast<const char *>(p.Z2 + (size_t)b * p.Lp * DZ);
+        const char *Khb = reinterpret_cast<const char *>(p.Kh + (size_t)bh * p.Lp * kDH);
+        const char *Vhb = reinterpret_cast<const char *>(p.Vh + (size_t)bh * p.Lp * kDH);
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    a[x] = lo[x];
-                    a[4 + x] = hi[x];
-                }
-                acc[nbw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt], acc[nbw], 0, 0, 0);
-            }
+        for (int k = 0; k < C::NIW; ++k) {
+            int i = wave + 4 * k;
+            if (i >= C::NI) i = 0;
+            const bool isz = i < C::NZ;
+            const bool isk = !isz && i < C::NZ + C::NH;
+            const int first = isz ? 0 : (isk ? C::NZ : C::NZ + C::NH);
+            const int spr = isz ? C::Z_SPR : C::H_SPR;        // 16-byte slots per LDS row
+            const int cols = isz ? DZ / 8 : kDH / 8;          // 16-byte columns of a global row
+            const int s = 64 * (i - first) + lane;
+            const int row = s / spr, col = s - row * spr;
+            dma.step[k] = kKB * cols * 16;
+            dma.src[k] = isz ? Z2b : (isk ? Khb : Vhb);
+            // one block before the first block: every request advances the offset first
+            dma.voff[k] = ((row < kKB && col < cols) ? row * (cols * 16) + col * 16 : 0) + (first_blk - 1) * dma.step[k];
+        }
+        dma.step[C::NIW] = kKB * 4;
+        dma.src[C::NIW] = reinterpret_cast<const char *>(p.kbias + (size_t)bh * p.Lp);
+        dma.voff[C::NIW] = min(lane, 7) * 16 + (first_blk - 1) * dma.step[C::NIW];
+    }
+    const unsigned smem_lds = lds_address(smem);
+    int next_blk = first_blk;
+    if (nblk > 0) {
+        wide_issue_block<C>(dma, smem_lds);
+        ++next_blk;
+    }
+
+    bf16x8 qf[C::KS];
+    {
+        const bf16_t *qh = p.Qh + ((size_t)bh * p.Lp + irow) * kDH;
+        const bf16_t *qz = p.Qz + ((size_t)bh * p.Lp + irow) * DZ;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            const bf16_t *src = ks < C::KSH ? qh + ks * 16 + 8 * g : qz + (ks - C::KSH) * 16 + 8 * g;
+            qf[ks] = *reinterpret_cast<const bf16x8 *>(src);
         }
     }
+    f32x16 acc[C::NBW];
+#pragma unroll
+    for (int nb = 0; nb < C::NBW; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    WideLane ln;
+    {
+        const int l16 = lane & 15, grp2 = (lane >> 4) & 1, e4 = l16 >> 2, j4 = l16 & 3;
+        ln.kaddr_h = li * kHS + g * 16;
+        ln.kaddr_z = li * C::ZS + g * 16;
+        ln.vaddr_h = (4 * g + e4) * kHS + (16 * grp2 + 4 * j4) * 2;
+        ln.vaddr_z = (4 * g + e4) * C::ZS + (16 * grp2 + 4 * j4) * 2;
+        ln.g = g;
+        ln.win = win;
+    }
+
+    bf16x8 pf[2] = {};
+    int sidx = 0;  // stage of block n
+    const char *st_prev = smem;
+    for (int n = 0; n < nblk; ++n) {
+        const char *st = smem + sidx * C::STAGE;
+        // block n must have landed; the barrier also tells everyone that the stage of block n-2
+        // is free again
+        wait_vmem<0>();
+        wg_barrier();
+        sidx = sidx + 1 < C::NSTAGE ? sidx + 1 : 0;
+        if (n + 1 < nblk) {
+            if (next_blk == nblk) {  // continue at block 0
+#pragma unroll
+                for (int k = 0; k <= C::NIW; ++k) dma.src[k] -= (size_t)nblk * dma.step[k];
+                next_blk = 0;
+            }
+            wide_issue_block<C>(dma, smem_lds + sidx * C::STAGE);
+            ++next_blk;
+        }
+        if (n == 0)
+            wide_step<DZ, NWIN, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run);
+        else
+            wide_step<DZ, NWIN, true, true>(st, st_prev, ln, qf, acc, pf, m_run, l_run);
+        st_prev = st;
+    }
+    if (nblk > 0) wide_step<DZ, NWIN, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run);
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
