@@ -102,10 +102,11 @@ int fipa_forward(const fipa_desc *desc,
 
 /*
  * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three
- * point sets, z1, z2 (same shapes and dtype as the inputs) and gamma ([H], float32), given
+ * point sets, z1, z2 (same shapes and dtype as the inputs), gamma ([H], float32) and, when
+ * d_w_b is not NULL, the pair-bias weights w_b ([H, cz], float32), given
  * the upstream gradients d_o, d_o_pts, d_o_pair (float32, shapes of o, o_pts, o_pair) and
- * the forward results o, o_pts, o_pair, lse.  Frames and w_b are treated as constants.
- * d_gamma is overwritten (not accumulated).  The paper gives no backward; it is the chain
+ * the forward results o, o_pts, o_pair, lse.  Frames are treated as constants.
+ * d_gamma and d_w_b are overwritten (not accumulated).  The paper gives no backward; it is the chain
  * rule through Eqs. 3-4 and z_ij = z1_i^T z2_j.
  * Supported for FIPA_DTYPE_BF16 with r*cz <= 256; otherwise FIPA_ERR_UNSUPPORTED.
  */
@@ -119,7 +120,7 @@ int fipa_backward(const fipa_desc *desc,
                   const float *d_o, const float *d_o_pts, const float *d_o_pair,
                   void *d_q, void *d_k, void *d_v,
                   void *d_q_pts, void *d_k_pts, void *d_v_pts,
-                  void *d_z1, void *d_z2, float *d_gamma,
+                  void *d_z1, void *d_z2, float *d_gamma, float *d_w_b,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

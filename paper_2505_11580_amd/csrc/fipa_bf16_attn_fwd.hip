@@ -750,12 +750,12 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         // with device-scope atomic accesses (which go to the coherence point, not through the
         // non-coherent caches); a part's words are complete (vmcnt = 0) before it takes its ticket.
         if (nparts > 1) {
-            // per lane: 2 groups of scalars, 3 of point coordinates, 4 per pair block, 1 of (m, l)
-            constexpr int kGroups = 6 + 4 * NZB;
+            // per lane: 2 groups of scalars, 3 of point coordinates, 1 of (m, l), 4 per pair block
+            const int groups = attn_partial_groups(cz);
             // wave-uniform base: this wave's rows in part 0 of the tile; byte offsets within 32 bits
             const __amdgpu_buffer_rsrc_t xr =
-                xchg_resource(p.partial + ((size_t)tile_local * nparts * 4 + wave) * (kGroups * 64 * 4));
-            constexpr int kPartBytes = 4 * kGroups * 64 * 16;
+                xchg_resource(p.partial + ((size_t)tile_local * nparts * 4 + wave) * (groups * 64 * 4));
+            const int kPartBytes = 4 * groups * 64 * 16;
             const int mine = part * kPartBytes + lane * 16;
             xchg_store(xr, mine + 0 * 1024, (f32x4){oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]});
             xchg_store(xr, mine + 1 * 1024, (f32x4){oacc[0][4], oacc[0][5], oacc[0][6], oacc[0][7]});

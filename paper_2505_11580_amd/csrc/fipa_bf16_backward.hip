@@ -185,9 +185,44 @@ __global__ __launch_bounds__(256) void fipa_bwd_gamma_kernel(const float *gpart,
     if (tid == 0) d_gamma[h] = coef * red[0];
 }
 
+// d w_b[h, d] = w_L * sum over (batch, residue, rho) of z1[b,i,rho,d] * dQ^[b,h,i, 64 + rho*cz + d]
+// (b^{h1} = w_L w_b (.) z1, Algorithm 1 step 2 with Eq. 3's w_L).  Two passes with a fixed
+// summation order: per (head, chunk of 64 residues) partial sums per lifted column, then the
+// sum over chunks and rho.
+constexpr int kWbChunk = 64;
+
+__global__ __launch_bounds__(256) void fipa_bwd_wb_partial_kernel(BwdUnpackParams p)
+{
+    const int h = blockIdx.y, chunk = blockIdx.x, D = kDH + p.DZ;
+    const int nres = p.B * p.L;
+    for (int x = threadIdx.x; x < p.DZ; x += 256) {
+        float s = 0.f;
+        for (int t = 0; t < kWbChunk; ++t) {
+            const int bi = chunk * kWbChunk + t;
+            if (bi >= nres) break;
+            const int b = bi / p.L, i = bi - b * p.L;
+            const bool valid = p.mask ? p.mask[bi] != 0 : true;
+            if (valid)
+                s += bf2f(p.z1[(size_t)bi * p.DZ + x]) * p.dQhat[(((size_t)b * p.H + h) * p.Lp + i) * D + kDH + x];
+        }
+        p.wpart[((size_t)h * gridDim.x + chunk) * p.DZ + x] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void fipa_bwd_wb_reduce_kernel(BwdUnpackParams p, int nchunk)
+{
+    const int h = blockIdx.x;
+    for (int d = threadIdx.x; d < p.cz; d += 256) {
+        float s = 0.f;
+        for (int ch = 0; ch < nchunk; ++ch)
+            for (int rho = 0; rho < p.r; ++rho) s += p.wpart[((size_t)h * nchunk + ch) * p.DZ + rho * p.cz + d];
+        p.d_w_b[(size_t)h * p.cz + d] = p.w_L * s;
+    }
+}
+
 struct BwdLayout {
     Bf16Layout f;
-    size_t dOhat, Dvec, nlse, dQhat, dKhat, dVhat, rowsum, colsum, gpart, total;
+    size_t dOhat, Dvec, nlse, dQhat, dKhat, dVhat, rowsum, colsum, gpart, wpart, total;
 };
 
 BwdLayout bwd_layout(const fipa_desc &d)
@@ -211,6 +246,7 @@ BwdLayout bwd_layout(const fipa_desc &d)
     w.rowsum = take(BHL * 4);
     w.colsum = take(BHL * 4);
     w.gpart = take(BHL * 4);
+    w.wpart = take((size_t)d.H * (((size_t)d.B * d.L + kWbChunk - 1) / kWbChunk) * w.f.DZ * 4);
     w.total = off;
     return w;
 }
@@ -231,6 +267,11 @@ hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream)
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fipa_bwd_gamma_kernel, dim3(p.H), dim3(256), 0, stream, p.gpart, p.d_gamma, p.B, p.H, p.L,
                        p.Lp, -0.5f * p.w_L * p.w_C);
+    if (p.d_w_b) {
+        const int nchunk = (p.B * p.L + kWbChunk - 1) / kWbChunk;
+        hipLaunchKernelGGL(fipa_bwd_wb_partial_kernel, dim3(nchunk, p.H), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL(fipa_bwd_wb_reduce_kernel, dim3(p.H), dim3(256), 0, stream, p, nchunk);
+    }
     return hipGetLastError();
 }
 
@@ -317,6 +358,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     up.d_q_pts = (bf16_t *)a.d_q_pts; up.d_k_pts = (bf16_t *)a.d_k_pts; up.d_v_pts = (bf16_t *)a.d_v_pts;
     up.d_z1 = (bf16_t *)a.d_z1; up.d_z2 = (bf16_t *)a.d_z2;
     up.gpart = (float *)(base + w.gpart); up.d_gamma = a.d_gamma;
+    up.d_w_b = a.d_w_b; up.wpart = (float *)(base + w.wpart);
     up.B = d.B; up.L = d.L; up.Lp = w.f.Lp; up.H = d.H; up.c = d.c; up.Pq = d.Pq; up.Pv = d.Pv; up.cz = d.cz;
     up.r = d.r; up.DZ = w.f.DZ;
     up.w_L = d.w_L; up.w_C = d.w_C; up.qk_scale = d.qk_scale;

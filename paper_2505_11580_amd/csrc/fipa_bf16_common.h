@@ -81,9 +81,11 @@ inline SplitPlan attn_split_plan(int total_tiles, int Lp, int DZ, int cz, bool f
     return s;
 }
 
-// Floats one wave of one part leaves for the merge: per lane 16-byte groups -- 2 of scalars, 3 of
-// point coordinates, 1 of (reference maximum, weight sum), 4 per 32-column block of the pair part.
-inline size_t attn_partial_floats(int DZ) { return (size_t)(6 + 4 * (DZ / 32)) * 64 * 4; }
+// 16-byte groups per lane that one wave of one part leaves for the merge: 2 of scalars, 3 of
+// point coordinates, 1 of (reference maximum, weight sum), 4 per 32-column block of the
+// z1-contracted pair part (c_z / 32 blocks).
+__host__ __device__ inline int attn_partial_groups(int cz) { return 6 + 4 * (cz / 32); }
+constexpr int kMaxSplitUnits = 256;  // a split launch has at most this many part workgroups
 
 struct Bf16Layout {
     int Lp, NT, DZ;
@@ -117,9 +119,10 @@ inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
     w.lse2 = take(BH * w.Lp * sizeof(float));
     w.Ohat = with_ohat ? take(BH * w.Lp * (size_t)(kDH + w.DZ) * sizeof(float)) : 0;
     w.plan = attn_split_plan((int)(BH * (w.Lp / kTileQ)), w.Lp, w.DZ, d.cz, !with_ohat);
-    const bool split = w.plan.S > 1;
-    w.partial = split ? take((size_t)w.plan.rem * w.plan.S * 4 * attn_partial_floats(w.DZ) * sizeof(float)) : 0;
-    w.counters = split ? take((size_t)w.plan.rem * 4 * sizeof(int)) : 0;
+    // (sized for the largest split any length can give, so that the total stays affine in L)
+    const bool can_split = !with_ohat && w.DZ <= 256 && d.cz >= 32;
+    w.partial = can_split ? take((size_t)kMaxSplitUnits * 4 * attn_partial_groups(d.cz) * 64 * 16) : 0;
+    w.counters = can_split ? take((size_t)kMaxSplitUnits * 4 * sizeof(int)) : 0;
     w.total = off;
     return w;
 }
@@ -195,6 +198,8 @@ struct BwdUnpackParams {
     bf16_t *d_q, *d_k, *d_v, *d_q_pts, *d_k_pts, *d_v_pts, *d_z1, *d_z2;
     float *gpart;   // [B,H,Lp] per-(b,h,i) contribution to d gamma
     float *d_gamma; // [H]
+    float *d_w_b;   // [H, cz] or null
+    float *wpart;   // [H, ceil(B*L/64), DZ] partial sums of d w_b
     int B, L, Lp, H, c, Pq, Pv, cz, r, DZ;
     float w_L, w_C, qk_scale;
 };

@@ -105,10 +105,9 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_bf16_kernel(PackParams p)
 }
 
 // z2 copy (zeroing masked and padded residues): one thread per 8 consecutive features.
-__global__ __launch_bounds__(256) void fipa_pack_z2_bf16_kernel(PackParams p)
+__device__ __forceinline__ void pack_z2_chunk(const PackParams &p, size_t idx)
 {
     const int cpr = p.DZ / 8;  // 16-byte chunks per row
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)p.B * p.Lp * cpr) return;
     const int cc = (int)(idx % cpr);
     const size_t bi = idx / cpr;
@@ -117,6 +116,11 @@ __global__ __launch_bounds__(256) void fipa_pack_z2_bf16_kernel(PackParams p)
     uint4 val = make_uint4(0, 0, 0, 0);
     if (ok) val = *reinterpret_cast<const uint4 *>(p.z2 + ((size_t)b * p.L + i) * p.DZ + cc * 8);
     *reinterpret_cast<uint4 *>(p.Z2 + ((size_t)b * p.Lp + i) * p.DZ + cc * 8) = val;
+}
+
+__global__ __launch_bounds__(256) void fipa_pack_z2_bf16_kernel(PackParams p)
+{
+    pack_z2_chunk(p, (size_t)blockIdx.x * 256 + threadIdx.x);
 }
 
 // Query-side factor bias vectors b^{h1} = log2e * w_L * w_b[h] (.) z1 for every head (Algorithm 1
@@ -228,16 +232,22 @@ __device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i,
     if (ROLE == 1) p.kbias[bh * p.Lp + i] = bias;
 }
 
-__global__ __launch_bounds__(256) void fipa_pack_heads_af2_bf16_kernel(PackParams p)
+// The launch covers the three roles (nbh workgroups each) and, after them, the z2 copy.
+__global__ __launch_bounds__(256) void fipa_pack_heads_af2_bf16_kernel(PackParams p, unsigned nbh)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, i, h), h fastest
+    const unsigned role = blockIdx.x / nbh;
+    if (role >= 3) {
+        pack_z2_chunk(p, (size_t)(blockIdx.x - 3 * nbh) * 256 + threadIdx.x);
+        return;
+    }
+    const size_t idx = (size_t)(blockIdx.x - role * nbh) * 256 + threadIdx.x;  // (b, i, h), h fastest
     if (idx >= (size_t)p.B * p.Lp * p.H) return;
     const int h = (int)(idx % p.H);
     const size_t bi = idx / p.H;
     const int i = (int)(bi % p.Lp), b = (int)(bi / p.Lp);
-    if (blockIdx.y == 0)
+    if (role == 0)
         pack_head_row<0>(p, b, i, h);
-    else if (blockIdx.y == 1)
+    else if (role == 1)
         pack_head_row<1>(p, b, i, h);
     else
         pack_head_row<2>(p, b, i, h);
@@ -248,9 +258,11 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_af2_bf16_kernel(PackParam
 hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream)
 {
     hipError_t e;
+    const size_t cpr = p.DZ / 8;
+    const unsigned nbz = (unsigned)(((size_t)p.B * p.Lp * cpr + 255) / 256);
     if (p.c == 16 && p.Pq == 4 && p.Pv == 8) {
-        const unsigned nb = (unsigned)(((size_t)p.B * p.Lp * p.H + 255) / 256);
-        hipLaunchKernelGGL(fipa_pack_heads_af2_bf16_kernel, dim3(nb, 3), dim3(256), 0, stream, p);
+        const unsigned nbh = (unsigned)(((size_t)p.B * p.Lp * p.H + 255) / 256);
+        hipLaunchKernelGGL(fipa_pack_heads_af2_bf16_kernel, dim3(3 * nbh + nbz), dim3(256), 0, stream, p, nbh);
     } else {
         const size_t lds_heads = (size_t)4 * 3 * 64 * kRowStride * sizeof(bf16_t);
         e = hipFuncSetAttribute((const void *)fipa_pack_heads_bf16_kernel,
@@ -258,12 +270,10 @@ hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream)
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(fipa_pack_heads_bf16_kernel, dim3(p.NT, (p.H + 3) / 4, p.B), dim3(256),
                            lds_heads, stream, p);
+        hipLaunchKernelGGL(fipa_pack_z2_bf16_kernel, dim3(nbz), dim3(256), 0, stream, p);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t cpr = p.DZ / 8;
-    hipLaunchKernelGGL(fipa_pack_z2_bf16_kernel, dim3((unsigned)(((size_t)p.B * p.Lp * cpr + 255) / 256)),
-                       dim3(256), 0, stream, p);
     if (!p.skip_qz)
         hipLaunchKernelGGL(fipa_pack_qz_bf16_kernel,
                            dim3((unsigned)(((size_t)p.B * p.H * p.Lp * cpr + 255) / 256)), dim3(256), 0, stream, p);

@@ -12,7 +12,7 @@ from tests import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 GRADS = (("d_q", "dq"), ("d_k", "dk"), ("d_v", "dv"), ("d_q_pts", "dq_pts"), ("d_k_pts", "dk_pts"),
-         ("d_v_pts", "dv_pts"), ("d_z1", "dz1"), ("d_z2", "dz2"), ("d_gamma", "dgamma"))
+         ("d_v_pts", "dv_pts"), ("d_z1", "dz1"), ("d_z2", "dz2"), ("d_gamma", "dgamma"), ("d_w_b", "dw_b"))
 
 
 def run_gpu_backward(inp):
