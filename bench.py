@@ -93,7 +93,7 @@ def calibrate_copy(nbytes=256 << 20):
 
 # HBM traffic of one launch of the attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script (see profiles/), scaled by what the same counters read for calibrate_copy().
-MEASURED_TRAFFIC_BYTES = {2: 86.1e6}  # workload 2: 52.1 MB fetched + 34.0 MB written
+MEASURED_TRAFFIC_BYTES = {2: 140.9e6}  # workload 2: 80.8 MB fetched + 60.1 MB written
 
 
 def main():

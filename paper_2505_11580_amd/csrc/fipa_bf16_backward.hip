@@ -187,9 +187,9 @@ __global__ __launch_bounds__(256) void fipa_bwd_gamma_kernel(const float *gpart,
 
 // d w_b[h, d] = w_L * sum over (batch, residue, rho) of z1[b,i,rho,d] * dQ^[b,h,i, 64 + rho*cz + d]
 // (b^{h1} = w_L w_b (.) z1, Algorithm 1 step 2 with Eq. 3's w_L).  Two passes with a fixed
-// summation order: per (head, chunk of 64 residues) partial sums per lifted column, then the
+// summation order: per (head, chunk of 128 residues) partial sums per lifted column, then the
 // sum over chunks and rho.
-constexpr int kWbChunk = 64;
+constexpr int kWbChunk = 128;
 
 __global__ __launch_bounds__(256) void fipa_bwd_wb_partial_kernel(BwdUnpackParams p)
 {
@@ -211,11 +211,17 @@ __global__ __launch_bounds__(256) void fipa_bwd_wb_partial_kernel(BwdUnpackParam
 
 __global__ __launch_bounds__(256) void fipa_bwd_wb_reduce_kernel(BwdUnpackParams p, int nchunk)
 {
+    __shared__ float col[512];  // per lifted pair column: sum over the chunks
     const int h = blockIdx.x;
+    for (int x = threadIdx.x; x < p.DZ; x += 256) {
+        float s = 0.f;
+        for (int ch = 0; ch < nchunk; ++ch) s += p.wpart[((size_t)h * nchunk + ch) * p.DZ + x];
+        col[x] = s;
+    }
+    __syncthreads();
     for (int d = threadIdx.x; d < p.cz; d += 256) {
         float s = 0.f;
-        for (int ch = 0; ch < nchunk; ++ch)
-            for (int rho = 0; rho < p.r; ++rho) s += p.wpart[((size_t)h * nchunk + ch) * p.DZ + rho * p.cz + d];
+        for (int rho = 0; rho < p.r; ++rho) s += col[rho * p.cz + d];
         p.d_w_b[(size_t)h * p.cz + d] = p.w_L * s;
     }
 }

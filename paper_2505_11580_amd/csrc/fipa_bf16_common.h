@@ -199,7 +199,7 @@ struct BwdUnpackParams {
     float *gpart;   // [B,H,Lp] per-(b,h,i) contribution to d gamma
     float *d_gamma; // [H]
     float *d_w_b;   // [H, cz] or null
-    float *wpart;   // [H, ceil(B*L/64), DZ] partial sums of d w_b
+    float *wpart;   // [H, ceil(B*L/128), DZ] partial sums of d w_b
     int B, L, Lp, H, c, Pq, Pv, cz, r, DZ;
     float w_L, w_C, qk_scale;
 };
