@@ -120,6 +120,34 @@ def make_inputs(cfg, seed=None, with_grads=None, trans_scale=1.0, **override):
     return out
 
 
+def module_widths(dims):
+    """(N_in, N_cat): output width of the input projection (Eq. 1) and input width of the output
+    projection (Eq. 5)."""
+    H, c, Pq, Pv, cz = (dims[n] for n in ("H", "c", "Pq", "Pv", "cz"))
+    return H * (3 * c + 3 * (2 * Pq + Pv)), H * (cz + c + 4 * Pv)
+
+
+def make_module_inputs(cfg, d_s=256, seed=None, **override):
+    """Inputs of the whole IPA module: the frames, pair factors and parameters of
+    make_inputs(cfg, ...) plus the single representation s [B, L, d_s] (bf16 values) and the
+    two Linear layers, weights [out, in] as bf16 values with variance 1/in, biases float32."""
+    m = make_inputs(cfg, seed=seed, with_grads=False, **override)
+    for n in ("q", "k", "v", "q_pts", "k_pts", "v_pts"):
+        del m[n]
+    d = m["dims"]
+    n_in, n_cat = module_widths(d)
+    rng = np.random.default_rng(BASE_SEED + 100 + cfg if seed is None else seed + 100)
+    m["s"] = round_to_bf16(rng.standard_normal((d["B"], d["L"], d_s)).astype(np.float32))
+    m["w_in"] = round_to_bf16((rng.standard_normal((n_in, d_s)) / math.sqrt(d_s)).astype(np.float32))
+    m["b_in"] = (0.1 * rng.standard_normal(n_in)).astype(np.float32)
+    m["w_out"] = round_to_bf16((rng.standard_normal((d_s, n_cat)) / math.sqrt(n_cat)).astype(np.float32))
+    m["b_out"] = (0.1 * rng.standard_normal(d_s)).astype(np.float32)
+    if m["mask"] is not None:
+        m["s"][m["mask"] == 0] = PAD_GARBAGE
+    m["d_s"] = d_s
+    return m
+
+
 def select_rows(inp, n_rows, seed=0):
     """Query rows for sampled parity at sizes the oracle cannot sweep: per batch element the
     first row, the last valid row, the first padded row (if any) and random valid rows."""

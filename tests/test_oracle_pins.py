@@ -277,3 +277,118 @@ def test_gradients_are_se3_invariant():
     g1 = ipa_oracle.backward(global_move(inp, 32), *ups)
     for n in ("dq", "dk", "dv", "dq_pts", "dk_pts", "dv_pts", "dz1", "dz2", "dgamma"):
         assert np.abs(g0[n] - g1[n]).max() <= 1e-9 * max(1.0, np.abs(g0[n]).max()), n
+
+
+# ---- the module around the core (Eq. 1, Eq. 5) -----------------------------------------------------
+def _tiny_module(seed=3, B=1, L=6, H=2, cz=8, r=2, d_s=None, varlen=False):
+    from paper_2505_11580_amd import workloads as wl
+    dims = dict(B=B, L=L, H=H, cz=cz, r=r, varlen=varlen, min_len=3, dtype="bf16")
+    n_in, _ = wl.module_widths(dict(H=H, c=16, Pq=4, Pv=8, cz=cz))
+    return wl.make_module_inputs(1, d_s=d_s or 24, seed=seed, **dims)
+
+
+def test_module_identity_projections_reduce_to_core():
+    """With identity weights and no bias the module is the core applied to slices of s, followed
+    by the concatenation with norms, written here with plain loops."""
+    from oracle import module_ref
+    from paper_2505_11580_amd import workloads as wl
+    m = _tiny_module()
+    d = m["dims"]
+    n_in, n_cat = wl.module_widths(d)
+    rng = np.random.default_rng(0)
+    m["s"] = wl.round_to_bf16(rng.standard_normal((d["B"], d["L"], n_in)).astype(np.float32))
+    m["w_in"], m["b_in"] = np.eye(n_in), None
+    m["w_out"], m["b_out"] = np.eye(n_cat), None
+    got = module_ref.module_forward(m)
+    H, c, Pq, Pv, cz = d["H"], d["c"], d["Pq"], d["Pv"], d["cz"]
+    s = m["s"].astype(np.float64)
+    inp = dict(m)
+    at = 0
+    for name, shp in (("q", (H, c)), ("k", (H, c)), ("v", (H, c)), ("q_pts", (H, Pq, 3)), ("k_pts", (H, Pq, 3)),
+                      ("v_pts", (H, Pv, 3))):
+        w = int(np.prod(shp))
+        inp[name] = s[..., at:at + w].reshape((d["B"], d["L"]) + shp)
+        at += w
+    core = ipa_oracle.forward(inp)
+    for b in range(d["B"]):
+        for i in range(d["L"]):
+            row = []
+            for h in range(H):
+                row += list(core["o_pair"][b, i, h])
+            for h in range(H):
+                row += list(core["o"][b, i, h])
+            for h in range(H):
+                for p in range(Pv):
+                    row += list(core["o_pts"][b, i, h, p])
+            for h in range(H):
+                for p in range(Pv):
+                    x, y, z = core["o_pts"][b, i, h, p]
+                    row.append(math.sqrt(x * x + y * y + z * z))
+            assert np.allclose(got[b, i], row, rtol=1e-12, atol=1e-12)
+
+
+def test_module_is_invariant_under_global_rigid_motion():
+    """Section 2.2: the IPA update is SE(3) invariant -- also through the norms of Eq. 5."""
+    from oracle import module_ref
+    m = _tiny_module(seed=5, L=7, varlen=True)
+    base = module_ref.module_forward(m)
+    rng = np.random.default_rng(1)
+    qn = rng.standard_normal(4)
+    qn /= np.linalg.norm(qn)
+    w, x, y, z = qn
+    G = np.array([[1 - 2 * (y * y + z * z), 2 * (x * y - z * w), 2 * (x * z + y * w)],
+                  [2 * (x * y + z * w), 1 - 2 * (x * x + z * z), 2 * (y * z - x * w)],
+                  [2 * (x * z - y * w), 2 * (y * z + x * w), 1 - 2 * (x * x + y * y)]])
+    shift = np.array([30.0, -20.0, 5.0])
+    moved = dict(m)
+    moved["rot"] = np.einsum("xy,blyz->blxz", G, m["rot"].astype(np.float64))
+    moved["trans"] = np.einsum("xy,bly->blx", G, m["trans"].astype(np.float64)) + shift
+    assert np.allclose(module_ref.module_forward(moved), base, rtol=1e-9, atol=1e-9)
+    # and it does depend on the frames: moving one residue alone changes the result
+    one = dict(m)
+    one["trans"] = m["trans"].astype(np.float64).copy()
+    one["trans"][0, 1] += np.array([3.0, 0.0, 0.0])
+    assert np.abs(module_ref.module_forward(one) - base).max() > 1e-6
+
+
+def test_module_output_projection_is_affine_and_masked_rows_give_the_bias():
+    from oracle import module_ref
+    m = _tiny_module(seed=7, B=2, L=6, varlen=True)
+    base = module_ref.module_forward(m)
+    shifted = dict(m)
+    delta = np.linspace(-1, 1, m["d_s"])
+    shifted["b_out"] = m["b_out"].astype(np.float64) + delta
+    assert np.allclose(module_ref.module_forward(shifted) - base, delta, atol=1e-12)
+    doubled = dict(m)
+    doubled["w_out"] = 2.0 * m["w_out"].astype(np.float64)
+    b = m["b_out"].astype(np.float64)
+    assert np.allclose(module_ref.module_forward(doubled) - b, 2.0 * (base - b), rtol=1e-12, atol=1e-12)
+    for bi, ln in enumerate(m["lengths"]):
+        assert np.allclose(base[bi, int(ln):], b, atol=1e-12)   # masked rows: zero core output
+    # rows argument: a subset equals the full result at those rows
+    rows = [np.array([0, 2], dtype=np.int32)] * 2
+    assert np.allclose(module_ref.module_forward(m, rows=rows), base[:, [0, 2]], atol=1e-12)
+
+
+def test_module_input_projection_orientation_and_rounding():
+    """Eq. 1 with weights [out, in]: a single non-zero weight copies one input feature into one
+    output feature; outputs are bfloat16 values; torch's Linear agrees before the rounding."""
+    from oracle import module_ref
+    m = _tiny_module(seed=9)
+    d = m["dims"]
+    n_in = m["w_in"].shape[0]
+    w = np.zeros_like(m["w_in"], dtype=np.float64)
+    w[5, 2] = 0.5           # output feature 5 (= q[h=0, channel 5]) <- 0.5 * s[..., 2]
+    w[n_in - 1, 0] = -2.0   # last output feature (= v_pts[h=H-1, p=Pv-1, z]) <- -2 * s[..., 0]
+    one = dict(m, w_in=w, b_in=None)
+    got = module_ref.project_in(one)
+    s = m["s"].astype(np.float64)
+    assert np.array_equal(got["q"][..., 0, 5], 0.5 * s[..., 2])
+    assert np.array_equal(got["v_pts"][..., d["H"] - 1, d["Pv"] - 1, 2], -2.0 * s[..., 0])
+    assert np.count_nonzero(got["k"]) == 0 and np.count_nonzero(got["q_pts"]) == 0
+    full = module_ref.project_in(m)
+    ref = torch.nn.functional.linear(torch.tensor(s), torch.tensor(m["w_in"].astype(np.float64)),
+                                     torch.tensor(m["b_in"].astype(np.float64))).numpy()
+    flat = np.concatenate([full[n].reshape(d["B"], d["L"], -1) for n in ("q", "k", "v", "q_pts", "k_pts", "v_pts")], -1)
+    assert np.abs(flat - ref).max() <= 2.0 ** -8 * np.abs(ref).max()      # half an ulp of bf16
+    assert np.array_equal(flat.astype(np.float32).view(np.uint32) & 0xFFFF, np.zeros(flat.shape, np.uint32))
