@@ -124,6 +124,35 @@ int fipa_backward(const fipa_desc *desc,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The whole IPA module around the core (Eq. 1 and Eq. 5; Algorithm 1 steps 1 and 10), for
+ * FIPA_DTYPE_BF16 descriptions:
+ *     q | k | v | q_pts | k_pts | v_pts = s W_in^T + b_in      (Eq. 1; results kept as bfloat16)
+ *     o, o_pts, o_pair                  = fipa_forward(...)     (Eqs. 2-4)
+ *     s_out = concat(o_pair, o, o_pts, |o_pts|_2) W_out^T + b_out                      (Eq. 5)
+ *   s       [B, L, d_s] bfloat16        single representation
+ *   w_in    [N_in, d_s] bfloat16        N_in = H*(3c + 3*(2Pq + Pv)); output features in the order
+ *                                       q [H,c] | k | v | q_pts [H,Pq,3] | k_pts | v_pts [H,Pv,3]
+ *   b_in    [N_in] float32 or NULL
+ *   w_out   [d_s, N_cat] bfloat16       N_cat = H*(cz + c + 4*Pv); input features in the order
+ *                                       o_pair [H,cz] | o [H,c] | o_pts [H,Pv,3] | norms [H,Pv]
+ *   b_out   [d_s] float32 or NULL
+ *   s_out   [B, L, d_s] float32         (rows of masked residues receive b_out)
+ *   rot, trans, z1, z2, w_b, gamma, mask: as for fipa_forward.
+ * Shapes: d_s % 16 == 0, H*Pv % 8 == 0, N_cat % 16 == 0, else FIPA_ERR_UNSUPPORTED.
+ * The workspace holds the core's workspace, its six bfloat16 inputs and its float32 outputs
+ * (affine in L).  Device pointers, caller's stream, nothing allocated, as for fipa_forward.
+ */
+int fipa_module_workspace_bytes(const fipa_desc *desc, int32_t d_s, size_t *bytes);
+int fipa_module_forward(const fipa_desc *desc, int32_t d_s,
+                        const void *s, const void *w_in, const float *b_in,
+                        const float *rot, const float *trans,
+                        const void *z1, const void *z2,
+                        const float *w_b, const float *gamma, const uint8_t *mask,
+                        const void *w_out, const float *b_out,
+                        float *s_out,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Optional stage timing for benchmarks.  Between fipa_profile_begin() and fipa_profile_end()
  * every fipa_forward / fipa_backward call on any stream additionally records HIP events around
  * its stages on that stream (up to `capacity` calls; later calls run untimed).  This is the only

@@ -8,6 +8,8 @@ import ctypes
 import math
 import os
 
+import numpy as np
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # FIPA_LIB selects another build of the same library (e.g. one compiled with different flags)
 LIB_PATH = os.environ.get("FIPA_LIB") or os.path.join(_HERE, "libfipa.so")
@@ -22,7 +24,8 @@ FIPA_DTYPE_F32 = 0
 FIPA_DTYPE_BF16 = 1
 
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
-           "fipa_backward", "fipa_profile_begin", "fipa_profile_end")
+           "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
+           "fipa_profile_begin", "fipa_profile_end")
 PROFILE_STAGES = 3
 
 
@@ -59,6 +62,10 @@ def lib():
         L.fipa_forward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 17 + [vp, sz, vp]
         L.fipa_backward.restype = ctypes.c_int
         L.fipa_backward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 30 + [vp, sz, vp]
+        L.fipa_module_workspace_bytes.restype = ctypes.c_int
+        L.fipa_module_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32, ctypes.POINTER(sz)]
+        L.fipa_module_forward.restype = ctypes.c_int
+        L.fipa_module_forward.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32] + [vp] * 13 + [vp, sz, vp]
         L.fipa_profile_begin.restype = ctypes.c_int
         L.fipa_profile_begin.argtypes = [ctypes.c_int]
         L.fipa_profile_end.restype = ctypes.c_int
@@ -122,6 +129,24 @@ def fipa_backward(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, g
         raise FipaError(rc, "fipa_backward")
 
 
+def module_workspace_bytes(desc, d_s):
+    n = ctypes.c_size_t(0)
+    rc = lib().fipa_module_workspace_bytes(ctypes.byref(desc), int(d_s), ctypes.byref(n))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_module_workspace_bytes")
+    return n.value
+
+
+def fipa_module_forward(desc, d_s, s, w_in, b_in, rot, trans, z1, z2, w_b, gamma, mask, w_out, b_out, s_out,
+                        workspace):
+    """Enqueue fipa_module_forward on torch's current stream (b_in, b_out, mask may be None)."""
+    args = [s, w_in, b_in, rot, trans, z1, z2, w_b, gamma, mask, w_out, b_out, s_out]
+    rc = lib().fipa_module_forward(ctypes.byref(desc), int(d_s), *[_ptr(t) for t in args], _ptr(workspace),
+                                   ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_module_forward")
+
+
 def fipa_profile_begin(capacity):
     rc = lib().fipa_profile_begin(int(capacity))
     if rc != FIPA_OK:
@@ -172,6 +197,29 @@ def forward(desc, dev, out):
     fipa_forward(desc, dev["q"], dev["k"], dev["v"], dev["q_pts"], dev["k_pts"], dev["v_pts"],
                  dev["rot"], dev["trans"], dev["z1"], dev["z2"], dev["w_b"], dev["gamma"], dev["mask"],
                  out["o"], out["o_pts"], out["o_pair"], out["lse"], out["workspace"])
+
+
+def upload_module(m, device="cuda:0"):
+    """numpy module workload (workloads.make_module_inputs) -> desc, device tensors."""
+    import torch
+    d = m["dims"]
+    desc = make_desc(d["B"], d["L"], d["H"], d["c"], d["Pq"], d["Pv"], d["cz"], d["r"], FIPA_DTYPE_BF16,
+                     m["w_L"], m["w_C"])
+    dev = {}
+    for n in ("s", "w_in", "w_out", "z1", "z2"):
+        dev[n] = torch.from_numpy(np.ascontiguousarray(m[n], dtype=np.float32)).to(device).to(torch.bfloat16).contiguous()
+    for n in ("rot", "trans", "w_b", "gamma", "b_in", "b_out"):
+        dev[n] = None if m.get(n) is None else torch.from_numpy(np.ascontiguousarray(m[n], dtype=np.float32)).to(device)
+    dev["mask"] = None if m.get("mask") is None else torch.from_numpy(m["mask"]).to(device).contiguous()
+    dev["s_out"] = torch.empty(d["B"], d["L"], m["d_s"], dtype=torch.float32, device=device)
+    dev["workspace"] = torch.empty(max(module_workspace_bytes(desc, m["d_s"]), 16), dtype=torch.uint8, device=device)
+    return desc, dev
+
+
+def module_forward(desc, d_s, dev):
+    fipa_module_forward(desc, d_s, dev["s"], dev["w_in"], dev["b_in"], dev["rot"], dev["trans"], dev["z1"],
+                        dev["z2"], dev["w_b"], dev["gamma"], dev["mask"], dev["w_out"], dev["b_out"], dev["s_out"],
+                        dev["workspace"])
 
 
 def alloc_grads(desc, device="cuda:0"):

@@ -125,4 +125,33 @@ int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const voi
     return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
 }
 
+int fipa_module_workspace_bytes(const fipa_desc *desc, int32_t d_s, size_t *bytes)
+{
+    if (bytes) *bytes = 0;
+    const int rc = check_desc(desc, false);
+    if (rc != FIPA_OK) return rc;
+    if (desc->dtype != FIPA_DTYPE_BF16 || !module_shape_supported(*desc, d_s)) return FIPA_ERR_UNSUPPORTED;
+    if (bytes) *bytes = module_forward_workspace(*desc);
+    return FIPA_OK;
+}
+
+int fipa_module_forward(const fipa_desc *desc, int32_t d_s, const void *s, const void *w_in, const float *b_in,
+                        const float *rot, const float *trans, const void *z1, const void *z2, const float *w_b,
+                        const float *gamma, const uint8_t *mask, const void *w_out, const float *b_out,
+                        float *s_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    size_t need = 0;
+    const int rc = fipa_module_workspace_bytes(desc, d_s, &need);
+    if (rc != FIPA_OK) return rc;
+    const void *req[] = {s, w_in, rot, trans, z1, z2, w_b, gamma, w_out, s_out, workspace};
+    for (const void *ptr : req) {
+        if (!ptr) return FIPA_ERR_INVALID_ARG;
+        if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
+    }
+    if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
+    const ModuleArgs a{s, w_in, b_in, rot, trans, z1, z2, w_b, gamma, mask, w_out, b_out, s_out};
+    const hipError_t e = module_forward(*desc, d_s, a, workspace, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
+}
+
 }  // extern "C"

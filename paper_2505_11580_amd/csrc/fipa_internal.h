@@ -32,6 +32,19 @@ struct BwdArgs {
     float *d_w_b;  // may be null
 };
 
+// Arguments of fipa_module_forward beyond the description.
+struct ModuleArgs {
+    const void *s, *w_in;
+    const float *b_in;
+    const float *rot, *trans;
+    const void *z1, *z2;
+    const float *w_b, *gamma;
+    const uint8_t *mask;
+    const void *w_out;
+    const float *b_out;
+    float *s_out;
+};
+
 // Stage timing (fipa_profile_begin / fipa_profile_end).  A StageTimer is created per API call;
 // when profiling is inactive every method is a no-op.
 class StageTimer {
@@ -61,6 +74,11 @@ hipError_t f32_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream
 size_t bf16_forward_workspace(const fipa_desc &d);
 hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream_t stream);
 size_t bf16_backward_workspace(const fipa_desc &d);
+
+// IPA module around the core (fipa_module.hip)
+bool module_shape_supported(const fipa_desc &d, int d_s);
+size_t module_forward_workspace(const fipa_desc &d);
+hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void *ws, hipStream_t stream);
 hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream);
 
 }  // namespace fipa

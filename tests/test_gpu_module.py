@@ -1,0 +1,60 @@
+"""GPU parity of fipa_module_forward (through the C ABI) against the module oracle
+(oracle/module_ref.py): bf16 inputs and weights, fp32 accumulation, max|gpu - oracle| /
+max|oracle| <= 2e-2 on the output representation."""
+import numpy as np
+import pytest
+
+from oracle import module_ref
+from paper_2505_11580_amd import binding
+from paper_2505_11580_amd import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu_module(m):
+    import torch
+    desc, dev = binding.upload_module(m)
+    dev["s_out"].fill_(float("nan"))
+    binding.module_forward(desc, m["d_s"], dev)
+    torch.cuda.synchronize()
+    return dev["s_out"].cpu().numpy().astype(np.float64)
+
+
+def check_module(m, label, rows=None, tol=2e-2):
+    got = run_gpu_module(m)
+    assert np.all(np.isfinite(got)), label
+    want = module_ref.module_forward(m, rows=rows)
+    if rows is not None:
+        got = np.stack([got[b][rows[b]] for b in range(got.shape[0])])
+    err = gu.rel_err(got, want)
+    print(label, "s_out rel err %.2e" % err, flush=True)
+    assert err <= tol, (label, err)
+
+
+def test_module_small_shapes():
+    # several row tiles with a ragged tail, d_s not a multiple of the column tile
+    check_module(wl.make_module_inputs(1, d_s=48, B=2, L=200, H=4), "module L=200 d_s=48")
+    check_module(wl.make_module_inputs(1, d_s=256, B=1, L=130, H=12, trans_scale=0.1), "module spread L=130 H=12")
+    check_module(wl.make_module_inputs(1, d_s=64, B=1, L=96, H=2, cz=32, r=2), "module H=2 cz=32")
+
+
+def test_module_masked_rows_receive_the_bias():
+    m = wl.make_module_inputs(1, d_s=64, B=3, L=160, H=4, varlen=True, min_len=20)
+    check_module(m, "module varlen")
+    got = run_gpu_module(m)
+    for b, ln in enumerate(m["lengths"]):
+        assert np.array_equal(got[b, int(ln):], np.broadcast_to(m["b_out"].astype(np.float64), got[b, int(ln):].shape))
+    m["b_in"], m["b_out"] = None, None
+    check_module(m, "module varlen, no biases")
+
+
+def test_module_workload2_sampled_rows():
+    m = wl.make_module_inputs(2, d_s=256)
+    check_module(m, "module cfg2 sampled rows", rows=wl.select_rows(m, 48))
+
+
+def test_module_rejects_unsupported_width():
+    m = wl.make_module_inputs(1, d_s=40, B=1, L=64, H=4)
+    with pytest.raises(binding.FipaError):
+        binding.upload_module(m)
