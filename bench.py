@@ -80,6 +80,28 @@ def backward_leg(workload, steps=10, warmup=3):
     }
 
 
+def module_leg(workload, d_s=256, steps=50, warmup=5):
+    """fipa_module_forward (input projection + core + output projection) on the headline
+    workload; reported beside the headline number, not part of `value`."""
+    import torch
+    from paper_2505_11580_amd import binding, workloads
+    m = workloads.make_module_inputs(workload, d_s=d_s)
+    desc, dev = binding.upload_module(m)
+    for _ in range(warmup):
+        binding.module_forward(desc, d_s, dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        binding.module_forward(desc, d_s, dev)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    n_in, n_cat = workloads.module_widths(m["dims"])
+    rows = m["dims"]["B"] * m["dims"]["L"]
+    return {"workload": "workload %d with d_s=%d" % (workload, d_s), "ms_per_call": ms, "steps": steps,
+            "projection_gflop": 2.0 * rows * d_s * (n_in + n_cat) / 1e9,
+            "residues_per_s": float(m["lengths"].sum()) / (ms * 1e-3)}
+
+
 def calibrate_copy(nbytes=256 << 20):
     """A plain elementwise copy of known size (reads nbytes, writes nbytes), so that a counter run of
     this script sees a kernel whose HBM traffic is known next to the attention kernel."""
@@ -175,6 +197,7 @@ def main():
     if not args.no_backward:
         del out, dev
         torch.cuda.empty_cache()
+        result["module"] = module_leg(args.workload)
         result["backward"] = backward_leg(4)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, fpp)
