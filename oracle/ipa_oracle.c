@@ -238,8 +238,17 @@ int ipa_oracle_backward(int L, int H, int c, int Pq, int Pv, int cz,
                         const double *d_o, const double *d_o_pts, const double *d_o_pair,
                         double *dq, double *dk, double *dv,
                         double *dq_pts, double *dk_pts, double *dv_pts,
-                        double *dz, double *dgamma, double *dw_b)
+                        double *dz, double *dgamma, double *dw_b,
+                        double *drot, double *dtrans)
 {
+    /* drot [L,3,3], dtrans [L,3] (both may be NULL): gradients with respect to the frames, every
+     * entry of R_i taken as a free variable of G = R_i x + t_i (Eq. 3) and of R_i^T (G - t_i) (Eq. 4). */
+    const int frames = drot != NULL && dtrans != NULL;
+    if (frames) {
+        memset(drot, 0, sizeof(double) * (size_t)L * 9);
+        memset(dtrans, 0, sizeof(double) * (size_t)L * 3);
+    }
+    double *Gacc = (double *)malloc(sizeof(double) * (size_t)Pv * 3);
     memset(dq, 0, sizeof(double) * (size_t)L * H * c);
     memset(dk, 0, sizeof(double) * (size_t)L * H * c);
     memset(dv, 0, sizeof(double) * (size_t)L * H * c);
@@ -272,6 +281,8 @@ int ipa_oracle_backward(int L, int H, int c, int Pq, int Pv, int cz,
             for (int p = 0; p < Pv; ++p)
                 rot_apply(rot + 9 * (size_t)i, gp + 3 * p, dG + 3 * p);
 
+            for (int x = 0; x < 3 * Pv; ++x)
+                Gacc[x] = 0.0;
             /* gradients of the three weighted sums of Eq. 4 */
             double dot = 0.0; /* sum_j a_ij * dL/da_ij */
             for (int j = 0; j < L; ++j) {
@@ -291,6 +302,15 @@ int ipa_oracle_backward(int L, int H, int c, int Pq, int Pv, int cz,
                     for (int x = 0; x < 3; ++x) {
                         g += dG[3 * p + x] * V[x];
                         aG[x] = a[j] * dG[3 * p + x];
+                        Gacc[3 * p + x] += a[j] * V[x];
+                    }
+                    if (frames) { /* V_jp = R_j v_jp + t_j */
+                        const double *vl = v_pts + (((size_t)j * H + h) * Pv + p) * 3;
+                        for (int x = 0; x < 3; ++x) {
+                            dtrans[3 * (size_t)j + x] += aG[x];
+                            for (int y = 0; y < 3; ++y)
+                                drot[9 * (size_t)j + 3 * x + y] += aG[x] * vl[y];
+                        }
                     }
                     /* V_jp = R_j v_jp + t_j  =>  dL/dv_jp = R_j^T dL/dV_jp */
                     rot_transpose_apply(rot + 9 * (size_t)j, aG, loc);
@@ -299,6 +319,15 @@ int ipa_oracle_backward(int L, int H, int c, int Pq, int Pv, int cz,
                 }
                 da[j] = g;
                 dot += a[j] * g;
+            }
+            if (frames) { /* o_pts = R_i^T (G - t_i): dL/dt_i = -R_i g, dL/dR_i[x][y] = (G - t_i)[x] g[y] */
+                for (int p = 0; p < Pv; ++p)
+                    for (int x = 0; x < 3; ++x) {
+                        dtrans[3 * (size_t)i + x] -= dG[3 * p + x];
+                        for (int y = 0; y < 3; ++y)
+                            drot[9 * (size_t)i + 3 * x + y] +=
+                                (Gacc[3 * p + x] - trans[3 * (size_t)i + x]) * gp[3 * p + y];
+                    }
             }
             /* softmax backward, then Eq. 3 term by term */
             for (int j = 0; j < L; ++j) {
@@ -326,6 +355,18 @@ int ipa_oracle_backward(int L, int H, int c, int Pq, int Pv, int cz,
                         gQ[x] = -ds * pc * (Qg[x] - Kg[x]);
                         gK[x] = ds * pc * (Qg[x] - Kg[x]);
                     }
+                    if (frames) {
+                        const double *ql = q_pts + (((size_t)i * H + h) * Pq + p) * 3;
+                        const double *kl = k_pts + (((size_t)j * H + h) * Pq + p) * 3;
+                        for (int x = 0; x < 3; ++x) {
+                            dtrans[3 * (size_t)i + x] += gQ[x];
+                            dtrans[3 * (size_t)j + x] += gK[x];
+                            for (int y = 0; y < 3; ++y) {
+                                drot[9 * (size_t)i + 3 * x + y] += gQ[x] * ql[y];
+                                drot[9 * (size_t)j + 3 * x + y] += gK[x] * kl[y];
+                            }
+                        }
+                    }
                     rot_transpose_apply(rot + 9 * (size_t)i, gQ, loc);
                     for (int x = 0; x < 3; ++x)
                         dq_pts[(((size_t)i * H + h) * Pq + p) * 3 + x] += loc[x];
@@ -341,6 +382,7 @@ int ipa_oracle_backward(int L, int H, int c, int Pq, int Pv, int cz,
     free(D);
     free(da);
     free(dG);
+    free(Gacc);
     return 0;
 }
 

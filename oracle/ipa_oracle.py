@@ -30,7 +30,7 @@ def lib():
         L.ipa_oracle_forward_rows.restype = ctypes.c_int
         L.ipa_oracle_forward_rows.argtypes = [i] * 6 + [dp] * 11 + [d, d, bp, i, ip] + [dp] * 4
         L.ipa_oracle_backward.restype = ctypes.c_int
-        L.ipa_oracle_backward.argtypes = [i] * 6 + [dp] * 11 + [d, d, bp] + [dp] * 3 + [dp] * 9
+        L.ipa_oracle_backward.argtypes = [i] * 6 + [dp] * 11 + [d, d, bp] + [dp] * 3 + [dp] * 11
         L.ipa_oracle_pair_backward.restype = None
         L.ipa_oracle_pair_backward.argtypes = [i, i, i, dp, dp, dp, dp, dp]
         _LIB = L
@@ -124,7 +124,8 @@ def backward(inp, d_o, d_o_pts, d_o_pair):
     """Gradients of sum(o*d_o) + sum(o_pts*d_o_pts) + sum(o_pair*d_o_pair).
 
     Same inp as forward().  Returns dq, dk, dv, dq_pts, dk_pts, dv_pts, dgamma [H],
-    dw_b [H,cz], dz [B,L,L,cz] and, when inp holds factors, dz1, dz2 [B,L,r,cz].
+    dw_b [H,cz], dz [B,L,L,cz], drot [B,L,3,3] (every entry of R_i taken as a free variable),
+    dtrans [B,L,3] and, when inp holds factors, dz1, dz2 [B,L,r,cz].
     """
     B, L, H, c, Pq, Pv, cz = _dims(inp)
     w_b, gamma = _f64(inp["w_b"]), _f64(inp["gamma"])
@@ -136,6 +137,8 @@ def backward(inp, d_o, d_o_pts, d_o_pair):
     g["dz"] = np.zeros((B, L, L, cz))
     g["dgamma"] = np.zeros(H)
     g["dw_b"] = np.zeros((H, cz))
+    g["drot"] = np.zeros((B, L, 3, 3))
+    g["dtrans"] = np.zeros((B, L, 3))
     if factored:
         g["dz1"] = np.zeros(np.asarray(inp["z1"]).shape)
         g["dz2"] = np.zeros(np.asarray(inp["z2"]).shape)
@@ -151,7 +154,7 @@ def backward(inp, d_o, d_o_pts, d_o_pair):
         ups = [_f64(d_o[b]), _f64(d_o_pts[b]), _f64(d_o_pair[b])]
         outs = [np.zeros((L, H, c)), np.zeros((L, H, c)), np.zeros((L, H, c)),
                 np.zeros((L, H, Pq, 3)), np.zeros((L, H, Pq, 3)), np.zeros((L, H, Pv, 3)),
-                np.zeros((L, L, cz)), np.zeros(H), np.zeros((H, cz))]
+                np.zeros((L, L, cz)), np.zeros(H), np.zeros((H, cz)), np.zeros((L, 3, 3)), np.zeros((L, 3))]
         lib().ipa_oracle_backward(
             L, H, c, Pq, Pv, cz, *[_p(a) for a in arrs], _p(z), _p(w_b), _p(gamma),
             float(inp["w_L"]), float(inp["w_C"]), mp, *[_p(a) for a in ups],
@@ -160,6 +163,7 @@ def backward(inp, d_o, d_o_pts, d_o_pair):
             g[key][b] = arr
         g["dgamma"] += outs[7]
         g["dw_b"] += outs[8]
+        g["drot"][b], g["dtrans"][b] = outs[9], outs[10]
         if factored:
             z1b, z2b = _f64(inp["z1"][b]), _f64(inp["z2"][b])
             r = z1b.shape[1]

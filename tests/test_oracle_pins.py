@@ -245,7 +245,7 @@ def test_backward_matches_central_differences(dense, masked):
            (("o", (1, 5, 2, 3)), ("o_pts", (1, 5, 2, 2, 3)), ("o_pair", (1, 5, 2, 3)))}
     g = ipa_oracle.backward(inp, ups["o"], ups["o_pts"], ups["o_pair"])
     names = [("q", "dq"), ("k", "dk"), ("v", "dv"), ("q_pts", "dq_pts"), ("k_pts", "dk_pts"),
-             ("v_pts", "dv_pts"), ("gamma", "dgamma"), ("w_b", "dw_b")]
+             ("v_pts", "dv_pts"), ("gamma", "dgamma"), ("w_b", "dw_b"), ("rot", "drot"), ("trans", "dtrans")]
     names += [("z", "dz")] if dense else [("z1", "dz1"), ("z2", "dz2")]
     h = 1e-5
     for src, dst in names:
@@ -265,6 +265,21 @@ def test_backward_matches_central_differences(dense, masked):
         assert err < 2e-7, (src, err)
         if masked and src not in ("gamma", "w_b"):
             assert np.all(g[dst][0, 2] == 0), src
+
+
+def test_translation_gradients_sum_to_zero_and_rotation_gradient_has_no_net_torque():
+    """A common shift of all frames leaves the loss unchanged, so the translation gradients sum to
+    zero; so does a common rotation G, whose generator gives sum_i (dR_i R_i^T + dt_i t_i^T) with
+    no antisymmetric part."""
+    inp = small(seed=41, L=6)
+    rng = np.random.default_rng(42)
+    ups = [rng.standard_normal(inp[n].shape) for n in ("v", "v_pts")] + \
+          [rng.standard_normal(inp["q"].shape[:3] + (4,))]
+    g = ipa_oracle.backward(inp, *ups)
+    assert np.abs(g["dtrans"].sum(axis=1)).max() <= 1e-10 * max(1.0, np.abs(g["dtrans"]).max())
+    R, t = np.asarray(inp["rot"], dtype=np.float64), np.asarray(inp["trans"], dtype=np.float64)
+    M = np.einsum("blxy,blzy->xz", g["drot"], R) + np.einsum("blx,blz->xz", g["dtrans"], t)
+    assert np.abs(M - M.T).max() <= 1e-9 * max(1.0, np.abs(M).max())
 
 
 def test_gradients_are_se3_invariant():
