@@ -102,11 +102,13 @@ int fipa_forward(const fipa_desc *desc,
 
 /*
  * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three
- * point sets, z1, z2 (same shapes and dtype as the inputs), gamma ([H], float32) and, when
- * d_w_b is not NULL, the pair-bias weights w_b ([H, cz], float32), given
+ * point sets, z1, z2 (same shapes and dtype as the inputs), gamma ([H], float32) and, when the
+ * pointers are not NULL, the pair-bias weights w_b (d_w_b [H, cz], float32) and the frames
+ * (d_rot [B, L, 3, 3] and d_trans [B, L, 3], float32, both or neither; every entry of R_i is
+ * taken as a free variable of R_i x + t_i in Eq. 3 and of R_i^T (. - t_i) in Eq. 4), given
  * the upstream gradients d_o, d_o_pts, d_o_pair (float32, shapes of o, o_pts, o_pair) and
- * the forward results o, o_pts, o_pair, lse.  Frames are treated as constants.
- * d_gamma and d_w_b are overwritten (not accumulated).  The paper gives no backward; it is the chain
+ * the forward results o, o_pts, o_pair, lse.
+ * d_gamma, d_w_b, d_rot and d_trans are overwritten (not accumulated).  The paper gives no backward; it is the chain
  * rule through Eqs. 3-4 and z_ij = z1_i^T z2_j.
  * Supported for FIPA_DTYPE_BF16 with r*cz <= 256; otherwise FIPA_ERR_UNSUPPORTED.
  */
@@ -121,6 +123,7 @@ int fipa_backward(const fipa_desc *desc,
                   void *d_q, void *d_k, void *d_v,
                   void *d_q_pts, void *d_k_pts, void *d_v_pts,
                   void *d_z1, void *d_z2, float *d_gamma, float *d_w_b,
+                  float *d_rot, float *d_trans,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

@@ -61,7 +61,7 @@ def lib():
         L.fipa_forward.restype = ctypes.c_int
         L.fipa_forward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 17 + [vp, sz, vp]
         L.fipa_backward.restype = ctypes.c_int
-        L.fipa_backward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 30 + [vp, sz, vp]
+        L.fipa_backward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 32 + [vp, sz, vp]
         L.fipa_module_workspace_bytes.restype = ctypes.c_int
         L.fipa_module_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32, ctypes.POINTER(sz)]
         L.fipa_module_forward.restype = ctypes.c_int
@@ -118,11 +118,12 @@ def fipa_forward(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, ga
 
 def fipa_backward(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,
                   o, o_pts, o_pair, lse, d_o, d_o_pts, d_o_pair,
-                  d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2, d_gamma, d_w_b, workspace):
-    """Enqueue fipa_backward on torch's current stream; d_w_b may be None."""
+                  d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2, d_gamma, d_w_b, d_rot, d_trans,
+                  workspace):
+    """Enqueue fipa_backward on torch's current stream; d_w_b and (d_rot, d_trans) may be None."""
     args = [q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,
             o, o_pts, o_pair, lse, d_o, d_o_pts, d_o_pair,
-            d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2, d_gamma, d_w_b]
+            d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2, d_gamma, d_w_b, d_rot, d_trans]
     rc = lib().fipa_backward(ctypes.byref(desc), *[_ptr(t) for t in args], _ptr(workspace),
                              ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
     if rc != FIPA_OK:
@@ -236,6 +237,8 @@ def alloc_grads(desc, device="cuda:0"):
                 d_z1=torch.empty(B, L, desc.r, desc.cz, **f), d_z2=torch.empty(B, L, desc.r, desc.cz, **f),
                 d_gamma=torch.empty(H, dtype=torch.float32, device=device),
                 d_w_b=torch.empty(H, desc.cz, dtype=torch.float32, device=device),
+                d_rot=torch.empty(B, L, 3, 3, dtype=torch.float32, device=device),
+                d_trans=torch.empty(B, L, 3, dtype=torch.float32, device=device),
                 workspace=torch.empty(max(bwd, 16), dtype=torch.uint8, device=device))
 
 
@@ -247,4 +250,4 @@ def backward(desc, dev, out, grads):
                   dev["d_o"], dev["d_o_pts"], dev["d_o_pair"],
                   grads["d_q"], grads["d_k"], grads["d_v"], grads["d_q_pts"], grads["d_k_pts"],
                   grads["d_v_pts"], grads["d_z1"], grads["d_z2"], grads["d_gamma"], grads.get("d_w_b"),
-                  grads["workspace"])
+                  grads.get("d_rot"), grads.get("d_trans"), grads["workspace"])

@@ -99,7 +99,7 @@ int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const voi
                   const float *o_pair, const float *lse, const float *d_o, const float *d_o_pts,
                   const float *d_o_pair, void *d_q, void *d_k, void *d_v, void *d_q_pts,
                   void *d_k_pts, void *d_v_pts, void *d_z1, void *d_z2, float *d_gamma, float *d_w_b,
-                  void *workspace, size_t workspace_bytes, void *hip_stream)
+                  float *d_rot, float *d_trans, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     int rc = check_desc(desc, true);
     if (rc != FIPA_OK) return rc;
@@ -111,6 +111,8 @@ int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const voi
         if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
     }
     if (d_w_b && !aligned16(d_w_b)) return FIPA_ERR_ALIGNMENT;
+    if ((d_rot == nullptr) != (d_trans == nullptr)) return FIPA_ERR_INVALID_ARG;
+    if (d_rot && (!aligned16(d_rot) || !aligned16(d_trans))) return FIPA_ERR_ALIGNMENT;
     size_t need = 0;
     fipa_workspace_bytes(desc, nullptr, &need);
     if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
@@ -121,6 +123,7 @@ int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const voi
     a.d_o = d_o; a.d_o_pts = d_o_pts; a.d_o_pair = d_o_pair;
     a.d_q = d_q; a.d_k = d_k; a.d_v = d_v; a.d_q_pts = d_q_pts; a.d_k_pts = d_k_pts;
     a.d_v_pts = d_v_pts; a.d_z1 = d_z1; a.d_z2 = d_z2; a.d_gamma = d_gamma; a.d_w_b = d_w_b;
+    a.d_rot = d_rot; a.d_trans = d_trans;
     const hipError_t e = bf16_backward(*desc, a, workspace, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
 }

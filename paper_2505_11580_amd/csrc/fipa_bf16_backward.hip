@@ -73,6 +73,10 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
     for (int a = 0; a < 9; ++a) Rm[a] = R[a];
     for (int a = 0; a < 3; ++a) tc[a] = t[a] - p.cen[4 * b + a];
 
+    // frame gradients: every global-frame point gradient g of a point with local coordinates x
+    // contributes g to d t_i and g x^T to d R_i (G = R_i x + t_i); the output points
+    // o_pts = R_i^T (G - t_i) contribute -R_i d_o_pts and (G - t_i) d_o_pts^T
+    float ft[3] = {0.f, 0.f, 0.f}, fr[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const int HP = 256 / NTASK;  // heads per pass: the tasks of one head stay inside one pass
     for (int h0 = 0; h0 < p.H; h0 += HP) {
         float gpartial = 0.f;
@@ -116,6 +120,11 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
                     }
                 }
                 gpartial = gacc;
+                const float lc[3] = {lx, ly, lz};
+                for (int x = 0; x < 3; ++x) {
+                    ft[x] += grad[x];
+                    for (int y = 0; y < 3; ++y) fr[3 * x + y] += grad[x] * lc[y];
+                }
                 bf16_t *dst = (isq ? p.d_q_pts : p.d_k_pts) + (rec * Pq + pt) * 3;
                 for (int x = 0; x < 3; ++x) {
                     const float val = Rm[x] * grad[0] + Rm[3 + x] * grad[1] + Rm[6 + x] * grad[2];  // R^T
@@ -125,6 +134,17 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
                 const int pt = tk - 2 * Pq;
                 float grad[3];
                 for (int a = 0; a < 3; ++a) grad[a] = dV[v_pt_col(c, Pv, pt, a, 0)];
+                if (p.d_rot) {
+                    const bf16_t *vl = p.v_pts + (rec * Pv + pt) * 3;
+                    const float *gp = p.d_o_pts + (rec * Pv + pt) * 3;
+                    const float *oh = p.Ohat + (bh * p.Lp + i) * D;
+                    for (int x = 0; x < 3; ++x) {
+                        const float dGx = Rm[3 * x] * gp[0] + Rm[3 * x + 1] * gp[1] + Rm[3 * x + 2] * gp[2];  // R_i d_o_pts
+                        const float Gm = oh[v_pt_col(c, Pv, pt, x, 0)] + oh[v_pt_col(c, Pv, pt, x, 1)] - tc[x];
+                        ft[x] += grad[x] - dGx;
+                        for (int y = 0; y < 3; ++y) fr[3 * x + y] += grad[x] * bf2f(vl[y]) + Gm * gp[y];
+                    }
+                }
                 bf16_t *dst = p.d_v_pts + (rec * Pv + pt) * 3;
                 for (int x = 0; x < 3; ++x) {
                     const float val = Rm[x] * grad[0] + Rm[3 + x] * grad[1] + Rm[6 + x] * grad[2];
@@ -147,6 +167,21 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
             for (int x = 0; x < 2 * Pq; ++x) s += gsm[tid + x];
             p.gpart[((size_t)b * p.H + h) * p.Lp + i] = valid ? s : 0.f;
         }
+    }
+
+    // frame gradients of this residue: sum over the threads in a fixed order
+    if (p.d_rot) {
+        __shared__ float fsm[12][256];
+        for (int x = 0; x < 3; ++x) fsm[x][tid] = ft[x];
+        for (int x = 0; x < 9; ++x) fsm[3 + x][tid] = fr[x];
+        __syncthreads();
+        for (int st = 128; st > 0; st >>= 1) {
+            if (tid < st)
+                for (int x = 0; x < 12; ++x) fsm[x][tid] += fsm[x][tid + st];
+            __syncthreads();
+        }
+        if (tid < 3) p.d_trans[((size_t)b * p.L + i) * 3 + tid] = valid ? fsm[tid][0] : 0.f;
+        if (tid < 9) p.d_rot[((size_t)b * p.L + i) * 9 + tid] = valid ? fsm[3 + tid][0] : 0.f;
     }
 
     // pair factors: sums over heads
@@ -354,7 +389,8 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     // ---- back to the inputs ----------------------------------------------------------------------------
     timer.begin(2);
     BwdUnpackParams up;
-    up.q_pts = pk.q_pts; up.k_pts = pk.k_pts; up.z1 = pk.z1;
+    up.q_pts = pk.q_pts; up.k_pts = pk.k_pts; up.v_pts = pk.v_pts; up.z1 = pk.z1;
+    up.d_o_pts = a.d_o_pts; up.d_rot = a.d_rot; up.d_trans = a.d_trans;
     up.rot = a.f.rot; up.trans = a.f.trans; up.cen = cen; up.gamma = a.f.gamma; up.w_b = a.f.w_b;
     up.d_o_pair = a.d_o_pair; up.mask = a.f.mask;
     up.dQhat = (const float *)(base + w.dQhat); up.dKhat = (const float *)(base + w.dKhat);

@@ -191,14 +191,15 @@ struct BwdPackParams {
 };
 
 struct BwdUnpackParams {
-    const bf16_t *q_pts, *k_pts, *z1;
-    const float *rot, *trans, *cen, *gamma, *w_b, *d_o_pair;
+    const bf16_t *q_pts, *k_pts, *v_pts, *z1;
+    const float *rot, *trans, *cen, *gamma, *w_b, *d_o_pair, *d_o_pts;
     const uint8_t *mask;
     const float *dQhat, *dKhat, *dVhat, *Ohat, *rowsum, *colsum;
     bf16_t *d_q, *d_k, *d_v, *d_q_pts, *d_k_pts, *d_v_pts, *d_z1, *d_z2;
     float *gpart;   // [B,H,Lp] per-(b,h,i) contribution to d gamma
     float *d_gamma; // [H]
     float *d_w_b;   // [H, cz] or null
+    float *d_rot, *d_trans;  // [B, L, 3, 3], [B, L, 3] or null
     float *wpart;   // [H, ceil(B*L/128), DZ] partial sums of d w_b
     int B, L, Lp, H, c, Pq, Pv, cz, r, DZ;
     float w_L, w_C, qk_scale;

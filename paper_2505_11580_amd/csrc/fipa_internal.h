@@ -29,7 +29,8 @@ struct BwdArgs {
     const float *d_o, *d_o_pts, *d_o_pair;
     void *d_q, *d_k, *d_v, *d_q_pts, *d_k_pts, *d_v_pts, *d_z1, *d_z2;
     float *d_gamma;
-    float *d_w_b;  // may be null
+    float *d_w_b;            // may be null
+    float *d_rot, *d_trans;  // both or neither
 };
 
 // Arguments of fipa_module_forward beyond the description.

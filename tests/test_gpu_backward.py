@@ -12,7 +12,8 @@ from tests import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 GRADS = (("d_q", "dq"), ("d_k", "dk"), ("d_v", "dv"), ("d_q_pts", "dq_pts"), ("d_k_pts", "dk_pts"),
-         ("d_v_pts", "dv_pts"), ("d_z1", "dz1"), ("d_z2", "dz2"), ("d_gamma", "dgamma"), ("d_w_b", "dw_b"))
+         ("d_v_pts", "dv_pts"), ("d_z1", "dz1"), ("d_z2", "dz2"), ("d_gamma", "dgamma"), ("d_w_b", "dw_b"),
+         ("d_rot", "drot"), ("d_trans", "dtrans"))
 
 
 def run_gpu_backward(inp):
@@ -80,5 +81,12 @@ def test_backward_full_size_properties():
     moved["rot"] = np.einsum("xy,blyz->blxz", Rg, inp["rot"]).astype(np.float32)
     moved["trans"] = (np.einsum("xy,bly->blx", Rg, inp["trans"]) + tg).astype(np.float32)
     g3 = run_gpu_backward(moved)
+    # the frame gradients are global-frame objects: they turn with the global rotation
+    g3["d_rot"] = np.einsum("yx,blyz->blxz", Rg.astype(np.float64), g3["d_rot"])
+    g3["d_trans"] = np.einsum("yx,bly->blx", Rg.astype(np.float64), g3["d_trans"])
     for n, _ in GRADS:
         assert gu.rel_err(g3[n], g1[n]) <= 2e-2, n
+    # a common shift of all frames changes nothing: the translation gradients of a chain sum to zero
+    # (up to the rounding noise of L independent terms)
+    L = g1["d_trans"].shape[1]
+    assert np.abs(g1["d_trans"].sum(axis=1)).max() <= 2e-2 * np.abs(g1["d_trans"]).max() * np.sqrt(L)
