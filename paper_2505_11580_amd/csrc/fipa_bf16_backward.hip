@@ -138,8 +138,11 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
                     const bf16_t *vl = p.v_pts + (rec * Pv + pt) * 3;
                     const float *gp = p.d_o_pts + (rec * Pv + pt) * 3;
                     const float *oh = p.Ohat + (bh * p.Lp + i) * D;
+                    const bf16_t *dgh = p.dOhat + (bh * p.Lp + i) * D;
                     for (int x = 0; x < 3; ++x) {
-                        const float dGx = Rm[3 * x] * gp[0] + Rm[3 * x + 1] * gp[1] + Rm[3 * x + 2] * gp[2];  // R_i d_o_pts
+                        // R_i d_o_pts, in the rounded form that the gradient kernels used: it then cancels
+                        // against the value-point term exactly where the mathematics says so (shift invariance)
+                        const float dGx = bf2f(dgh[v_pt_col(c, Pv, pt, x, 0)]);
                         const float Gm = oh[v_pt_col(c, Pv, pt, x, 0)] + oh[v_pt_col(c, Pv, pt, x, 1)] - tc[x];
                         ft[x] += grad[x] - dGx;
                         for (int y = 0; y < 3; ++y) fr[3 * x + y] += grad[x] * bf2f(vl[y]) + Gm * gp[y];
@@ -390,7 +393,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     timer.begin(2);
     BwdUnpackParams up;
     up.q_pts = pk.q_pts; up.k_pts = pk.k_pts; up.v_pts = pk.v_pts; up.z1 = pk.z1;
-    up.d_o_pts = a.d_o_pts; up.d_rot = a.d_rot; up.d_trans = a.d_trans;
+    up.d_o_pts = a.d_o_pts; up.d_rot = a.d_rot; up.d_trans = a.d_trans; up.dOhat = bp.dOhat;
     up.rot = a.f.rot; up.trans = a.f.trans; up.cen = cen; up.gamma = a.f.gamma; up.w_b = a.f.w_b;
     up.d_o_pair = a.d_o_pair; up.mask = a.f.mask;
     up.dQhat = (const float *)(base + w.dQhat); up.dKhat = (const float *)(base + w.dKhat);

@@ -191,7 +191,7 @@ struct BwdPackParams {
 };
 
 struct BwdUnpackParams {
-    const bf16_t *q_pts, *k_pts, *v_pts, *z1;
+    const bf16_t *q_pts, *k_pts, *v_pts, *z1, *dOhat;
     const float *rot, *trans, *cen, *gamma, *w_b, *d_o_pair, *d_o_pts;
     const uint8_t *mask;
     const float *dQhat, *dKhat, *dVhat, *Ohat, *rowsum, *colsum;

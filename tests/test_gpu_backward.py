@@ -33,9 +33,12 @@ def check_backward(inp, label, tol=2e-2):
     got = run_gpu_backward(inp)
     want = ipa_oracle.backward(inp, inp["d_o"], inp["d_o_pts"], inp["d_o_pair"])
     errs = {}
+    # a gradient that is exactly zero in the oracle (a single key: constant softmax) is measured
+    # against the scale of the value gradient instead of its own
+    floor = 1e-3 * float(np.abs(want["dv"]).max())
     for n, o in GRADS:
         assert np.all(np.isfinite(got[n])), (label, n)
-        errs[n] = gu.rel_err(got[n], want[o])
+        errs[n] = float(np.abs(got[n] - want[o]).max()) / max(float(np.abs(want[o]).max()), floor)
     print(label, {k: "%.1e" % v for k, v in errs.items()}, flush=True)
     for n, _ in GRADS:
         assert errs[n] <= tol, (label, n, errs[n])
@@ -90,3 +93,8 @@ def test_backward_full_size_properties():
     # (up to the rounding noise of L independent terms)
     L = g1["d_trans"].shape[1]
     assert np.abs(g1["d_trans"].sum(axis=1)).max() <= 2e-2 * np.abs(g1["d_trans"]).max() * np.sqrt(L)
+
+
+def test_backward_degenerate_shapes():
+    check_backward(wl.make_inputs(4, B=1, L=1, H=1), "bwd L=1 H=1")
+    check_backward(wl.make_inputs(4, B=2, L=40, H=2, cz=16, r=2, trans_scale=0.2), "bwd L=40 DZ=32")

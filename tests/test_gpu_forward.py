@@ -133,3 +133,36 @@ def test_runs_are_bit_identical():
     a, b = gu.run_gpu(inp), gu.run_gpu(inp)
     for n in gu.NAMES + ("lse",):
         assert np.array_equal(a[n], b[n]), n
+
+
+def test_bf16_degenerate_shapes():
+    # a single residue, a single head, and a chain shorter than one key block
+    gu.check(wl.make_inputs(1, B=1, L=1, H=1), label="bf16 L=1 H=1")
+    gu.check(wl.make_inputs(1, B=2, L=3, H=2, cz=16, r=2), label="bf16 L=3")
+    gu.check(wl.make_inputs(1, B=1, L=33, H=1, trans_scale=0.1), label="bf16 L=33 H=1")
+
+
+def test_bf16_batch_element_without_valid_residues():
+    # one chain of the batch is fully masked: its outputs are zero, the others are unaffected
+    inp = wl.make_inputs(1, B=3, L=150, H=2, trans_scale=0.3)
+    mask = np.ones((3, 150), dtype=np.uint8)
+    mask[1, :] = 0
+    mask[2, 100:] = 0
+    inp["mask"] = mask
+    got = gu.run_gpu(inp)
+    for n in gu.NAMES:
+        assert np.all(np.isfinite(got[n])), n
+        assert np.all(got[n][1] == 0), n
+    keep = dict(inp)
+    for n in ("q", "k", "v", "q_pts", "k_pts", "v_pts", "rot", "trans", "z1", "z2"):
+        keep[n] = inp[n][[0, 2]]
+    keep["mask"] = mask[[0, 2]]
+    keep["dims"] = dict(inp["dims"], B=2)
+    want = ipa_oracle_forward(keep)
+    for n in gu.NAMES:
+        assert gu.rel_err(got[n][[0, 2]], want[n]) <= 2e-2, n
+
+
+def ipa_oracle_forward(inp):
+    from oracle import ipa_oracle
+    return ipa_oracle.forward(inp)
