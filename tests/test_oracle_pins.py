@@ -407,3 +407,37 @@ def test_module_input_projection_orientation_and_rounding():
     flat = np.concatenate([full[n].reshape(d["B"], d["L"], -1) for n in ("q", "k", "v", "q_pts", "k_pts", "v_pts")], -1)
     assert np.abs(flat - ref).max() <= 2.0 ** -8 * np.abs(ref).max()      # half an ulp of bf16
     assert np.array_equal(flat.astype(np.float32).view(np.uint32) & 0xFFFF, np.zeros(flat.shape, np.uint32))
+
+
+def test_module_backward_matches_central_differences():
+    """Every gradient of the module against central differences of its (unrounded) forward."""
+    from oracle import module_ref
+    from paper_2505_11580_amd import workloads as wl
+    m = wl.make_module_inputs(1, d_s=8, seed=11, B=1, L=4, H=1, cz=8, r=2, varlen=False, dtype="bf16")
+    m["mask"] = np.array([[1, 1, 0, 1]], dtype=np.uint8)
+    for n in ("s", "w_in", "b_in", "w_out", "b_out"):
+        m[n] = np.asarray(m[n], dtype=np.float64)
+    rng = np.random.default_rng(12)
+    up = rng.standard_normal((1, 4, 8))
+
+    def loss(mm):
+        return float(np.sum(module_ref.module_forward(mm, rounded=False) * up))
+
+    g = module_ref.module_backward(m, up, rounded=False)
+    h = 1e-5
+    for src, dst in (("s", "ds"), ("b_in", "db_in"), ("w_out", "dw_out"), ("b_out", "db_out"), ("w_in", "dw_in")):
+        base = m[src]
+        fd = np.zeros_like(base)
+        idxs = list(np.ndindex(base.shape))
+        if len(idxs) > 150:                      # w_in, w_out: a fixed sample of entries
+            idxs = [idxs[i] for i in np.random.default_rng(13).choice(len(idxs), 150, replace=False)]
+        for idx in idxs:
+            vals = []
+            for sgn in (+1, -1):
+                pert = base.copy(); pert[idx] += sgn * h
+                vals.append(loss(dict(m, **{src: pert})))
+            fd[idx] = (vals[0] - vals[1]) / (2 * h)
+        sel = tuple(np.array(idxs).T)
+        scale = max(np.abs(fd[sel]).max(), 1e-12)
+        assert np.abs(g[dst][sel] - fd[sel]).max() / scale < 1e-6, (src, np.abs(g[dst][sel] - fd[sel]).max() / scale)
+    assert np.all(g["ds"][0, 2] == 0)            # a masked residue receives no gradient
