@@ -97,9 +97,22 @@ def module_leg(workload, d_s=256, steps=50, warmup=5):
     ms = (time.perf_counter() - t0) / steps * 1e3
     n_in, n_cat = workloads.module_widths(m["dims"])
     rows = m["dims"]["B"] * m["dims"]["L"]
-    return {"workload": "workload %d with d_s=%d" % (workload, d_s), "ms_per_call": ms, "steps": steps,
-            "projection_gflop": 2.0 * rows * d_s * (n_in + n_cat) / 1e9,
-            "residues_per_s": float(m["lengths"].sum()) / (ms * 1e-3)}
+    out = {"workload": "workload %d with d_s=%d" % (workload, d_s), "ms_per_call": ms, "steps": steps,
+           "projection_gflop": 2.0 * rows * d_s * (n_in + n_cat) / 1e9,
+           "residues_per_s": float(m["lengths"].sum()) / (ms * 1e-3)}
+    # fipa_module_backward on the same inputs (recomputes the forward inside)
+    grads = binding.alloc_module_grads(desc, d_s)
+    up = torch.randn(m["dims"]["B"], m["dims"]["L"], d_s, device="cuda:0")
+    bsteps = max(3, steps // 5)
+    for _ in range(2):
+        binding.module_backward(desc, d_s, dev, up, grads)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(bsteps):
+        binding.module_backward(desc, d_s, dev, up, grads)
+    torch.cuda.synchronize()
+    out["backward_ms_per_call"] = (time.perf_counter() - t0) / bsteps * 1e3
+    return out
 
 
 def calibrate_copy(nbytes=256 << 20):

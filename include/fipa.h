@@ -156,6 +156,29 @@ int fipa_module_forward(const fipa_desc *desc, int32_t d_s,
                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Backward of fipa_module_forward: gradients of a scalar loss, given d_s_out [B, L, d_s] float32,
+ * with respect to s (d_s_in [B, L, d_s] float32), the two Linear layers (d_w_in [N_in, d_s],
+ * d_w_out [d_s, N_cat], float32; d_b_in [N_in], d_b_out [d_s], float32 or NULL) and, passed
+ * through from fipa_backward, z1, z2 (bfloat16), gamma, w_b (or NULL) and the frames (d_rot,
+ * d_trans, both or neither).  Everything is recomputed from the inputs: no forward results are
+ * taken.  The bfloat16 rounding of Eq. 1's results is transparent to the gradient; the norm of a
+ * zero vector contributes zero.  All outputs are overwritten.
+ * Shapes: as fipa_module_forward, and r*cz <= 256, N_in % 8 == 0; else FIPA_ERR_UNSUPPORTED.
+ */
+int fipa_module_backward_workspace_bytes(const fipa_desc *desc, int32_t d_s, size_t *bytes);
+int fipa_module_backward(const fipa_desc *desc, int32_t d_s,
+                         const void *s, const void *w_in, const float *b_in,
+                         const float *rot, const float *trans,
+                         const void *z1, const void *z2,
+                         const float *w_b, const float *gamma, const uint8_t *mask,
+                         const void *w_out, const float *b_out,
+                         const float *d_s_out,
+                         float *d_s_in, float *d_w_in, float *d_b_in, float *d_w_out, float *d_b_out,
+                         void *d_z1, void *d_z2, float *d_gamma, float *d_w_b,
+                         float *d_rot, float *d_trans,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Optional stage timing for benchmarks.  Between fipa_profile_begin() and fipa_profile_end()
  * every fipa_forward / fipa_backward call on any stream additionally records HIP events around
  * its stages on that stream (up to `capacity` calls; later calls run untimed).  This is the only

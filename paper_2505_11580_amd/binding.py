@@ -25,6 +25,7 @@ FIPA_DTYPE_BF16 = 1
 
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
            "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
+           "fipa_module_backward_workspace_bytes", "fipa_module_backward",
            "fipa_profile_begin", "fipa_profile_end")
 PROFILE_STAGES = 3
 
@@ -66,6 +67,10 @@ def lib():
         L.fipa_module_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32, ctypes.POINTER(sz)]
         L.fipa_module_forward.restype = ctypes.c_int
         L.fipa_module_forward.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32] + [vp] * 13 + [vp, sz, vp]
+        L.fipa_module_backward_workspace_bytes.restype = ctypes.c_int
+        L.fipa_module_backward_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32, ctypes.POINTER(sz)]
+        L.fipa_module_backward.restype = ctypes.c_int
+        L.fipa_module_backward.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32] + [vp] * 24 + [vp, sz, vp]
         L.fipa_profile_begin.restype = ctypes.c_int
         L.fipa_profile_begin.argtypes = [ctypes.c_int]
         L.fipa_profile_end.restype = ctypes.c_int
@@ -221,6 +226,39 @@ def module_forward(desc, d_s, dev):
     fipa_module_forward(desc, d_s, dev["s"], dev["w_in"], dev["b_in"], dev["rot"], dev["trans"], dev["z1"],
                         dev["z2"], dev["w_b"], dev["gamma"], dev["mask"], dev["w_out"], dev["b_out"], dev["s_out"],
                         dev["workspace"])
+
+
+def alloc_module_grads(desc, d_s, device="cuda:0"):
+    """Gradient tensors and the workspace of fipa_module_backward."""
+    import torch
+    B, L, H = desc.B, desc.L, desc.H
+    n_in = H * (3 * desc.c + 3 * (2 * desc.Pq + desc.Pv))
+    n_cat = H * (desc.cz + desc.c + 4 * desc.Pv)
+    f = dict(dtype=torch.float32, device=device)
+    n = ctypes.c_size_t(0)
+    rc = lib().fipa_module_backward_workspace_bytes(ctypes.byref(desc), int(d_s), ctypes.byref(n))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_module_backward_workspace_bytes")
+    return dict(d_s=torch.empty(B, L, d_s, **f), d_w_in=torch.empty(n_in, d_s, **f), d_b_in=torch.empty(n_in, **f),
+                d_w_out=torch.empty(d_s, n_cat, **f), d_b_out=torch.empty(d_s, **f),
+                d_z1=torch.empty(B, L, desc.r, desc.cz, dtype=torch.bfloat16, device=device),
+                d_z2=torch.empty(B, L, desc.r, desc.cz, dtype=torch.bfloat16, device=device),
+                d_gamma=torch.empty(H, **f), d_w_b=torch.empty(H, desc.cz, **f),
+                d_rot=torch.empty(B, L, 3, 3, **f), d_trans=torch.empty(B, L, 3, **f),
+                workspace=torch.empty(max(n.value, 16), dtype=torch.uint8, device=device))
+
+
+def module_backward(desc, d_s, dev, d_s_out, grads):
+    """dev: tensors of upload_module; d_s_out: float32 device tensor [B, L, d_s]."""
+    args = [dev["s"], dev["w_in"], dev["b_in"], dev["rot"], dev["trans"], dev["z1"], dev["z2"], dev["w_b"],
+            dev["gamma"], dev["mask"], dev["w_out"], dev["b_out"], d_s_out,
+            grads["d_s"], grads["d_w_in"], grads["d_b_in"], grads["d_w_out"], grads["d_b_out"],
+            grads["d_z1"], grads["d_z2"], grads["d_gamma"], grads["d_w_b"], grads["d_rot"], grads["d_trans"]]
+    ws = grads["workspace"]
+    rc = lib().fipa_module_backward(ctypes.byref(desc), int(d_s), *[_ptr(t) for t in args], _ptr(ws),
+                                    ctypes.c_size_t(ws.numel()), _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_module_backward")
 
 
 def alloc_grads(desc, device="cuda:0"):

@@ -157,4 +157,41 @@ int fipa_module_forward(const fipa_desc *desc, int32_t d_s, const void *s, const
     return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
 }
 
+int fipa_module_backward_workspace_bytes(const fipa_desc *desc, int32_t d_s, size_t *bytes)
+{
+    if (bytes) *bytes = 0;
+    const int rc = check_desc(desc, true);
+    if (rc != FIPA_OK) return rc;
+    if (!module_backward_shape_supported(*desc, d_s)) return FIPA_ERR_UNSUPPORTED;
+    if (bytes) *bytes = module_backward_workspace(*desc, d_s);
+    return FIPA_OK;
+}
+
+int fipa_module_backward(const fipa_desc *desc, int32_t d_s, const void *s, const void *w_in, const float *b_in,
+                         const float *rot, const float *trans, const void *z1, const void *z2, const float *w_b,
+                         const float *gamma, const uint8_t *mask, const void *w_out, const float *b_out,
+                         const float *d_s_out, float *d_s_in, float *d_w_in, float *d_b_in, float *d_w_out,
+                         float *d_b_out, void *d_z1, void *d_z2, float *d_gamma, float *d_w_b, float *d_rot,
+                         float *d_trans, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    size_t need = 0;
+    const int rc = fipa_module_backward_workspace_bytes(desc, d_s, &need);
+    if (rc != FIPA_OK) return rc;
+    const void *req[] = {s, w_in, rot, trans, z1, z2, w_b, gamma, w_out, d_s_out, d_s_in, d_w_in, d_w_out, d_z1, d_z2,
+                         d_gamma, workspace};
+    for (const void *ptr : req) {
+        if (!ptr) return FIPA_ERR_INVALID_ARG;
+        if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
+    }
+    if ((d_rot == nullptr) != (d_trans == nullptr)) return FIPA_ERR_INVALID_ARG;
+    const void *opt[] = {b_in, b_out, d_b_in, d_b_out, d_w_b, d_rot, d_trans};
+    for (const void *ptr : opt)
+        if (ptr && !aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
+    if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
+    const ModuleArgs a{s, w_in, b_in, rot, trans, z1, z2, w_b, gamma, mask, w_out, b_out, nullptr};
+    const ModuleBwdArgs g{d_s_out, d_s_in, d_w_in, d_b_in, d_w_out, d_b_out, d_z1, d_z2, d_gamma, d_w_b, d_rot, d_trans};
+    const hipError_t e = module_backward(*desc, d_s, a, g, workspace, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
+}
+
 }  // extern "C"

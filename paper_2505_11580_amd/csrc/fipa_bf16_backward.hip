@@ -225,25 +225,27 @@ __global__ __launch_bounds__(256) void fipa_bwd_gamma_kernel(const float *gpart,
 
 // d w_b[h, d] = w_L * sum over (batch, residue, rho) of z1[b,i,rho,d] * dQ^[b,h,i, 64 + rho*cz + d]
 // (b^{h1} = w_L w_b (.) z1, Algorithm 1 step 2 with Eq. 3's w_L).  Two passes with a fixed
-// summation order: per (head, chunk of 128 residues) partial sums per lifted column, then the
+// summation order: per (head, chunk of 32 residues) partial sums per lifted column, then the
 // sum over chunks and rho.
-constexpr int kWbChunk = 128;
+constexpr int kWbChunk = 32;
 
 __global__ __launch_bounds__(256) void fipa_bwd_wb_partial_kernel(BwdUnpackParams p)
 {
     const int h = blockIdx.y, chunk = blockIdx.x, D = kDH + p.DZ;
     const int nres = p.B * p.L;
     for (int x = threadIdx.x; x < p.DZ; x += 256) {
-        float s = 0.f;
-        for (int t = 0; t < kWbChunk; ++t) {
-            const int bi = chunk * kWbChunk + t;
-            if (bi >= nres) break;
-            const int b = bi / p.L, i = bi - b * p.L;
-            const bool valid = p.mask ? p.mask[bi] != 0 : true;
-            if (valid)
-                s += bf2f(p.z1[(size_t)bi * p.DZ + x]) * p.dQhat[(((size_t)b * p.H + h) * p.Lp + i) * D + kDH + x];
+        float s4[4] = {0.f, 0.f, 0.f, 0.f};  // four independent chains of loads; summed in a fixed order
+        for (int t0 = 0; t0 < kWbChunk; t0 += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int bi = min(chunk * kWbChunk + t0 + u, nres - 1);
+                const int b = bi / p.L, i = bi - b * p.L;
+                const bool valid = chunk * kWbChunk + t0 + u < nres && (p.mask ? p.mask[bi] != 0 : true);
+                const float prod = bf2f(p.z1[(size_t)bi * p.DZ + x]) * p.dQhat[(((size_t)b * p.H + h) * p.Lp + i) * D + kDH + x];
+                s4[u] += valid ? prod : 0.f;
+            }
         }
-        p.wpart[((size_t)h * gridDim.x + chunk) * p.DZ + x] = s;
+        p.wpart[((size_t)h * gridDim.x + chunk) * p.DZ + x] = (s4[0] + s4[1]) + (s4[2] + s4[3]);
     }
 }
 

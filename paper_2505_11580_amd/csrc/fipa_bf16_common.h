@@ -200,7 +200,7 @@ struct BwdUnpackParams {
     float *d_gamma; // [H]
     float *d_w_b;   // [H, cz] or null
     float *d_rot, *d_trans;  // [B, L, 3, 3], [B, L, 3] or null
-    float *wpart;   // [H, ceil(B*L/128), DZ] partial sums of d w_b
+    float *wpart;   // [H, ceil(B*L/32), DZ] partial sums of d w_b
     int B, L, Lp, H, c, Pq, Pv, cz, r, DZ;
     float w_L, w_C, qk_scale;
 };

@@ -46,6 +46,14 @@ struct ModuleArgs {
     float *s_out;
 };
 
+// Arguments of fipa_module_backward beyond those of the forward.
+struct ModuleBwdArgs {
+    const float *d_s_out;
+    float *d_s_in, *d_w_in, *d_b_in, *d_w_out, *d_b_out;  // the two bias gradients may be null
+    void *d_z1, *d_z2;
+    float *d_gamma, *d_w_b, *d_rot, *d_trans;             // d_w_b and the frame pair may be null
+};
+
 // Stage timing (fipa_profile_begin / fipa_profile_end).  A StageTimer is created per API call;
 // when profiling is inactive every method is a no-op.
 class StageTimer {
@@ -78,8 +86,12 @@ size_t bf16_backward_workspace(const fipa_desc &d);
 
 // IPA module around the core (fipa_module.hip)
 bool module_shape_supported(const fipa_desc &d, int d_s);
+bool module_backward_shape_supported(const fipa_desc &d, int d_s);
 size_t module_forward_workspace(const fipa_desc &d);
 hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void *ws, hipStream_t stream);
+size_t module_backward_workspace(const fipa_desc &d, int d_s);
+hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, const ModuleBwdArgs &g, void *ws,
+                           hipStream_t stream);
 hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream);
 
 }  // namespace fipa

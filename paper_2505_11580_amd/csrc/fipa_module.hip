@@ -23,6 +23,8 @@ struct GemmParams {
     float *C;            // [M, N] float32                      (output projection)
     bf16_t *seg_ptr[6];  // six row-major bf16 tensors [M, width] (input projection)
     int seg_start[7];    // first column of each, and N
+    int chunks_per_split;  // 0: one workgroup sums all of K; else blockIdx.z takes this many K chunks
+                           // and writes its partial product to C + blockIdx.z * M * N
 };
 
 __device__ __forceinline__ bf16x8 to_bf16x8(const float (&v)[8])
@@ -159,13 +161,17 @@ __global__ __launch_bounds__(256) void fipa_gemm_kernel(GemmParams p)
         for (int b = 0; b < NTW; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-    const int nkc = (p.K + kGK - 1) / kGK;
+    int kc0 = 0, nkc = (p.K + kGK - 1) / kGK;
+    if (p.chunks_per_split > 0) {
+        kc0 = blockIdx.z * p.chunks_per_split;
+        nkc = min(nkc, kc0 + p.chunks_per_split);
+    }
     Staged st;
-    fetch(0, st);
-    stash(0, 0, st);
+    fetch(kc0, st);
+    stash(0, kc0, st);
     __syncthreads();
-    for (int kc = 0; kc < nkc; ++kc) {
-        const int buf = kc & 1;
+    for (int kc = kc0; kc < nkc; ++kc) {
+        const int buf = (kc - kc0) & 1;
         if (kc + 1 < nkc) fetch(kc + 1, st);
         const char *at = lds + buf * kBuf + (32 * MTW * wm + li) * kGRS + kg * 16;
         const char *wt = lds + buf * kBuf + T::TM * kGRS + (32 * NTW * wn + li) * kGRS + kg * 16;
@@ -221,10 +227,11 @@ __global__ __launch_bounds__(256) void fipa_gemm_kernel(GemmParams p)
                         }
                     }
                 } else {
+                    float *C = p.C + (p.chunks_per_split > 0 ? (size_t)blockIdx.z * p.M * p.N : 0);
                     if (col + 3 < p.N && (p.N & 3) == 0) {
-                        *reinterpret_cast<f32x4 *>(p.C + (size_t)row * p.N + col) = (f32x4){val[0], val[1], val[2], val[3]};
+                        *reinterpret_cast<f32x4 *>(C + (size_t)row * p.N + col) = (f32x4){val[0], val[1], val[2], val[3]};
                     } else {
-                        for (int x = 0; x < 4 && col + x < p.N; ++x) p.C[(size_t)row * p.N + col + x] = val[x];
+                        for (int x = 0; x < 4 && col + x < p.N; ++x) C[(size_t)row * p.N + col + x] = val[x];
                     }
                 }
             }
@@ -237,8 +244,11 @@ hipError_t launch_gemm(const GemmParams &g, hipStream_t stream)
     hipError_t e = hipFuncSetAttribute((const void *)fipa_gemm_kernel<T, CONCAT_A, SCATTER>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((fipa_gemm_kernel<T, CONCAT_A, SCATTER>), dim3((g.M + T::TM - 1) / T::TM, (g.N + T::TN - 1) / T::TN),
-                       dim3(256), T::LDS_BYTES, stream, g);
+    const int nkc = (g.K + kGK - 1) / kGK;
+    const int nsplit = g.chunks_per_split > 0 ? (nkc + g.chunks_per_split - 1) / g.chunks_per_split : 1;
+    hipLaunchKernelGGL((fipa_gemm_kernel<T, CONCAT_A, SCATTER>),
+                       dim3((g.M + T::TM - 1) / T::TM, (g.N + T::TN - 1) / T::TN, nsplit), dim3(256), T::LDS_BYTES,
+                       stream, g);
     return hipGetLastError();
 }
 
@@ -270,7 +280,184 @@ ModuleLayout module_layout(const fipa_desc &d)
     return w;
 }
 
+// ---- small memory-bound kernels of the module's backward ----------------------------------------
+
+// dst[c][r] = bf16(src[r][c]) for a row-major [R, C] matrix of float or bf16 (32 x 32 tiles through
+// LDS); dst has rows of length ld >= R, the tail of each row is set to zero.
+template <class SrcT>
+__global__ __launch_bounds__(256) void fipa_transpose_bf16_kernel(const SrcT *__restrict__ src, bf16_t *__restrict__ dst,
+                                                                  int R, int C, int ld)
+{
+    __shared__ bf16_t tile[32][33];
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    for (int j = ty; j < 32; j += 8) {
+        const int r = r0 + j, c = c0 + tx;
+        bf16_t v = 0;
+        if (r < R && c < C) {
+            if constexpr (sizeof(SrcT) == 4)
+                v = f2bf(((const float *)src)[(size_t)r * C + c]);
+            else
+                v = ((const bf16_t *)src)[(size_t)r * C + c];
+        }
+        tile[j][tx] = v;
+    }
+    __syncthreads();
+    for (int j = ty; j < 32; j += 8) {
+        const int c = c0 + j, r = r0 + tx;
+        if (r < ld && c < C) dst[(size_t)c * ld + r] = tile[tx][j];  // (tile entries with r >= R hold zero)
+    }
+}
+
+template <class SrcT>
+hipError_t launch_transpose(const SrcT *src, bf16_t *dst, int R, int C, int ld, hipStream_t stream)
+{
+    hipLaunchKernelGGL((fipa_transpose_bf16_kernel<SrcT>), dim3((C + 31) / 32, (ld + 31) / 32), dim3(256), 0, stream, src, dst,
+                       R, C, ld);
+    return hipGetLastError();
+}
+
+// float32 -> bf16 copy.
+__global__ __launch_bounds__(256) void fipa_to_bf16_kernel(const float *__restrict__ src, bf16_t *__restrict__ dst, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = f2bf(src[i]);
+}
+
+// Row r of the concatenation of Eq. 5 as bf16: [o_pair | o | o_pts | norms].
+__global__ __launch_bounds__(256) void fipa_concat_bf16_kernel(GemmParams p, bf16_t *__restrict__ cat)
+{
+    const int row = blockIdx.x;
+    for (int k = 8 * threadIdx.x; k < p.K; k += 8 * 256)
+        *reinterpret_cast<bf16x8 *>(cat + (size_t)row * p.K + k) = concat_chunk(p, row, k);
+}
+
+// Gradient of the concatenation back to the core's upstream gradients:
+//   d_o_pair, d_o copied; d_o_pts = its own columns + d_norm * o_pts / |o_pts| (zero at a zero vector).
+__global__ __launch_bounds__(256) void fipa_split_dcat_kernel(const float *__restrict__ dcat, const float *__restrict__ o_pts,
+                                                               float *__restrict__ d_o_pair, float *__restrict__ d_o,
+                                                               float *__restrict__ d_o_pts, int k_pair, int k_o, int k_pts)
+{
+    const int row = blockIdx.x;
+    const int K = k_pair + k_o + k_pts + k_pts / 3;
+    const float *src = dcat + (size_t)row * K;
+    for (int k = threadIdx.x; k < k_pair; k += 256) d_o_pair[(size_t)row * k_pair + k] = src[k];
+    for (int k = threadIdx.x; k < k_o; k += 256) d_o[(size_t)row * k_o + k] = src[k_pair + k];
+    for (int pt = threadIdx.x; pt < k_pts / 3; pt += 256) {
+        const float *op = o_pts + (size_t)row * k_pts + 3 * pt;
+        const float nrm = sqrtf(op[0] * op[0] + op[1] * op[1] + op[2] * op[2]);
+        const float gn = nrm > 0.f ? src[k_pair + k_o + k_pts + pt] / nrm : 0.f;
+        for (int x = 0; x < 3; ++x)
+            d_o_pts[(size_t)row * k_pts + 3 * pt + x] = src[k_pair + k_o + 3 * pt + x] + gn * op[x];
+    }
+}
+
+// The six bf16 gradient tensors of the core, side by side: dX [M, N_in].
+__global__ __launch_bounds__(256) void fipa_gather6_kernel(GemmParams p, bf16_t *__restrict__ dst)
+{
+    const int row = blockIdx.x;
+    for (int col = threadIdx.x; col < p.N; col += 256) {
+        int seg = 0;
+#pragma unroll
+        for (int s = 1; s < 6; ++s)
+            if (col >= p.seg_start[s]) seg = s;
+        const int width = p.seg_start[seg + 1] - p.seg_start[seg];
+        dst[(size_t)row * p.N + col] = p.seg_ptr[seg][(size_t)row * width + (col - p.seg_start[seg])];
+    }
+}
+
+// out[i] = sum over the nsplit partial matrices (fixed order), n entries each.
+__global__ __launch_bounds__(256) void fipa_sum_partials_kernel(const float *__restrict__ part, float *__restrict__ out,
+                                                                 size_t n, int nsplit)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int z = 0; z < nsplit; ++z) s += part[(size_t)z * n + i];
+    out[i] = s;
+}
+
+// out[r] = sum over the C entries of row r of a bf16 matrix [R, C] (one workgroup per row, fixed order).
+__global__ __launch_bounds__(256) void fipa_rowsum_bf16_kernel(const bf16_t *__restrict__ src, float *__restrict__ out, int C)
+{   // (rows may carry a zero tail: C is the stored row length)
+    __shared__ float red[256];
+    const int r = blockIdx.x;
+    float s = 0.f;
+    for (int c = threadIdx.x; c < C; c += 256) s += bf2f(src[(size_t)r * C + c]);
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[r] = red[0];
+}
+
+constexpr int kWgradChunks = 8;  // K chunks (of 64 rows of the batch) per workgroup of a weight-gradient product
+
+struct ModuleBwdLayout {
+    ModuleLayout f;   // forward part: core workspace slot (sized for the backward), core inputs and outputs
+    size_t g16, gT, w_outT, w_inT, sT, dcat, d_o, d_o_pts, d_o_pair, dq, dk, dv, dq_pts, dk_pts, dv_pts, dX, dXT, cat,
+        catT, part, total;
+};
+
+ModuleBwdLayout module_bwd_layout(const fipa_desc &d, int d_s)
+{
+    ModuleBwdLayout w;
+    const size_t M = (size_t)d.B * d.L, Mp = align_up(M, kGK);  // transposed matrices carry rows of Mp entries
+    const size_t n_in = (size_t)d.H * (3 * d.c + 3 * (2 * d.Pq + d.Pv)), n_cat = (size_t)d.H * (d.cz + d.c + 4 * d.Pv);
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    // the forward layout with the core slot enlarged to what the core's backward needs
+    w.f.core = take(bf16_backward_workspace(d) > bf16_forward_workspace(d) ? bf16_backward_workspace(d)
+                                                                           : bf16_forward_workspace(d));
+    w.f.q = take(M * d.H * d.c * 2);
+    w.f.k = take(M * d.H * d.c * 2);
+    w.f.v = take(M * d.H * d.c * 2);
+    w.f.q_pts = take(M * d.H * d.Pq * 3 * 2);
+    w.f.k_pts = take(M * d.H * d.Pq * 3 * 2);
+    w.f.v_pts = take(M * d.H * d.Pv * 3 * 2);
+    w.f.o = take(M * d.H * d.c * 4);
+    w.f.o_pts = take(M * d.H * d.Pv * 3 * 4);
+    w.f.o_pair = take(M * d.H * d.cz * 4);
+    w.f.total = 0;
+    w.g16 = take(M * d_s * 2);
+    w.gT = take(Mp * d_s * 2);
+    w.w_outT = take(n_cat * d_s * 2);
+    w.w_inT = take(n_in * d_s * 2);
+    w.sT = take(Mp * d_s * 2);
+    w.dcat = take(M * n_cat * 4);
+    w.d_o = take(M * d.H * d.c * 4);
+    w.d_o_pts = take(M * d.H * d.Pv * 3 * 4);
+    w.d_o_pair = take(M * d.H * d.cz * 4);
+    w.dq = take(M * d.H * d.c * 2);
+    w.dk = take(M * d.H * d.c * 2);
+    w.dv = take(M * d.H * d.c * 2);
+    w.dq_pts = take(M * d.H * d.Pq * 3 * 2);
+    w.dk_pts = take(M * d.H * d.Pq * 3 * 2);
+    w.dv_pts = take(M * d.H * d.Pv * 3 * 2);
+    w.dX = take(M * n_in * 2);
+    w.dXT = take(Mp * n_in * 2);
+    w.cat = take(M * n_cat * 2);
+    w.catT = take(Mp * n_cat * 2);
+    const size_t nsplit = ((M + kGK - 1) / kGK + kWgradChunks - 1) / kWgradChunks;
+    w.part = take(nsplit * (n_cat > n_in ? n_cat : n_in) * d_s * 4);
+    w.total = off;
+    return w;
+}
+
 }  // namespace
+
+bool module_backward_shape_supported(const fipa_desc &d, int d_s)
+{
+    const int n_in = d.H * (3 * d.c + 3 * (2 * d.Pq + d.Pv));
+    return module_shape_supported(d, d_s) && n_in % 8 == 0 && (long long)d.r * d.cz <= 256;
+}
 
 bool module_shape_supported(const fipa_desc &d, int d_s)
 {
@@ -318,6 +505,108 @@ hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void
     g2.K = g2.k_pair + g2.k_o + g2.k_pts + d.H * d.Pv;
     g2.C = a.s_out;
     return launch_gemm<GemmTile<2, 2, 1, 1>, true, false>(g2, stream);
+}
+
+size_t module_backward_workspace(const fipa_desc &d, int d_s) { return module_bwd_layout(d, d_s).total; }
+
+hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, const ModuleBwdArgs &g, void *ws,
+                           hipStream_t stream)
+{
+    const ModuleBwdLayout w = module_bwd_layout(d, d_s);
+    char *base = static_cast<char *>(ws);
+    const int M = d.B * d.L, Mp = (int)align_up((size_t)M, kGK);
+    const int widths[6] = {d.H * d.c, d.H * d.c, d.H * d.c, d.H * d.Pq * 3, d.H * d.Pq * 3, d.H * d.Pv * 3};
+    const int n_cat = d.H * (d.cz + d.c + 4 * d.Pv);
+    hipError_t e;
+#define FIPA_TRY(call)        \
+    do {                      \
+        e = (call);           \
+        if (e != hipSuccess)  \
+            return e;         \
+    } while (0)
+
+    // ---- forward again: Eq. 1 and the core (its outputs feed the norm's derivative and d W_out) ----
+    GemmParams g1 = {};
+    g1.M = M; g1.K = d_s;
+    g1.W = (const bf16_t *)a.w_in; g1.bias = a.b_in; g1.A = (const bf16_t *)a.s;
+    const size_t in_offs[6] = {w.f.q, w.f.k, w.f.v, w.f.q_pts, w.f.k_pts, w.f.v_pts};
+    g1.seg_start[0] = 0;
+    for (int s = 0; s < 6; ++s) {
+        g1.seg_ptr[s] = (bf16_t *)(base + in_offs[s]);
+        g1.seg_start[s + 1] = g1.seg_start[s] + widths[s];
+    }
+    g1.N = g1.seg_start[6];
+    const int n_in = g1.N;
+    FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, true>(g1, stream)));
+    FwdArgs f{base + w.f.q, base + w.f.k, base + w.f.v, base + w.f.q_pts, base + w.f.k_pts, base + w.f.v_pts,
+              a.rot, a.trans, a.z1, a.z2, a.w_b, a.gamma, a.mask,
+              (float *)(base + w.f.o), (float *)(base + w.f.o_pts), (float *)(base + w.f.o_pair), nullptr};
+    FIPA_TRY(bf16_forward(d, f, base + w.f.core, stream));
+
+    // ---- through Eq. 5: d cat = d s_out W_out; d W_out = d s_out^T cat; d b_out = column sums ----------
+    bf16_t *g16 = (bf16_t *)(base + w.g16), *gT = (bf16_t *)(base + w.gT);
+    hipLaunchKernelGGL(fipa_to_bf16_kernel, dim3((unsigned)(((size_t)M * d_s + 255) / 256)), dim3(256), 0, stream,
+                       g.d_s_out, g16, (size_t)M * d_s);
+    FIPA_TRY(launch_transpose<float>(g.d_s_out, gT, M, d_s, Mp, stream));                                // [d_s, Mp]
+    FIPA_TRY(launch_transpose<bf16_t>((const bf16_t *)a.w_out, (bf16_t *)(base + w.w_outT), d_s, n_cat, d_s, stream));  // [N_cat, d_s]
+    GemmParams gc = {};
+    gc.M = M; gc.N = n_cat; gc.K = d_s;
+    gc.A = g16; gc.W = (const bf16_t *)(base + w.w_outT); gc.C = (float *)(base + w.dcat);
+    FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, false>(gc, stream)));
+    GemmParams cp = {};  // description of the concatenation (as for the forward's output projection)
+    cp.M = M; cp.o_pair = f.o_pair; cp.o = f.o; cp.o_pts = f.o_pts;
+    cp.k_pair = d.H * d.cz; cp.k_o = d.H * d.c; cp.k_pts = d.H * d.Pv * 3; cp.K = n_cat;
+    hipLaunchKernelGGL(fipa_split_dcat_kernel, dim3(M), dim3(256), 0, stream, gc.C, f.o_pts, (float *)(base + w.d_o_pair),
+                       (float *)(base + w.d_o), (float *)(base + w.d_o_pts), cp.k_pair, cp.k_o, cp.k_pts);
+    hipLaunchKernelGGL(fipa_concat_bf16_kernel, dim3(M), dim3(256), 0, stream, cp, (bf16_t *)(base + w.cat));
+    FIPA_TRY(launch_transpose<bf16_t>((const bf16_t *)(base + w.cat), (bf16_t *)(base + w.catT), M, n_cat, Mp, stream));  // [N_cat, Mp]
+    const int nkc = Mp / kGK, nsplit = (nkc + kWgradChunks - 1) / kWgradChunks;
+    GemmParams gw = {};
+    gw.M = d_s; gw.N = n_cat; gw.K = Mp;
+    gw.A = gT; gw.W = (const bf16_t *)(base + w.catT); gw.C = (float *)(base + w.part); gw.chunks_per_split = kWgradChunks;
+    FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, false>(gw, stream)));
+    hipLaunchKernelGGL(fipa_sum_partials_kernel, dim3((unsigned)(((size_t)d_s * n_cat + 255) / 256)), dim3(256), 0, stream,
+                       gw.C, g.d_w_out, (size_t)d_s * n_cat, nsplit);
+    if (g.d_b_out) hipLaunchKernelGGL(fipa_rowsum_bf16_kernel, dim3(d_s), dim3(256), 0, stream, gT, g.d_b_out, Mp);
+    FIPA_TRY(hipGetLastError());
+
+    // ---- the core's backward -----------------------------------------------------------------------
+    BwdArgs b;
+    b.f = f;
+    b.d_o = (const float *)(base + w.d_o); b.d_o_pts = (const float *)(base + w.d_o_pts);
+    b.d_o_pair = (const float *)(base + w.d_o_pair);
+    b.d_q = base + w.dq; b.d_k = base + w.dk; b.d_v = base + w.dv;
+    b.d_q_pts = base + w.dq_pts; b.d_k_pts = base + w.dk_pts; b.d_v_pts = base + w.dv_pts;
+    b.d_z1 = g.d_z1; b.d_z2 = g.d_z2; b.d_gamma = g.d_gamma; b.d_w_b = g.d_w_b; b.d_rot = g.d_rot; b.d_trans = g.d_trans;
+    FIPA_TRY(bf16_backward(d, b, base + w.f.core, stream));
+
+    // ---- through Eq. 1: d s = dX W_in; d W_in = dX^T s; d b_in = column sums of dX ---------------------
+    GemmParams gx = {};
+    gx.M = M; gx.N = n_in;
+    const size_t gr_offs[6] = {w.dq, w.dk, w.dv, w.dq_pts, w.dk_pts, w.dv_pts};
+    gx.seg_start[0] = 0;
+    for (int s = 0; s < 6; ++s) {
+        gx.seg_ptr[s] = (bf16_t *)(base + gr_offs[s]);
+        gx.seg_start[s + 1] = gx.seg_start[s] + widths[s];
+    }
+    bf16_t *dX = (bf16_t *)(base + w.dX), *dXT = (bf16_t *)(base + w.dXT);
+    hipLaunchKernelGGL(fipa_gather6_kernel, dim3(M), dim3(256), 0, stream, gx, dX);
+    FIPA_TRY(launch_transpose<bf16_t>(dX, dXT, M, n_in, Mp, stream));                                                  // [N_in, Mp]
+    FIPA_TRY(launch_transpose<bf16_t>((const bf16_t *)a.w_in, (bf16_t *)(base + w.w_inT), n_in, d_s, n_in, stream));  // [d_s, N_in]
+    FIPA_TRY(launch_transpose<bf16_t>((const bf16_t *)a.s, (bf16_t *)(base + w.sT), M, d_s, Mp, stream));              // [d_s, Mp]
+    GemmParams gs = {};
+    gs.M = M; gs.N = d_s; gs.K = n_in;
+    gs.A = dX; gs.W = (const bf16_t *)(base + w.w_inT); gs.C = g.d_s_in;
+    FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, false>(gs, stream)));
+    GemmParams gi = {};
+    gi.M = n_in; gi.N = d_s; gi.K = Mp;
+    gi.A = dXT; gi.W = (const bf16_t *)(base + w.sT); gi.C = (float *)(base + w.part); gi.chunks_per_split = kWgradChunks;
+    FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, false>(gi, stream)));
+    hipLaunchKernelGGL(fipa_sum_partials_kernel, dim3((unsigned)(((size_t)n_in * d_s + 255) / 256)), dim3(256), 0, stream,
+                       gi.C, g.d_w_in, (size_t)n_in * d_s, nsplit);
+    if (g.d_b_in) hipLaunchKernelGGL(fipa_rowsum_bf16_kernel, dim3(n_in), dim3(256), 0, stream, dXT, g.d_b_in, Mp);
+#undef FIPA_TRY
+    return hipGetLastError();
 }
 
 }  // namespace fipa

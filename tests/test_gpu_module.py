@@ -58,3 +58,43 @@ def test_module_rejects_unsupported_width():
     m = wl.make_module_inputs(1, d_s=40, B=1, L=64, H=4)
     with pytest.raises(binding.FipaError):
         binding.upload_module(m)
+
+
+MODULE_GRADS = (("d_s", "ds"), ("d_w_in", "dw_in"), ("d_b_in", "db_in"), ("d_w_out", "dw_out"), ("d_b_out", "db_out"),
+                ("d_z1", "dz1"), ("d_z2", "dz2"), ("d_gamma", "dgamma"), ("d_w_b", "dw_b"), ("d_rot", "drot"),
+                ("d_trans", "dtrans"))
+
+
+def check_module_backward(m, label, seed=0, tol=2e-2):
+    import torch
+    rng = np.random.default_rng(seed)
+    d = m["dims"]
+    up = rng.standard_normal((d["B"], d["L"], m["d_s"])).astype(np.float32)
+    desc, dev = binding.upload_module(m)
+    grads = binding.alloc_module_grads(desc, m["d_s"])
+    for n, _ in MODULE_GRADS:
+        grads[n].fill_(float("nan"))
+    binding.module_backward(desc, m["d_s"], dev, torch.from_numpy(up).to("cuda:0"), grads)
+    torch.cuda.synchronize()
+    want = module_ref.module_backward(m, up)
+    errs = {}
+    for n, o in MODULE_GRADS:
+        got = grads[n].float().cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got)), (label, n)
+        errs[n] = gu.rel_err(got, want[o])
+    print(label, {k: "%.1e" % v for k, v in errs.items()}, flush=True)
+    for n, _ in MODULE_GRADS:
+        assert errs[n] <= tol, (label, n, errs[n])
+
+
+def test_module_backward_small_shapes():
+    # B*L = 130 is neither a multiple of the row tile nor of the K chunk of the weight gradients
+    check_module_backward(wl.make_module_inputs(4, d_s=48, B=1, L=130, H=4, trans_scale=0.3), "module bwd L=130 d_s=48")
+    check_module_backward(wl.make_module_inputs(4, d_s=64, B=2, L=96, H=2, cz=32, r=2), "module bwd B=2 L=96 cz=32")
+
+
+def test_module_backward_masked_and_without_biases():
+    m = wl.make_module_inputs(4, d_s=64, B=2, L=160, H=4, varlen=True, min_len=30, trans_scale=0.5)
+    check_module_backward(m, "module bwd varlen")
+    m["b_in"], m["b_out"] = None, None
+    check_module_backward(m, "module bwd varlen, no biases")
