@@ -604,13 +604,14 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             for (int ks = 0; ks < C::KSZ; ++ks) {
                 const f32x4 w0 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks);
                 const f32x4 w1 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks + 4);
-                const bf16_t *e = reinterpret_cast<const bf16_t *>(&zraw[ks]);
+                const unsigned zw[4] = {zraw[ks].x, zraw[ks].y, zraw[ks].z, zraw[ks].w};  // two bf16 values each
                 unsigned pk[4];
 #pragma unroll
-                for (int x = 0; x < 8; x += 2) {
-                    const unsigned lo = f2bf((x < 4 ? w0[x & 3] : w1[x & 3]) * bf2f(e[x]));
-                    const unsigned hi = f2bf((x < 4 ? w0[(x & 3) + 1] : w1[(x & 3) + 1]) * bf2f(e[x + 1]));
-                    pk[x >> 1] = (lo | (hi << 16)) & keep;
+                for (int x = 0; x < 4; ++x) {
+                    const float wl = x < 2 ? w0[2 * x] : w1[2 * x - 4], wh = x < 2 ? w0[2 * x + 1] : w1[2 * x - 3];
+                    const float lo = wl * __uint_as_float(zw[x] << 16), hi = wh * __uint_as_float(zw[x] & 0xFFFF0000u);
+                    // (round to nearest even, as the pack kernel's conversion; one v_cvt_pk_bf16_f32)
+                    pk[x] = __builtin_bit_cast(unsigned, __builtin_convertvector((f32x2){lo, hi}, bf16x2)) & keep;
                 }
                 w.qf[C::KSH + ks] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
             }
