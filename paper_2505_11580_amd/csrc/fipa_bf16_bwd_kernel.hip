@@ -183,6 +183,19 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     const int nblk = (kvlen + kSB - 1) / kSB;       // streamed blocks: residues past the last valid one contribute nothing
     const int srow = tile * kTileQ + wave * 32 + li;  // stationary row of this lane, < Lp
 
+    // Stationary rows past the last valid residue of the chain (padding of a ragged batch) take
+    // part in nothing: zero gradient.
+    if (tile * kTileQ >= kvlen) {
+        float *orow = p.out + ((size_t)bh * p.Lp + srow) * C::D;
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<f32x4 *>(orow + 32 * nb + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (p.wsum && g == 0) p.wsum[(size_t)bh * p.Lp + srow] = 0.f;
+        return;
+    }
+
     // streamed tiles (row 0 of block 0, row pitch in bytes) and stationary sources, by mode
     const bf16_t *Qh = p.Qh + (size_t)bh * p.Lp * kDH, *Qz = p.Qz + (size_t)bh * p.Lp * DZ;
     const bf16_t *Kh = p.Kh + (size_t)bh * p.Lp * kDH, *Vh = p.Vh + (size_t)bh * p.Lp * kDH;
