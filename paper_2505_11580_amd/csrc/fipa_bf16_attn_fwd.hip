@@ -398,12 +398,20 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // units so that the query tiles of one (batch, head) share that XCD's L2 copy of k^ and v^.
     // The first plan.full workgroups take whole tiles; the others take one of the plan.S key-range
     // parts of a remaining tile (the parts of a tile are neighbours in the launch order).
+    // In a mixed launch (see SplitPlan) the last 512 workgroups alternate, per XCD, between runs of
+    // 16 whole tiles and 16 parts.
     int logical, part = 0, tile_local = 0, nparts = 1;
-    if ((int)blockIdx.x < p.plan.full) {
-        logical = (blockIdx.x % 8) * (p.plan.full / 8) + blockIdx.x / 8;
+    int wg = blockIdx.x;        // position in the plain order: whole tiles, then parts
+    if (p.plan.mixed && wg >= p.plan.full - 256) {
+        const int i = wg - (p.plan.full - 256), x = i % 8, j = i / 8;  // XCD, slot 0..63
+        const int run = j / 16, k = j % 16 + 16 * (run / 2);            // k-th whole tile / part of this XCD's 32
+        wg = (run % 2 == 0 ? p.plan.full - 256 : p.plan.full) + 8 * k + x;
+    }
+    if (wg < p.plan.full) {
+        logical = (wg % 8) * (p.plan.full / 8) + wg / 8;
     } else {
         nparts = p.plan.S;
-        const int u = blockIdx.x - p.plan.full, n_units = p.plan.rem * nparts;
+        const int u = wg - p.plan.full, n_units = p.plan.rem * nparts;
         if (u >= n_units) return;
         const int lin = n_units % 8 == 0 ? (u % 8) * (n_units / 8) + u / 8 : u;
         tile_local = lin / nparts;
@@ -660,6 +668,31 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     }
     wait_vmem<0>();  // requests past the end of the sequence went to free stages; let them finish
 
+    // ---- fused epilogue, first step: this wave's 32 z1 rows go to LDS while the last blocks are
+    // being multiplied.  After the barrier every wave has left the loop and every block load has
+    // landed, so the three stages that do not hold the last two blocks are free; each wave takes
+    // 32 * 2 DZ bytes of them.  Row-major with the 16-byte chunks of row r stored at position
+    // chunk ^ (r mod chunks-per-row): the loads are whole rows (coalesced) and the reads below,
+    // one chunk index across 32 rows, spread over the banks.
+    [[maybe_unused]] int z1_off = 0;
+    if constexpr (FUSED) {
+        static_assert(C::NSTAGE == 5 && 32 * DZ * 2 <= C::STAGE, "z1 staging needs three free stages");
+        constexpr int kRowBytes = DZ * 2, kWaveBytes = 32 * kRowBytes, kCpr = DZ / 8;  // 16-byte chunks per row
+        wg_barrier();
+        const int f0 = s0 + 2 < C::NSTAGE ? s0 + 2 : s0 + 2 - C::NSTAGE;  // first free stage (cyclically)
+        const int room = min(C::NSTAGE - f0, 3) * C::STAGE;                // free bytes before the ring wraps
+        const int n_head = min(4, room / kWaveBytes);                     // waves that fit there; the rest start at 0
+        z1_off = wave < n_head ? f0 * C::STAGE + wave * kWaveBytes : (wave - n_head) * kWaveBytes;
+        const char *zbase = reinterpret_cast<const char *>(p.z1 + (size_t)b * p.L * DZ);
+        const int row0 = qt * kTileQ + wave * 32;
+#pragma unroll
+        for (int k = 0; k < kWaveBytes / 1024; ++k) {
+            const int slot = 64 * k + lane, r = slot / kCpr, c = (slot % kCpr) ^ (r % kCpr);
+            int voff = min(row0 + r, p.L - 1) * kRowBytes + 16 * c;
+            dma16<0>(zbase, voff, 0, smem_lds + z1_off + 1024 * k);
+        }
+    }
+
     // ---- drain: the last two blocks -----------------------------------------------------------------
     if (nblk > 1) {
         // P V of the last block but one, exponentials of the last block
@@ -720,13 +753,16 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         }
         // pair part: o~[d'] = sum_rho z1[rho, d'] * U[rho, d']; the lane holds columns 8a + 4g + x
         {
-            const bf16_t *z1 = p.z1 + ((size_t)b * p.L + irow_c) * DZ;
+            wait_vmem<0>();  // the z1 rows staged before the drain (this wave's own loads, no barrier needed)
+            asm volatile("" ::: "memory");
+            constexpr int kCpr = DZ / 8;
+            const char *z1l = smem + z1_off + li * (DZ * 2) + 8 * g;
 #pragma unroll
             for (int zb = 0; zb < NZB; ++zb)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
-                    const int dz = 32 * zb + 8 * a + 4 * g;  // column in [0, DZ)
-                    const uint2 zraw = *reinterpret_cast<const uint2 *>(z1 + dz);
+                    // columns 32 zb + 8 a + 4 g .. + 3 of row li: half g of chunk 4 zb + a
+                    const uint2 zraw = *reinterpret_cast<const uint2 *>(z1l + 16 * ((4 * zb + a) ^ (li % kCpr)));
                     const bf16_t *zb16 = reinterpret_cast<const bf16_t *>(&zraw);
 #pragma unroll
                     for (int x = 0; x < 4; ++x) oacc[C::NBH + zb][4 * a + x] *= bf2f(zb16[x]);

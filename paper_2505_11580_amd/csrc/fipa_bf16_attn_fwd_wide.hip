@@ -60,19 +60,40 @@ __device__ __forceinline__ void wide_issue_block(WideDma<C> &d, unsigned stage)
     }
 }
 
+// Entry k of the loads of the next block (k is a compile-time constant after unrolling).
+template <class C, int K = 0>
+__device__ __forceinline__ void wide_issue_entry(WideDma<C> &d, unsigned stage, int k)
+{
+    if constexpr (K <= C::NIW) {
+        if (k == K) {
+            if constexpr (K < C::NIW)
+                dma16<4096 * K>(d.src[K], d.voff[K], d.step[K], stage + d.wave_lds);
+            else
+                dma16<C::KB_OFF>(d.src[K], d.voff[K], d.step[K], stage);
+        } else {
+            wide_issue_entry<C, K + 1>(d, stage, k);
+        }
+    }
+}
+
 struct WideLane {
     int kaddr_h, kaddr_z, vaddr_h, vaddr_z, g, win;
 };
 
 // One step of the pipeline: S^T and the softmax of the block in stage `st` (CUR), interleaved
 // with P V of the previous block (stage `st_prev`, probabilities `pf` on entry) (PREV).  On exit
-// `pf` holds the probabilities of the current block.
+// `pf` holds the probabilities of the current block.  When `load_next` is set the loads of the
+// next block are issued between the MFMAs, one entry every few of them (issued back to back they
+// cost about 60 cycles each).
 template <int DZ, int NWIN, bool CUR, bool PREV>
 __device__ __forceinline__ void wide_step(const char *__restrict__ st, const char *__restrict__ st_prev, const WideLane &ln,
                                           const bf16x8 (&qf)[WideCfg<DZ, NWIN>::KS], f32x16 (&acc)[WideCfg<DZ, NWIN>::NBW],
-                                          bf16x8 (&pf)[2], float &m_run, float &l_run)
+                                          bf16x8 (&pf)[2], float &m_run, float &l_run,
+                                          WideDma<WideCfg<DZ, NWIN>> &dma, unsigned next_stage, bool load_next)
 {
     using C = WideCfg<DZ, NWIN>;
+    constexpr int kDmaEvery = C::KS / (C::NIW + 1);
+    static_assert(kDmaEvery >= 1, "more load entries than S^T MFMAs");
     f32x16 sacc;
     if constexpr (CUR) {
 #pragma unroll
@@ -88,6 +109,7 @@ __device__ __forceinline__ void wide_step(const char *__restrict__ st, const cha
             const char *src = ks < C::KSH ? st + C::KH_OFF + ln.kaddr_h + ks * 32 : st + C::Z_OFF + ln.kaddr_z + (ks - C::KSH) * 32;
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(src);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
+            if (load_next && ks % kDmaEvery == 0) wide_issue_entry<C>(dma, next_stage, ks / kDmaEvery);
         }
         if constexpr (PREV) {
             if ((ks & 1) == 0) {
@@ -239,22 +261,24 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
         wait_vmem<0>();
         wg_barrier();
         sidx = sidx + 1 < C::NSTAGE ? sidx + 1 : 0;
-        if (n + 1 < nblk) {
+        const bool load_next = n + 1 < nblk;
+        unsigned next_stage = 0;
+        if (load_next) {
             if (next_blk == nblk) {  // continue at block 0
 #pragma unroll
                 for (int k = 0; k <= C::NIW; ++k) dma.src[k] -= (size_t)nblk * dma.step[k];
                 next_blk = 0;
             }
-            wide_issue_block<C>(dma, smem_lds + sidx * C::STAGE);
+            next_stage = smem_lds + sidx * C::STAGE;
             ++next_blk;
         }
         if (n == 0)
-            wide_step<DZ, NWIN, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run);
+            wide_step<DZ, NWIN, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
         else
-            wide_step<DZ, NWIN, true, true>(st, st_prev, ln, qf, acc, pf, m_run, l_run);
+            wide_step<DZ, NWIN, true, true>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
         st_prev = st;
     }
-    if (nblk > 0) wide_step<DZ, NWIN, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run);
+    if (nblk > 0) wide_step<DZ, NWIN, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run, dma, 0u, false);
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;

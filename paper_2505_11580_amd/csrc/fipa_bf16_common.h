@@ -61,6 +61,12 @@ struct SplitPlan {
     int full;  // leading tiles that run whole (a multiple of 256)
     int rem;   // remaining tiles
     int S;     // parts per remaining tile (1 = not split)
+    // When the parts fill exactly one round (rem * S = 256) the last 256 whole tiles and the parts
+    // are launched interleaved: half of the compute units take a part first and a whole tile
+    // second, the other half the other way round.  Work per unit stays the same, but the
+    // start-up loads and the output stores of the two halves no longer fall on the same instant
+    // (those phases are bandwidth-bound when all 256 workgroups reach them together).
+    int mixed;
     int units() const { return full + rem * S; }
 };
 
@@ -78,6 +84,7 @@ inline SplitPlan attn_split_plan(int total_tiles, int Lp, int DZ, int cz, bool f
         if (s.S > by_blocks) s.S = by_blocks;
         if (s.S < 1) s.S = 1;
     }
+    s.mixed = s.S > 1 && s.rem * s.S == kCU && s.full >= kCU;
     return s;
 }
 
