@@ -349,6 +349,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.f.DZ;
     pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
     pk.skip_qz = false;
+    pk.cen_out = nullptr; pk.kvlen_out = nullptr; pk.counters = nullptr; pk.n_counters = 0;
     e = launch_pack_bf16(pk, stream);
     if (e != hipSuccess) return e;
 

@@ -146,6 +146,13 @@ struct PackParams {
     int B, L, Lp, NT, H, c, Pq, Pv, cz, r, DZ;
     float w_L, w_C, qk_scale;
     bool skip_qz;  // the attention kernel forms the query-side factor vectors itself
+    // When cen_out is set, the AlphaFold2-shape pack kernel finds the per-batch reference point
+    // and key-loop bound itself (no separate preparation launch), uses them, and leaves them
+    // here for the attention kernel; it also clears `counters`.  `cen` is ignored then.
+    float *cen_out;
+    int *kvlen_out;
+    int *counters;
+    int n_counters;
 };
 
 struct AttnParams {

@@ -17,8 +17,13 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     timer.begin(0);
     int *counters = reinterpret_cast<int *>(base + w.counters);
     const int n_counters = w.plan.S > 1 ? w.plan.rem * 4 : 0;
-    hipError_t e = launch_prep(d, a.trans, a.mask, cen, kvlen, counters, n_counters, stream);
-    if (e != hipSuccess) return e;
+    // With the AlphaFold2 head shape the pack kernel does the per-batch preparation itself.
+    const bool prep_in_pack = d.c == 16 && d.Pq == 4 && d.Pv == 8;
+    hipError_t e = hipSuccess;
+    if (!prep_in_pack) {
+        e = launch_prep(d, a.trans, a.mask, cen, kvlen, counters, n_counters, stream);
+        if (e != hipSuccess) return e;
+    }
 
     PackParams pk;
     pk.q = (const bf16_t *)a.q; pk.k = (const bf16_t *)a.k; pk.v = (const bf16_t *)a.v;
@@ -35,6 +40,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.DZ;
     pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
     pk.skip_qz = fused && w.DZ <= 256;
+    pk.cen_out = prep_in_pack ? cen : nullptr; pk.kvlen_out = kvlen; pk.counters = counters; pk.n_counters = n_counters;
     e = launch_pack_bf16(pk, stream);
     if (e != hipSuccess) return e;
     timer.end(0);

@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) void fipa_pack_qz_bf16_kernel(PackParams p)
 // one thread per (batch, residue, head) and per role (blockIdx.y: 0 = q^, 1 = k^, 2 = v^),
 // rows assembled in registers.  Consecutive threads read consecutive (residue, head) records.
 template <int ROLE>
-__device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i, int h)
+__device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i, int h, const float (&cen)[3])
 {
     constexpr int c = 16, Pq = 4, Pv = 8;
     const size_t bh = (size_t)b * p.H + h;
@@ -171,7 +171,7 @@ __device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i,
 #pragma unroll
         for (int a = 0; a < 9; ++a) Rm[a] = R[a];
 #pragma unroll
-        for (int a = 0; a < 3; ++a) tc[a] = t[a] - p.cen[4 * b + a];
+        for (int a = 0; a < 3; ++a) tc[a] = t[a] - cen[a];
         const size_t rec = ((size_t)b * p.L + i) * p.H + h;
         const float pscale = p.gamma[h] * p.w_L * p.w_C;  // weight of Q.K in the expanded distance
         const bf16_t *sc_src = ROLE == 0 ? p.q : (ROLE == 1 ? p.k : p.v);
@@ -232,6 +232,41 @@ __device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i,
     if (ROLE == 1) p.kbias[bh * p.Lp + i] = bias;
 }
 
+// Reference point and key-loop bound of batch element b, computed by one wave (every wave that
+// asks gets the same answer).  kvlen = 1 + index of the last valid residue.  The reference point
+// only has to lie inside the structure (the result does not depend on it, Section 2; it keeps
+// the coordinates that are split into bf16 pairs small): the mean translation of 64 valid
+// residues spread evenly over [0, kvlen) stands in for the centroid of all of them.
+__device__ __forceinline__ void batch_reference(const PackParams &p, int b, float (&cen)[3], int &kvlen)
+{
+    const int lane = threadIdx.x & 63;
+    int last = p.L;
+    if (p.mask) {
+        const uint8_t *m = p.mask + (size_t)b * p.L;
+        last = 0;
+        for (int i = lane; i < p.L; i += 64)
+            if (m[i] != 0) last = i + 1;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o));
+    }
+    kvlen = last;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (kvlen > 0) {
+        const int i = (int)(((long long)lane * kvlen) >> 6);
+        if (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true) {
+            const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+            v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = 1.f;
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v[a] += __shfl_xor(v[a], o);
+    const float n = v[3] > 0.f ? v[3] : 1.f;
+#pragma unroll
+    for (int a = 0; a < 3; ++a) cen[a] = v[a] / n;
+}
+
 // The launch covers the three roles (nbh workgroups each) and, after them, the z2 copy.
 __global__ __launch_bounds__(256) void fipa_pack_heads_af2_bf16_kernel(PackParams p, unsigned nbh)
 {
@@ -240,17 +275,47 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_af2_bf16_kernel(PackParam
         pack_z2_chunk(p, (size_t)(blockIdx.x - 3 * nbh) * 256 + threadIdx.x);
         return;
     }
-    const size_t idx = (size_t)(blockIdx.x - role * nbh) * 256 + threadIdx.x;  // (b, i, h), h fastest
-    if (idx >= (size_t)p.B * p.Lp * p.H) return;
+    const size_t per_batch = (size_t)p.Lp * p.H, total = (size_t)p.B * per_batch;
+    const size_t idx0 = (size_t)(blockIdx.x - role * nbh) * 256;
+    const size_t idx = idx0 + threadIdx.x;  // (b, i, h), h fastest
+    float cen[3] = {0.f, 0.f, 0.f};
+    if (p.cen_out) {
+        if (role == 0)
+            for (int i = (int)idx; i < p.n_counters; i += (int)nbh * 256) p.counters[i] = 0;
+        // (wave-uniform control flow: the shuffles inside need all 64 lanes)
+        const size_t w0 = idx0 + (threadIdx.x & ~63u);
+        if (w0 >= total) return;
+        const int b0 = (int)(w0 / per_batch), b1 = (int)(min(w0 + 63, total - 1) / per_batch);
+        const int bmine = (int)(min(idx, total - 1) / per_batch);
+        for (int bb = b0; bb <= b1; ++bb) {
+            float cb[3];
+            int kv;
+            batch_reference(p, bb, cb, kv);
+            if (bb == bmine)
+#pragma unroll
+                for (int a = 0; a < 3; ++a) cen[a] = cb[a];
+            if (role == 0 && idx == (size_t)bb * per_batch) {  // the thread that packs (bb, 0, 0) publishes
+                p.cen_out[4 * bb + 0] = cb[0];
+                p.cen_out[4 * bb + 1] = cb[1];
+                p.cen_out[4 * bb + 2] = cb[2];
+                p.cen_out[4 * bb + 3] = 0.f;
+                p.kvlen_out[bb] = kv;
+            }
+        }
+    }
+    if (idx >= total) return;
     const int h = (int)(idx % p.H);
     const size_t bi = idx / p.H;
     const int i = (int)(bi % p.Lp), b = (int)(bi / p.Lp);
+    if (!p.cen_out)
+#pragma unroll
+        for (int a = 0; a < 3; ++a) cen[a] = p.cen[4 * b + a];
     if (role == 0)
-        pack_head_row<0>(p, b, i, h);
+        pack_head_row<0>(p, b, i, h, cen);
     else if (role == 1)
-        pack_head_row<1>(p, b, i, h);
+        pack_head_row<1>(p, b, i, h, cen);
     else
-        pack_head_row<2>(p, b, i, h);
+        pack_head_row<2>(p, b, i, h, cen);
 }
 
 }  // namespace
