@@ -637,7 +637,17 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+a"(w.qf[ks]));
         sacc = s_block<DZ>(w, smem);
-        const float mx = row_max16(sacc);
+        float mx = row_max16(sacc);
+        // The sequence of a whole tile (or of its first part) starts with the four blocks that
+        // hold the tile's own residues, wave v's in block v.  With distance-dominated logits a
+        // row's largest logits sit there, far above those of the neighbouring blocks, so waves
+        // 1-3 would raise the reference (and every wave would wait for them) when they get to
+        // their own block.  They look at it now instead and start from its maximum.
+        if (pos0 == 0 && !downwards && nblk >= 4) {
+            wait_vmem<0>();  // blocks 2 and 3
+            wg_barrier();
+            if (wave > 0) mx = fmaxf(mx, row_max16(s_block<DZ>(w, smem + wave * C::STAGE)));
+        }
         w.m_ref = mx;
         float psum = 0.f;
         exp_block(sacc, mx == -INFINITY ? 0.f : mx, pf, psum);
