@@ -154,12 +154,17 @@ __global__ __launch_bounds__(256) void fipa_pack_qz_bf16_kernel(PackParams p)
 // Head-specific columns for the AlphaFold2-style head shape (c = 16, N_query = 4, N_value = 8):
 // one thread per (batch, residue, head) and per role (blockIdx.y: 0 = q^, 1 = k^, 2 = v^),
 // rows assembled in registers.  Consecutive threads read consecutive (residue, head) records.
+// The finished row is not stored by its thread (a wave would then write 16 bytes into each of 64
+// different rows per instruction): the wave's 64 rows go through `stage` (this wave's 64 x 128
+// bytes of LDS, chunk c of row r at position (c + r) mod 8) and leave as whole 128-byte rows,
+// eight per instruction.  `active` is false for the threads past the end of the launch.
 template <int ROLE>
-__device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i, int h, const float (&cen)[3])
+__device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i, int h, const float (&cen)[3],
+                                              bool active, char *stage, unsigned long long *dst_of_row)
 {
     constexpr int c = 16, Pq = 4, Pv = 8;
     const size_t bh = (size_t)b * p.H + h;
-    const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    const bool ok = active && i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
     __attribute__((aligned(16))) bf16_t row[kDH];
 #pragma unroll
     for (int x = 0; x < kDH; ++x) row[x] = 0;
@@ -224,12 +229,27 @@ __device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i,
         if (ROLE == 0) bias = 0.5f * pscale * sq;
         if (ROLE == 1) bias = kscale != 0.f ? -sq / (2.f * kscale) : 0.f;
     }
+    static_assert(kDH == 64, "eight 16-byte chunks per row");
+    const int lane = threadIdx.x & 63;
     bf16_t *dst = (ROLE == 0 ? p.Qh : (ROLE == 1 ? p.Kh : p.Vh)) + (bh * p.Lp + i) * kDH;
 #pragma unroll
-    for (int x = 0; x < kDH / 8; ++x)
-        reinterpret_cast<uint4 *>(dst)[x] = reinterpret_cast<const uint4 *>(row)[x];
-    if (ROLE == 0) p.qbias[bh * p.Lp + i] = bias;
-    if (ROLE == 1) p.kbias[bh * p.Lp + i] = bias;
+    for (int x = 0; x < 8; ++x)
+        *reinterpret_cast<uint4 *>(stage + lane * 128 + 16 * ((x + lane) & 7)) = reinterpret_cast<const uint4 *>(row)[x];
+    dst_of_row[lane] = active ? (unsigned long long)(uintptr_t)dst : 0ull;
+    if (active) {
+        if (ROLE == 0) p.qbias[bh * p.Lp + i] = bias;
+        if (ROLE == 1) p.kbias[bh * p.Lp + i] = bias;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+        const int r = 8 * pass + (lane >> 3), c = lane & 7;
+        const uint4 val = *reinterpret_cast<const uint4 *>(stage + r * 128 + 16 * ((c + r) & 7));
+        const unsigned long long d = dst_of_row[r];
+        if (d != 0ull) reinterpret_cast<uint4 *>((uintptr_t)d)[c] = val;
+    }
 }
 
 // Reference point and key-loop bound of batch element b, computed by one wave (every wave that
@@ -303,19 +323,24 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_af2_bf16_kernel(PackParam
             }
         }
     }
-    if (idx >= total) return;
-    const int h = (int)(idx % p.H);
-    const size_t bi = idx / p.H;
+    // (whole waves stay together from here on: the rows leave through LDS, wave by wave)
+    const bool active = idx < total;
+    const size_t idc = active ? idx : total - 1;
+    const int h = (int)(idc % p.H);
+    const size_t bi = idc / p.H;
     const int i = (int)(bi % p.Lp), b = (int)(bi / p.Lp);
     if (!p.cen_out)
 #pragma unroll
         for (int a = 0; a < 3; ++a) cen[a] = p.cen[4 * b + a];
+    __shared__ __attribute__((aligned(16))) char stage[4][64 * 128];
+    __shared__ unsigned long long dst_of_row[4][64];
+    const int wv = threadIdx.x >> 6;
     if (role == 0)
-        pack_head_row<0>(p, b, i, h, cen);
+        pack_head_row<0>(p, b, i, h, cen, active, stage[wv], dst_of_row[wv]);
     else if (role == 1)
-        pack_head_row<1>(p, b, i, h, cen);
+        pack_head_row<1>(p, b, i, h, cen, active, stage[wv], dst_of_row[wv]);
     else
-        pack_head_row<2>(p, b, i, h, cen);
+        pack_head_row<2>(p, b, i, h, cen, active, stage[wv], dst_of_row[wv]);
 }
 
 }  // namespace
