@@ -165,7 +165,11 @@ def main():
         binding.forward(desc, dev, out)
     torch.cuda.synchronize()
 
-    binding.fipa_profile_begin(args.steps)
+    # The stage timers record HIP events on the stream around each kernel; with every step timed
+    # they cost about 13 us per 150 us step, so only one step in eight of the timed region
+    # carries them (every step when the run is short).
+    every = 8 if args.steps >= 64 else 1
+    binding.fipa_profile_begin_every((args.steps + every - 1) // every, every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -199,7 +203,7 @@ def main():
                                   dims["Pv"], dims["cz"], dims["r"]),
                    "valid_pairs": pairs, "flops_per_pair": fpp},
         "stage_ms": {"pack": stage_ms[0], "attention": stage_ms[1], "epilogue": stage_ms[2],
-                     "timed_calls": n_timed},
+                     "timed_calls": n_timed, "timed_every": every},
         "roofline": {"kernel": "fipa_attn_fwd_bf16_kernel", "bound": "mfma", "achieved": attn_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,

@@ -190,9 +190,16 @@ int fipa_module_backward(const fipa_desc *desc, int32_t d_s,
  * writes the mean duration of each stage in milliseconds to stage_ms[FIPA_PROFILE_STAGES] and
  * the number of timed calls to *n_calls, and releases the events.  begin allocates the events
  * (host-side driver objects, no device memory).
+ * The event records themselves cost GPU time (several microseconds per call, which is visible
+ * next to a 150 us step): fipa_profile_begin_every times only every `every`-th call (the first,
+ * the (every+1)-th, ...; every >= 1), so that a throughput measurement taken over the same calls
+ * is hardly disturbed.  fipa_profile_begin(capacity) is fipa_profile_begin_every(capacity, 1).
+ * Both return FIPA_ERR_INVALID_ARG for capacity outside 1..4096, every < 1, or when timing is
+ * already active.
  */
 #define FIPA_PROFILE_STAGES 3
 int fipa_profile_begin(int capacity);
+int fipa_profile_begin_every(int capacity, int every);
 int fipa_profile_end(float *stage_ms, int *n_calls);
 
 #ifdef __cplusplus

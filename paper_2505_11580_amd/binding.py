@@ -26,7 +26,7 @@ FIPA_DTYPE_BF16 = 1
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
            "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
            "fipa_module_backward_workspace_bytes", "fipa_module_backward",
-           "fipa_profile_begin", "fipa_profile_end")
+           "fipa_profile_begin", "fipa_profile_begin_every", "fipa_profile_end")
 PROFILE_STAGES = 3
 
 
@@ -73,6 +73,8 @@ def lib():
         L.fipa_module_backward.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32] + [vp] * 24 + [vp, sz, vp]
         L.fipa_profile_begin.restype = ctypes.c_int
         L.fipa_profile_begin.argtypes = [ctypes.c_int]
+        L.fipa_profile_begin_every.restype = ctypes.c_int
+        L.fipa_profile_begin_every.argtypes = [ctypes.c_int, ctypes.c_int]
         L.fipa_profile_end.restype = ctypes.c_int
         L.fipa_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
         _LIB = L
@@ -157,6 +159,12 @@ def fipa_profile_begin(capacity):
     rc = lib().fipa_profile_begin(int(capacity))
     if rc != FIPA_OK:
         raise FipaError(rc, "fipa_profile_begin")
+
+
+def fipa_profile_begin_every(capacity, every):
+    rc = lib().fipa_profile_begin_every(int(capacity), int(every))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_profile_begin_every")
 
 
 def fipa_profile_end():

@@ -10,6 +10,8 @@ struct ProfileState {
     bool active = false;
     int capacity = 0;
     int used = 0;
+    int every = 1;   // time one call in `every`
+    long calls = 0;  // calls seen since begin
     std::vector<hipEvent_t> ev;  // [capacity][FIPA_PROFILE_STAGES][2]
     std::vector<unsigned char> recorded;  // [capacity][FIPA_PROFILE_STAGES]
 };
@@ -18,7 +20,7 @@ ProfileState g_prof;
 
 StageTimer::StageTimer(hipStream_t stream) : stream_(stream), slot_(-1)
 {
-    if (g_prof.active && g_prof.used < g_prof.capacity) slot_ = g_prof.used++;
+    if (g_prof.active && g_prof.calls++ % g_prof.every == 0 && g_prof.used < g_prof.capacity) slot_ = g_prof.used++;
 }
 
 void StageTimer::begin(int stage)
@@ -38,15 +40,19 @@ void StageTimer::end(int stage)
 
 using namespace fipa;
 
-extern "C" int fipa_profile_begin(int capacity)
+extern "C" int fipa_profile_begin(int capacity) { return fipa_profile_begin_every(capacity, 1); }
+
+extern "C" int fipa_profile_begin_every(int capacity, int every)
 {
-    if (capacity <= 0 || capacity > 4096 || g_prof.active) return FIPA_ERR_INVALID_ARG;
+    if (capacity <= 0 || capacity > 4096 || every <= 0 || g_prof.active) return FIPA_ERR_INVALID_ARG;
     g_prof.ev.assign((size_t)capacity * FIPA_PROFILE_STAGES * 2, nullptr);
     g_prof.recorded.assign((size_t)capacity * FIPA_PROFILE_STAGES, 0);
     for (auto &e : g_prof.ev)
         if (hipEventCreate(&e) != hipSuccess) return FIPA_ERR_LAUNCH;
     g_prof.capacity = capacity;
     g_prof.used = 0;
+    g_prof.every = every;
+    g_prof.calls = 0;
     g_prof.active = true;
     return FIPA_OK;
 }
