@@ -128,17 +128,21 @@ def calibrate_copy(nbytes=256 << 20):
 
 # HBM traffic of one launch of the attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script (see profiles/), scaled by what the same counters read for calibrate_copy().
-MEASURED_TRAFFIC_BYTES = {2: 140.9e6}  # workload 2: 80.8 MB fetched + 60.1 MB written
+MEASURED_TRAFFIC_BYTES = {2: 177.5e6}  # workload 2: 115.9 MB fetched + 61.6 MB written
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # (the clocks settle over the first few hundred launches after an idle period: the step time
+    # falls by about 10 % during that time, so the default warm-up is long and the timed region
+    # covers 1000 steps = 0.15 s)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", type=int, default=2, help="workload index (2 = the L=2048 headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true", help="skip the fipa_backward leg (workload 4)")
+    ap.add_argument("--no-module", action="store_true", help="skip the module leg (fipa_module_forward / backward)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB copy kernel (for scaling hardware counters)")
     args = ap.parse_args()
@@ -211,10 +215,11 @@ def main():
     }
     if args.calibrate_copy:
         calibrate_copy()
-    if not args.no_backward:
-        del out, dev
-        torch.cuda.empty_cache()
+    del out, dev
+    torch.cuda.empty_cache()
+    if not args.no_module:
         result["module"] = module_leg(args.workload)
+    if not args.no_backward:
         result["backward"] = backward_leg(4)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, fpp)

@@ -254,9 +254,17 @@ __global__ __launch_bounds__(256) void fipa_bwd_wb_reduce_kernel(BwdUnpackParams
     __shared__ float col[512];  // per lifted pair column: sum over the chunks
     const int h = blockIdx.x;
     for (int x = threadIdx.x; x < p.DZ; x += 256) {
-        float s = 0.f;
-        for (int ch = 0; ch < nchunk; ++ch) s += p.wpart[((size_t)h * nchunk + ch) * p.DZ + x];
-        col[x] = s;
+        // eight independent chains of loads (one chain would pay the load latency nchunk times);
+        // summed in a fixed order
+        float s8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int ch0 = 0; ch0 < nchunk; ch0 += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float v = p.wpart[((size_t)h * nchunk + min(ch0 + u, nchunk - 1)) * p.DZ + x];
+                s8[u] += ch0 + u < nchunk ? v : 0.f;
+            }
+        }
+        col[x] = ((s8[0] + s8[1]) + (s8[2] + s8[3])) + ((s8[4] + s8[5]) + (s8[6] + s8[7]));
     }
     __syncthreads();
     for (int d = threadIdx.x; d < p.cz; d += 256) {
