@@ -292,11 +292,15 @@ __device__ __forceinline__ void dma_slot(Dma<DZ> &d, unsigned stage, int j)
 //   S^T of block n+2 (stage st_s) -> sacc,
 //   and the operand prefetch for the first P V MFMAs of the next iteration (stage st_pv_next).
 // `fr` is the operand ring; on entry it holds the operands of operations 0 .. LA-1.
-template <int DZ>
+// Operation 0 needs nothing but registers, so it is issued first and `head` -- the wait for block
+// n+2, the workgroup barrier and the ring bookkeeping, which yields the stages st_s, st_pv_next
+// and the load target st_dma -- runs behind it instead of in front of an idle matrix pipe.
+template <int DZ, class Head>
 __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f32x16 &sacc, bf16x8 (&fr)[AttnCfg<DZ>::RING],
-                                                 const char *st_pv, const char *st_s, const char *st_pv_next,
-                                                 Dma<DZ> &dma, unsigned st_dma)
+                                                 const char *st_pv, Dma<DZ> &dma, Head &&head)
 {
+    const char *st_s = nullptr, *st_pv_next = nullptr;
+    unsigned st_dma = 0;
     using C = AttnCfg<DZ>;
     using O = Ops<DZ>;
     constexpr int N = C::NOPS;
@@ -310,6 +314,12 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
+        if (j == 0) {
+            static_assert(O::is_pv(0) && O::idx(0) == 0, "operation 0 is the first P V MFMA");
+            w.oacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[0], pf[0], w.oacc[0], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            head(st_s, st_pv_next, st_dma);
+        }
         // operand fetch, LA operations ahead (wrapping into the next iteration), in order of use:
         // LDS returns data in order, so each MFMA waits for exactly its own operand.  (Fetching
         // groups of four operations with one wait per group measured 3 % slower; depths 3 to 6
@@ -329,7 +339,9 @@ __device__ __forceinline__ void steady_iteration(Wave<DZ> &w, bf16x8 (&pf)[2], f
         // one entry of the loads of the block four ahead, every few MFMAs
         dma_slot<DZ>(dma, st_dma, j);
         // the MFMA
-        if (O::is_pv(j)) {
+        if (j == 0) {
+            // (issued above)
+        } else if (O::is_pv(j)) {
             const int i = O::idx(j);
             w.oacc[i >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], pf[i & 1], w.oacc[i >> 1], 0, 0, 0);
         } else {
@@ -658,21 +670,25 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // ---- steady state: iteration n works on blocks n (P V), n+1 (exp), n+2 (S^T) ---------------
     int s0 = 0;  // stage of block n
     for (int n = 0; n + 2 < nblk; ++n) {
-        // Block n+2 must have landed (the requests of the previous iteration may still be in
-        // flight); the barrier also tells everyone that the stage of block n-1 is free again.
-        wait_vmem<C::VM_PER_BLOCK>();
-        wg_barrier();
-        const int s1 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
-        const int s2 = s0 + 2 < C::NSTAGE ? s0 + 2 : s0 + 2 - C::NSTAGE;
-        const int s4 = s0 + 4 < C::NSTAGE ? s0 + 4 : s0 + 4 - C::NSTAGE;
-        if (next_blk == wrap_at) {
-            dma_wrap<DZ>(dma, nkb);
-            next_blk = wrap_to;
-        }
-        next_blk += dir;
-        steady_iteration<DZ>(w, pf, sacc, fr, smem + s0 * C::STAGE, smem + s2 * C::STAGE, smem + s1 * C::STAGE,
-                             dma, smem_lds + s4 * C::STAGE);
-        s0 = s1;
+        steady_iteration<DZ>(w, pf, sacc, fr, smem + s0 * C::STAGE, dma,
+                             [&](const char *&st_s, const char *&st_pv_next, unsigned &st_dma) {
+            // Block n+2 must have landed (the requests of the previous iteration may still be in
+            // flight); the barrier also tells everyone that the stage of block n-1 is free again.
+            wait_vmem<C::VM_PER_BLOCK>();
+            wg_barrier();
+            const int s1 = s0 + 1 < C::NSTAGE ? s0 + 1 : s0 + 1 - C::NSTAGE;
+            const int s2 = s0 + 2 < C::NSTAGE ? s0 + 2 : s0 + 2 - C::NSTAGE;
+            const int s4 = s0 + 4 < C::NSTAGE ? s0 + 4 : s0 + 4 - C::NSTAGE;
+            if (next_blk == wrap_at) {
+                dma_wrap<DZ>(dma, nkb);
+                next_blk = wrap_to;
+            }
+            next_blk += dir;
+            st_s = smem + s2 * C::STAGE;
+            st_pv_next = smem + s1 * C::STAGE;
+            st_dma = smem_lds + s4 * C::STAGE;
+            s0 = s1;
+        });
     }
     wait_vmem<0>();  // requests past the end of the sequence went to free stages; let them finish
 
