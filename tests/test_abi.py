@@ -66,3 +66,11 @@ def test_forward_argument_checks_need_no_device():
     assert lib.fipa_forward(ctypes.byref(d), *mis, ctypes.c_void_p(0x1000), 1 << 30, None) == binding.FIPA_ERR_ALIGNMENT
     with pytest.raises(binding.FipaError):
         binding.workspace_bytes(binding.make_desc(1, -5, 4, 16, 4, 8, 16, 2, 0))
+
+
+def test_stage_timer_argument_checks_need_no_device():
+    lib = binding.lib()
+    assert lib.fipa_profile_begin_every(10, 0) == binding.FIPA_ERR_INVALID_ARG
+    assert lib.fipa_profile_begin_every(0, 1) == binding.FIPA_ERR_INVALID_ARG
+    assert lib.fipa_profile_begin_every(5000, 1) == binding.FIPA_ERR_INVALID_ARG
+    assert lib.fipa_profile_end(None, None) == binding.FIPA_ERR_INVALID_ARG  # timing is not active

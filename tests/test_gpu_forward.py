@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2505_11580_amd import workloads as wl
+from paper_2505_11580_amd import binding
 from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
@@ -166,3 +167,17 @@ def test_bf16_batch_element_without_valid_residues():
 def ipa_oracle_forward(inp):
     from oracle import ipa_oracle
     return ipa_oracle.forward(inp)
+
+
+def test_stage_timer_samples_every_nth_call():
+    import torch
+    inp = wl.make_inputs(1, B=1, L=256, H=4)
+    desc, dev = binding.upload(inp)
+    out = binding.alloc_outputs(desc)
+    binding.fipa_profile_begin_every(10, 4)
+    for _ in range(9):
+        binding.forward(desc, dev, out)
+    torch.cuda.synchronize()
+    stage_ms, n_timed = binding.fipa_profile_end()
+    assert n_timed == 3  # calls 0, 4 and 8
+    assert stage_ms[0] > 0 and stage_ms[1] > 0
