@@ -81,6 +81,23 @@ __device__ __forceinline__ void bwd_issue_block(BwdDma<DZ, MODE> &d, unsigned st
     }
 }
 
+// Entry k of the loads of a block (k is a compile-time constant after unrolling).
+template <int DZ, int MODE, int K = 0>
+__device__ __forceinline__ void bwd_issue_entry(BwdDma<DZ, MODE> &d, unsigned stage, int k)
+{
+    using C = BwdCfg<DZ, MODE>;
+    if constexpr (K < C::NIW + C::NSC) {
+        if (k == K) {
+            if constexpr (K < C::NIW)
+                dma16<4096 * K>(d.src[K], d.voff[K], d.step[K], stage + d.wave_lds);
+            else
+                dma16<C::SC_OFF + 1024 * (K - C::NIW)>(d.src[K], d.voff[K], d.step[K], stage);
+        } else {
+            bwd_issue_entry<DZ, MODE, K + 1>(d, stage, k);
+        }
+    }
+}
+
 struct BwdLane {
     int ka_h, ka_z, va_h, va_z, g;  // per-lane LDS offsets inside a stage, lane half
     float slane, dlane;             // per-stationary-row logit term and D
@@ -89,16 +106,39 @@ struct BwdLane {
 // One step of the pipeline: the small products and the weights of the block in stage `st`
 // (CUR), interleaved with the accumulation of the previous block (stage `st_prev`, weights `wf`
 // on entry) (PREV).  On exit `wf` holds the weights of the current block.
+// The last kTail accumulation MFMAs are held back and issued between the exponentials of the new
+// weights, which would otherwise run with the matrix pipe idle; the loads of the next block
+// (stage `next_stage`) are issued spread over the k-steps instead of back to back.
 template <int DZ, int MODE, bool CUR, bool PREV>
 __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char *__restrict__ st_prev, const BwdLane &ln,
                                          const bf16x8 (&y1f)[BwdCfg<DZ, MODE>::KS],
                                          const bf16x8 (&y2f)[MODE != FIPA_BWD_DV ? BwdCfg<DZ, MODE>::KS : 1],
-                                         f32x16 (&acc)[BwdCfg<DZ, MODE>::NB], bf16x8 (&wf)[2], float &wsum)
+                                         f32x16 (&acc)[BwdCfg<DZ, MODE>::NB], bf16x8 (&wf)[2], float &wsum,
+                                         BwdDma<DZ, MODE> &dma, unsigned next_stage)
 {
     using C = BwdCfg<DZ, MODE>;
     constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
     constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;  // tile the accumulation reads
     constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
+    constexpr int kEntries = C::NIW + C::NSC;  // load entries of a block, spread over the k-steps
+    constexpr int kTail = !CUR ? 0 : (C::KS >= 16 ? 12 : C::KS / 2);  // accumulation MFMAs issued among the weights
+    constexpr int kInLoop = C::KS - kTail;
+    // accumulation operation a: acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
+    auto acc_op = [&](int a) {
+        const int nb = a >> 1, tt = a & 1;
+        const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
+                                      : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+        const int rs = nb < C::NBH ? kHS : C::ZS;
+        const bf16x4 lo = lds_read_tr(src);
+        const bf16x4 hi = lds_read_tr(src + 8 * rs);
+        bf16x8 av;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            av[x] = lo[x];
+            av[4 + x] = hi[x];
+        }
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wf[tt], acc[nb], 0, 0, 0);
+    };
     f32x16 sacc, dpacc;
     if constexpr (CUR) {
 #pragma unroll
@@ -128,26 +168,21 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
                 const bf16x8 a2 = *reinterpret_cast<const bf16x8 *>(s2);
                 dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, y2f[ks], dpacc, 0, 0, 0);
             }
+            if (next_stage != 0xFFFFFFFFu) {
+#pragma unroll
+                for (int e = ks * kEntries / C::KS; e < (ks + 1) * kEntries / C::KS; ++e)
+                    bwd_issue_entry<DZ, MODE>(dma, next_stage, e);
+            }
         }
         if constexpr (PREV) {
-            // acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
-            const int nb = ks >> 1, tt = ks & 1;
-            const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
-                                          : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
-            const int rs = nb < C::NBH ? kHS : C::ZS;
-            const bf16x4 lo = lds_read_tr(src);
-            const bf16x4 hi = lds_read_tr(src + 8 * rs);
-            bf16x8 a;
+            // operations [ks * kInLoop / KS, (ks + 1) * kInLoop / KS) of the accumulation
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                a[x] = lo[x];
-                a[4 + x] = hi[x];
-            }
-            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wf[tt], acc[nb], 0, 0, 0);
+            for (int a = ks * kInLoop / C::KS; a < (ks + 1) * kInLoop / C::KS; ++a) acc_op(a);
         }
     }
     if constexpr (CUR) {
-        // weights of the accumulating product: P (DV) or dS = P (dP - D) (DQ, DK)
+        // weights of the accumulating product: P (DV) or dS = P (dP - D) (DQ, DK), with the held
+        // back accumulation MFMAs (which still use the old weights) between them
         unsigned wp[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
@@ -157,6 +192,12 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
                 w1 *= dpacc[r + 1];
             }
             wp[r >> 1] = pack_pair(w0, w1, wsum);
+            if constexpr (PREV) {
+                const int t = r >> 1;
+#pragma unroll
+                for (int a = kInLoop + t * kTail / 8; a < kInLoop + (t + 1) * kTail / 8; ++a) acc_op(a);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         wf[0] = __builtin_bit_cast(bf16x8, (u32x4){wp[0], wp[1], wp[2], wp[3]});
         wf[1] = __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]});
@@ -297,14 +338,15 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
         wait_vmem<0>();
         wg_barrier();
         sidx = sidx + 1 < C::NSTAGE ? sidx + 1 : 0;
-        if (n + 1 < nblk) bwd_issue_block<DZ, MODE>(dma, smem_lds + sidx * C::STAGE);
+        // (0xFFFFFFFF: no next block)
+        const unsigned next_stage = n + 1 < nblk ? smem_lds + sidx * C::STAGE : 0xFFFFFFFFu;
         if (n == 0)
-            bwd_step<DZ, MODE, true, false>(st, st_prev, ln, y1f, y2f, acc, wf, wsum);
+            bwd_step<DZ, MODE, true, false>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
         else
-            bwd_step<DZ, MODE, true, true>(st, st_prev, ln, y1f, y2f, acc, wf, wsum);
+            bwd_step<DZ, MODE, true, true>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
         st_prev = st;
     }
-    if (nblk > 0) bwd_step<DZ, MODE, false, true>(st_prev, st_prev, ln, y1f, y2f, acc, wf, wsum);
+    if (nblk > 0) bwd_step<DZ, MODE, false, true>(st_prev, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, 0xFFFFFFFFu);
 
     // ---- write acc^T: row srow, columns 32*nb + 8*(r/4) + 4*g + r%4 -------------------------------
     float *orow = p.out + ((size_t)bh * p.Lp + srow) * C::D;
