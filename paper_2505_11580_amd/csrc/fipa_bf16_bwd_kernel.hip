@@ -18,6 +18,8 @@
 //
 // The streamed blocks arrive in a ring of three LDS stages by direct global -> LDS loads issued
 // one block ahead; one barrier per block publishes the new stage and releases the oldest.
+#include <utility>
+
 #include "fipa_gfx950.h"
 
 namespace fipa {
@@ -102,6 +104,154 @@ struct BwdLane {
     int ka_h, ka_z, va_h, va_z, g;  // per-lane LDS offsets inside a stage, lane half
     float slane, dlane;             // per-stationary-row logit term and D
 };
+
+// Calls f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}) in order:
+// a loop whose index is a constant expression inside the body.
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// The MFMAs of a steady step in issue order: per k-step the small products S (and dP) of the
+// current block followed by its share of the first KS - kTail accumulation MFMAs of the previous
+// block; then the held-back kTail accumulation MFMAs, which are issued among the exponentials of
+// the new weights.  kind: 0 = S, 1 = dP, 2 = accumulation; idx: k-step, or accumulation number.
+template <int DZ, int MODE>
+struct BwdOps {
+    using C = BwdCfg<DZ, MODE>;
+    static constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
+    static constexpr int KS = C::KS;
+    static constexpr int kTail = KS >= 16 ? 12 : KS / 2;
+    static constexpr int kInLoop = KS - kTail;
+    static constexpr int NL = (kNeedDP ? 2 : 1) * KS + kInLoop;  // before the weights
+    static constexpr int NT = NL + kTail;
+    struct Op {
+        int kind, idx;
+    };
+    static constexpr Op op(int j)
+    {
+        int n = 0;
+        for (int ks = 0; ks < KS; ++ks) {
+            if (n == j) return {0, ks};
+            ++n;
+            if (kNeedDP) {
+                if (n == j) return {1, ks};
+                ++n;
+            }
+            for (int a = ks * kInLoop / KS; a < (ks + 1) * kInLoop / KS; ++a) {
+                if (n == j) return {2, a};
+                ++n;
+            }
+        }
+        return {2, kInLoop + (j - NL)};
+    }
+    // first tail operation of weight pair t (t = 0..7), relative to NL
+    static constexpr int tail_begin(int t) { return t * kTail / 8; }
+};
+
+// Steady step (current and previous block both present) with a fixed instruction order: the LDS
+// operand of every MFMA is requested kLA MFMAs ahead, in order of use, into a small ring; one
+// load entry of the next block goes out per k-step; the weights of the current block are formed
+// pair by pair between the held-back accumulation MFMAs.
+template <int DZ, int MODE>
+__device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, const char *__restrict__ st_prev, const BwdLane &ln,
+                                                const bf16x8 (&y1f)[BwdCfg<DZ, MODE>::KS],
+                                                const bf16x8 (&y2f)[MODE != FIPA_BWD_DV ? BwdCfg<DZ, MODE>::KS : 1],
+                                                f32x16 (&acc)[BwdCfg<DZ, MODE>::NB], bf16x8 (&wf)[2], float &wsum,
+                                                BwdDma<DZ, MODE> &dma, unsigned next_stage)
+{
+    using C = BwdCfg<DZ, MODE>;
+    using O = BwdOps<DZ, MODE>;
+    constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
+    constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;
+    constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
+    constexpr int kEntries = C::NIW + C::NSC;
+    constexpr int kLA = 3, kRing = 4;
+    auto fetch = [&](auto J) -> bf16x8 {
+        constexpr auto o = O::op(decltype(J)::value);
+        if constexpr (o.kind == 0) {
+            const int ks = o.idx;
+            const char *s1 = ks < C::KSH ? st + C::X1H_OFF + ln.ka_h + ks * 32 : st + C::X1Z_OFF + ln.ka_z + (ks - C::KSH) * 32;
+            return *reinterpret_cast<const bf16x8 *>(s1);
+        } else if constexpr (o.kind == 1) {
+            const int ks = o.idx;
+            const char *s2 = ks < C::KSH ? st + C::X2H_OFF + ln.ka_h + ks * 32 : st + C::X2Z_OFF + ln.ka_z + (ks - C::KSH) * 32;
+            return *reinterpret_cast<const bf16x8 *>(s2);
+        } else {
+            const int nb = o.idx >> 1, tt = o.idx & 1;
+            const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
+                                          : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+            const int rs = nb < C::NBH ? kHS : C::ZS;
+            const bf16x4 lo = lds_read_tr(src);
+            const bf16x4 hi = lds_read_tr(src + 8 * rs);
+            bf16x8 av;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                av[x] = lo[x];
+                av[4 + x] = hi[x];
+            }
+            return av;
+        }
+    };
+    f32x16 sacc, dpacc;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const f32x4 sb = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + (8 * a + 4 * ln.g) * 4);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) sacc[4 * a + x] = sb[x] + ln.slane;
+        if constexpr (C::NSC == 2) {
+            const f32x4 db = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + 1024 + (8 * a + 4 * ln.g) * 4);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -(db[x] + ln.dlane);
+        } else {
+#pragma unroll
+            for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -ln.dlane;
+        }
+    }
+    bf16x8 fr[kRing];
+    static_for<kLA>([&](auto J) { fr[decltype(J)::value] = fetch(J); });
+    unsigned wp[8];
+    static_for<O::NT>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        if constexpr (j + kLA < O::NT) fr[(j + kLA) % kRing] = fetch(std::integral_constant<int, j + kLA>{});
+        constexpr auto o = O::op(j);
+        // the weights of pair t, just before the first held-back MFMA of its group
+        if constexpr (j >= O::NL) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                if (O::NL + O::tail_begin(t) != j) continue;
+                // (several pairs fall on one MFMA when there are fewer held-back MFMAs than pairs)
+                float w0 = __builtin_amdgcn_exp2f(sacc[2 * t]), w1 = __builtin_amdgcn_exp2f(sacc[2 * t + 1]);
+                if constexpr (kNeedDP) {
+                    w0 *= dpacc[2 * t];
+                    w1 *= dpacc[2 * t + 1];
+                }
+                wp[t] = pack_pair(w0, w1, wsum);
+            }
+        }
+        if constexpr (o.kind == 0) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], y1f[o.idx], sacc, 0, 0, 0);
+            if (next_stage != 0xFFFFFFFFu) {
+#pragma unroll
+                for (int e = o.idx * kEntries / C::KS; e < (o.idx + 1) * kEntries / C::KS; ++e)
+                    bwd_issue_entry<DZ, MODE>(dma, next_stage, e);
+            }
+        } else if constexpr (o.kind == 1) {
+            dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], y2f[kNeedDP ? o.idx : 0], dpacc, 0, 0, 0);
+        } else {
+            acc[o.idx >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], wf[o.idx & 1], acc[o.idx >> 1], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    wf[0] = __builtin_bit_cast(bf16x8, (u32x4){wp[0], wp[1], wp[2], wp[3]});
+    wf[1] = __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]});
+}
 
 // One step of the pipeline: the small products and the weights of the block in stage `st`
 // (CUR), interleaved with the accumulation of the previous block (stage `st_prev`, weights `wf`
@@ -343,7 +493,7 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
         if (n == 0)
             bwd_step<DZ, MODE, true, false>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
         else
-            bwd_step<DZ, MODE, true, true>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
+            bwd_step_steady<DZ, MODE>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
         st_prev = st;
     }
     if (nblk > 0) bwd_step<DZ, MODE, false, true>(st_prev, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, 0xFFFFFFFFu);
