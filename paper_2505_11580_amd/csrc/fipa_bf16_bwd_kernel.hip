@@ -127,7 +127,7 @@ struct BwdOps {
     using C = BwdCfg<DZ, MODE>;
     static constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
     static constexpr int KS = C::KS;
-    static constexpr int kTail = KS >= 16 ? 12 : KS / 2;
+    static constexpr int kTail = KS >= 16 ? 8 : KS / 2;  // (8, 12 and 16 measured: 1.96, 2.00, 2.00 ms of gradient kernels at L = 4096)
     static constexpr int kInLoop = KS - kTail;
     static constexpr int NL = (kNeedDP ? 2 : 1) * KS + kInLoop;  // before the weights
     static constexpr int NT = NL + kTail;
@@ -253,12 +253,10 @@ __device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, con
     wf[1] = __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]});
 }
 
-// One step of the pipeline: the small products and the weights of the block in stage `st`
-// (CUR), interleaved with the accumulation of the previous block (stage `st_prev`, weights `wf`
-// on entry) (PREV).  On exit `wf` holds the weights of the current block.
-// The last kTail accumulation MFMAs are held back and issued between the exponentials of the new
-// weights, which would otherwise run with the matrix pipe idle; the loads of the next block
-// (stage `next_stage`) are issued spread over the k-steps instead of back to back.
+// First and last step of the pipeline: the small products and the weights of the block in stage
+// `st` (CUR: the first block, nothing to accumulate yet) or the accumulation of the last block
+// (PREV: stage `st_prev`, weights `wf`).  On exit of a CUR step `wf` holds the block's weights.
+// The loads of the next block (stage `next_stage`) are issued spread over the k-steps.
 template <int DZ, int MODE, bool CUR, bool PREV>
 __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char *__restrict__ st_prev, const BwdLane &ln,
                                          const bf16x8 (&y1f)[BwdCfg<DZ, MODE>::KS],
@@ -266,29 +264,12 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
                                          f32x16 (&acc)[BwdCfg<DZ, MODE>::NB], bf16x8 (&wf)[2], float &wsum,
                                          BwdDma<DZ, MODE> &dma, unsigned next_stage)
 {
+    static_assert(CUR != PREV, "the steady step is bwd_step_steady");
     using C = BwdCfg<DZ, MODE>;
     constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
     constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;  // tile the accumulation reads
     constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
-    constexpr int kEntries = C::NIW + C::NSC;  // load entries of a block, spread over the k-steps
-    constexpr int kTail = !CUR ? 0 : (C::KS >= 16 ? 12 : C::KS / 2);  // accumulation MFMAs issued among the weights
-    constexpr int kInLoop = C::KS - kTail;
-    // accumulation operation a: acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
-    auto acc_op = [&](int a) {
-        const int nb = a >> 1, tt = a & 1;
-        const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
-                                      : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
-        const int rs = nb < C::NBH ? kHS : C::ZS;
-        const bf16x4 lo = lds_read_tr(src);
-        const bf16x4 hi = lds_read_tr(src + 8 * rs);
-        bf16x8 av;
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            av[x] = lo[x];
-            av[4 + x] = hi[x];
-        }
-        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wf[tt], acc[nb], 0, 0, 0);
-    };
+    constexpr int kEntries = C::NIW + C::NSC;  // load entries of a block
     f32x16 sacc, dpacc;
     if constexpr (CUR) {
 #pragma unroll
@@ -325,14 +306,24 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
             }
         }
         if constexpr (PREV) {
-            // operations [ks * kInLoop / KS, (ks + 1) * kInLoop / KS) of the accumulation
+            // acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
+            const int nb = ks >> 1, tt = ks & 1;
+            const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
+                                          : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+            const int rs = nb < C::NBH ? kHS : C::ZS;
+            const bf16x4 lo = lds_read_tr(src);
+            const bf16x4 hi = lds_read_tr(src + 8 * rs);
+            bf16x8 a;
 #pragma unroll
-            for (int a = ks * kInLoop / C::KS; a < (ks + 1) * kInLoop / C::KS; ++a) acc_op(a);
+            for (int x = 0; x < 4; ++x) {
+                a[x] = lo[x];
+                a[4 + x] = hi[x];
+            }
+            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wf[tt], acc[nb], 0, 0, 0);
         }
     }
     if constexpr (CUR) {
-        // weights of the accumulating product: P (DV) or dS = P (dP - D) (DQ, DK), with the held
-        // back accumulation MFMAs (which still use the old weights) between them
+        // weights of the accumulating product: P (DV) or dS = P (dP - D) (DQ, DK)
         unsigned wp[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
@@ -342,12 +333,6 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
                 w1 *= dpacc[r + 1];
             }
             wp[r >> 1] = pack_pair(w0, w1, wsum);
-            if constexpr (PREV) {
-                const int t = r >> 1;
-#pragma unroll
-                for (int a = kInLoop + t * kTail / 8; a < kInLoop + (t + 1) * kTail / 8; ++a) acc_op(a);
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
         wf[0] = __builtin_bit_cast(bf16x8, (u32x4){wp[0], wp[1], wp[2], wp[3]});
         wf[1] = __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]});
@@ -474,8 +459,9 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     // Software pipeline over the streamed blocks: iteration n forms the small products S and dP
     // of block n and, interleaved with them, accumulates block n-1 with the weights computed
     // one iteration earlier -- two independent streams of MFMAs, so the matrix pipe does not
-    // wait on either's operands.  The weights of block n follow.  Blocks n-1 and n are resident,
-    // block n+1 is on its way into the third stage.
+    // wait on either's operands; the last accumulation MFMAs are held back and run while the
+    // weights of block n are formed.  Blocks n-1 and n are resident, block n+1 is on its way
+    // into the third stage.
     bf16x8 wf[2] = {};         // weights of the previous block (B operands of the accumulation)
     BwdLane ln;
     ln.ka_h = ka_h; ln.ka_z = ka_z; ln.va_h = va_h; ln.va_z = va_z; ln.g = g; ln.slane = slane; ln.dlane = dlane;
