@@ -156,6 +156,132 @@ __device__ __forceinline__ void wide_step(const char *__restrict__ st, const cha
     }
 }
 
+// The MFMAs of a steady step in issue order: the S^T MFMAs of the current block with the first
+// NPV - kTail P V MFMAs of the previous block spread between them, then the held-back kTail P V
+// MFMAs, which run while the row maximum and the exponentials of the current block are formed.
+// kind: 0 = S^T (idx = k-step), 1 = P V (idx = 2 * output block + key half).
+template <int DZ, int NWIN>
+struct WideOps {
+    using C = WideCfg<DZ, NWIN>;
+    static constexpr int KS = C::KS, NPV = 2 * C::NBW;
+    static constexpr int kTail = 8;
+    static constexpr int kInLoop = NPV - kTail;
+    static constexpr int NL = KS + kInLoop, NT = KS + NPV;
+    static_assert(kInLoop >= 0, "fewer P V MFMAs than held back");
+    struct Op {
+        int kind, idx;
+    };
+    static constexpr Op op(int j)
+    {
+        int n = 0;
+        for (int ks = 0; ks < KS; ++ks) {
+            if (n == j) return {0, ks};
+            ++n;
+            for (int a = ks * kInLoop / KS; a < (ks + 1) * kInLoop / KS; ++a) {
+                if (n == j) return {1, a};
+                ++n;
+            }
+        }
+        return {1, kInLoop + (j - NL)};
+    }
+};
+
+// Steady step (current and previous block both present) with a fixed instruction order: LDS
+// operands requested kLA MFMAs ahead into a small ring, the loads of the next block spread over
+// the S^T MFMAs, and the softmax of the current block -- row maximum, then the exponentials pair
+// by pair -- between the held-back P V MFMAs of the previous block.  Those still use the old
+// reference, so when the reference has to be raised the accumulator is rescaled only at the end
+// of the step, after the last of them.
+template <int DZ, int NWIN>
+__device__ __forceinline__ void wide_step_steady(const char *__restrict__ st, const char *__restrict__ st_prev, const WideLane &ln,
+                                                 const bf16x8 (&qf)[WideCfg<DZ, NWIN>::KS], f32x16 (&acc)[WideCfg<DZ, NWIN>::NBW],
+                                                 bf16x8 (&pf)[2], float &m_run, float &l_run,
+                                                 WideDma<WideCfg<DZ, NWIN>> &dma, unsigned next_stage, bool load_next)
+{
+    using C = WideCfg<DZ, NWIN>;
+    using O = WideOps<DZ, NWIN>;
+    constexpr int kDmaEvery = C::KS / (C::NIW + 1);
+    constexpr int kLA = 3, kRing = 4;
+    auto fetch = [&](auto J) -> bf16x8 {
+        constexpr auto o = O::op(decltype(J)::value);
+        if constexpr (o.kind == 0) {
+            constexpr int ks = o.idx;
+            const char *src = ks < C::KSH ? st + C::KH_OFF + ln.kaddr_h + ks * 32 : st + C::Z_OFF + ln.kaddr_z + (ks - C::KSH) * 32;
+            return *reinterpret_cast<const bf16x8 *>(src);
+        } else {
+            constexpr int nbw = o.idx >> 1, tt = o.idx & 1;
+            const int nb = ln.win * C::NBW + nbw;  // global 32-column block (win is uniform)
+            const bool head = nb < C::NBH;
+            const char *src = head ? st_prev + C::VH_OFF + ln.vaddr_h + 16 * tt * kHS + nb * 64
+                                   : st_prev + C::Z_OFF + ln.vaddr_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+            const int rs = head ? kHS : C::ZS;
+            const bf16x4 lo = lds_read_tr(src);
+            const bf16x4 hi = lds_read_tr(src + 8 * rs);
+            bf16x8 a;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                a[x] = lo[x];
+                a[4 + x] = hi[x];
+            }
+            return a;
+        }
+    };
+    f32x16 sacc;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const f32x4 bias = *reinterpret_cast<const f32x4 *>(st + C::KB_OFF + (8 * a + 4 * ln.g) * 4);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) sacc[4 * a + x] = bias[x];
+    }
+    bf16x8 fr[kRing];
+    static_for<kLA>([&](auto J) { fr[decltype(J)::value] = fetch(J); });
+    unsigned pp[8];
+    float mx = 0.f, m_use = 0.f, alpha = 1.f, psum = 0.f;
+    bool raise = false;
+    static_for<O::NT>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        if constexpr (j + kLA < O::NT) fr[(j + kLA) % kRing] = fetch(std::integral_constant<int, j + kLA>{});
+        constexpr auto o = O::op(j);
+        constexpr int t = j - O::NL;  // position among the held-back MFMAs
+        if constexpr (t == 0) {
+            // row maximum of the current block (first half of the tree)
+            mx = sacc[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+        } else if constexpr (t == 1) {
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            raise = __any(mx > m_run + kTauW);
+            const float m_new = raise ? fmaxf(m_run, mx) : m_run;
+            alpha = m_new == -INFINITY || !raise ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            m_use = m_new == -INFINITY ? 0.f : m_new;
+        }
+        if constexpr (t >= 2) {
+            constexpr int first = (t - 2) * 8 / (O::kTail - 2), last = (t - 1) * 8 / (O::kTail - 2);
+#pragma unroll
+            for (int q = first; q < last; ++q)
+                pp[q] = pack_pair(__builtin_amdgcn_exp2f(sacc[2 * q] - m_use), __builtin_amdgcn_exp2f(sacc[2 * q + 1] - m_use), psum);
+        }
+        if constexpr (o.kind == 0) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], qf[o.idx], sacc, 0, 0, 0);
+            if (load_next && o.idx % kDmaEvery == 0) wide_issue_entry<C>(dma, next_stage, o.idx / kDmaEvery);
+        } else {
+            acc[o.idx >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], pf[o.idx & 1], acc[o.idx >> 1], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    if (raise) {  // rare: every P V MFMA of the previous block has been issued; bring the accumulator to the new reference
+        l_run *= alpha;
+#pragma unroll
+        for (int nb = 0; nb < C::NBW; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nb][r] *= alpha;
+    }
+    l_run += psum;
+    pf[0] = __builtin_bit_cast(bf16x8, (u32x4){pp[0], pp[1], pp[2], pp[3]});
+    pf[1] = __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]});
+}
+
 template <int DZ, int NWIN>
 __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p)
 {
@@ -275,7 +401,7 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
         if (n == 0)
             wide_step<DZ, NWIN, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
         else
-            wide_step<DZ, NWIN, true, true>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
+            wide_step_steady<DZ, NWIN>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
         st_prev = st;
     }
     if (nblk > 0) wide_step<DZ, NWIN, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run, dma, 0u, false);

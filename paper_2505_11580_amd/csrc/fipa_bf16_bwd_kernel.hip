@@ -18,8 +18,6 @@
 //
 // The streamed blocks arrive in a ring of three LDS stages by direct global -> LDS loads issued
 // one block ahead; one barrier per block publishes the new stage and releases the oldest.
-#include <utility>
-
 #include "fipa_gfx950.h"
 
 namespace fipa {
@@ -104,19 +102,6 @@ struct BwdLane {
     int ka_h, ka_z, va_h, va_z, g;  // per-lane LDS offsets inside a stage, lane half
     float slane, dlane;             // per-stationary-row logit term and D
 };
-
-// Calls f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}) in order:
-// a loop whose index is a constant expression inside the body.
-template <class F, int... Is>
-__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
 
 // The MFMAs of a steady step in issue order: per k-step the small products S (and dP) of the
 // current block followed by its share of the first KS - kTail accumulation MFMAs of the previous

@@ -2,6 +2,8 @@
 // read, direct global -> LDS loads with explicit completion waits, and the fence-free barrier.
 #pragma once
 
+#include <utility>
+
 #include "fipa_bf16_common.h"
 
 namespace fipa {
@@ -69,6 +71,19 @@ template <int N>
 __device__ __forceinline__ void wait_vmem()  // s_waitcnt vmcnt(N) only
 {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// Calls f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}) in order:
+// a loop whose index is a constant expression inside the body.
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 }  // namespace fipa
