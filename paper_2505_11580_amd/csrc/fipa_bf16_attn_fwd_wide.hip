@@ -358,6 +358,13 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
             const bf16_t *src = ks < C::KSH ? qh + ks * 16 + 8 * g : qz + (ks - C::KSH) * 16 + 8 * g;
             qf[ks] = *reinterpret_cast<const bf16x8 *>(src);
         }
+        // Most q^ fragments live in accumulation registers, from where the MFMA reads its B
+        // operand directly (left to itself the compiler parks them there and copies each one to
+        // an architectural register before its MFMA): 16 * NBW registers hold the output
+        // accumulator, 16 the S^T accumulator, the rest of the 256 takes fragments.
+        constexpr int kInAcc = (256 - 16 * C::NBW - 16) / 4 < C::KS ? (256 - 16 * C::NBW - 16) / 4 : C::KS;
+#pragma unroll
+        for (int ks = 0; ks < kInAcc; ++ks) asm volatile("" : "+a"(qf[ks]));
     }
     f32x16 acc[C::NBW];
 #pragma unroll
