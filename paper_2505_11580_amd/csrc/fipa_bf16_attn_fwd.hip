@@ -473,8 +473,13 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // (The staggered starts also spread the tiles of a head over different blocks at any one
     // time; visiting the blocks in the same order everywhere measured slower.)
     // A key-range part takes its share of that rotated sequence: positions pos0 .. pos0 + nblk - 1.
-    const int pos0 = part * nkb / nparts;
-    const int nblk = (part + 1) * nkb / nparts - pos0;  // key blocks this workgroup processes
+    // The first part gets a quarter of a share more than the others: it holds the diagonal blocks
+    // and never has to raise its softmax reference, while the others may (in a compact chain a
+    // later block can lie closer in space than all earlier ones), so equal shares would leave it
+    // waiting.
+    const int pos0 = part == 0 ? 0 : (4 * part + 1) * nkb / (4 * nparts + 1);
+    const int pos1 = part + 1 == nparts ? nkb : (4 * part + 5) * nkb / (4 * nparts + 1);
+    const int nblk = pos1 - pos0;  // key blocks this workgroup processes
     // A part walks its range away from the diagonal too: upwards from its first position when
     // that end is the nearer one (always so for a whole tile), downwards from its last otherwise;
     // a range that approached the diagonal would raise the reference at every block.
