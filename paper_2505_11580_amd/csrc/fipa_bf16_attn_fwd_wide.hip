@@ -35,7 +35,8 @@ struct WideCfg {
     static constexpr int KB_OFF = NIW * 4 * 1024;        // 32 per-key fp32 biases (a full 1 KiB load lands here)
     static constexpr int STAGE = KB_OFF + 1024;
     static constexpr int NSTAGE = 3;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    static constexpr int CW_OFF = NSTAGE * STAGE;        // per-head scale vector of the query-side factors (DZ floats)
+    static constexpr int LDS_BYTES = CW_OFF + DZ * 4;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -352,11 +353,35 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
     bf16x8 qf[C::KS];
     {
         const bf16_t *qh = p.Qh + ((size_t)bh * p.Lp + irow) * kDH;
-        const bf16_t *qz = p.Qz + ((size_t)bh * p.Lp + irow) * DZ;
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const bf16_t *src = ks < C::KSH ? qh + ks * 16 + 8 * g : qz + (ks - C::KSH) * 16 + 8 * g;
-            qf[ks] = *reinterpret_cast<const bf16x8 *>(src);
+        for (int ks = 0; ks < C::KSH; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qh + ks * 16 + 8 * g);
+        // The pair part of q^ -- the bias vector b^{h1} = log2e * w_L * w_b[h] (.) z1 of Algorithm 1
+        // steps 2-3 -- is formed here from z1, which all heads of a residue share, instead of being
+        // packed per head (24 KiB per residue at this width) and read back.  The per-head scale
+        // vector goes through LDS; rows that do not exist or are masked get zeros.
+        {
+            float *cw = reinterpret_cast<float *>(smem + C::CW_OFF);
+            for (int x = tid; x < DZ; x += 256) cw[x] = kLog2e * p.w_L * p.w_b[(size_t)(bh - b * p.H) * p.cz + x % p.cz];
+            __syncthreads();
+            const bool ok = irow < p.L && (p.mask ? p.mask[(size_t)b * p.L + irow] != 0 : true);
+            const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
+            const bf16_t *z1row = p.z1 + ((size_t)b * p.L + min(irow, p.L - 1)) * DZ + 8 * g;
+#pragma unroll
+            for (int ks = 0; ks < C::KS - C::KSH; ++ks) {
+                const uint4 zr = *reinterpret_cast<const uint4 *>(z1row + 16 * ks);
+                const f32x4 w0 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks + 8 * g);
+                const f32x4 w1 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks + 8 * g + 4);
+                const unsigned zw[4] = {zr.x, zr.y, zr.z, zr.w};  // two bf16 values each
+                unsigned pk[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const float wl = x < 2 ? w0[2 * x] : w1[2 * x - 4], wh = x < 2 ? w0[2 * x + 1] : w1[2 * x - 3];
+                    const float lo = wl * __uint_as_float(zw[x] << 16), hi = wh * __uint_as_float(zw[x] & 0xFFFF0000u);
+                    // (round to nearest even, as the pack kernel's conversion; one v_cvt_pk_bf16_f32)
+                    pk[x] = __builtin_bit_cast(unsigned, __builtin_convertvector((f32x2){lo, hi}, bf16x2)) & keep;
+                }
+                qf[C::KSH + ks] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
+            }
         }
         // Most q^ fragments live in accumulation registers, from where the MFMA reads its B
         // operand directly (left to itself the compiler parks them there and copies each one to

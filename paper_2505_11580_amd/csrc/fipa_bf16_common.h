@@ -117,7 +117,9 @@ inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
     w.cen = take((size_t)d.B * 4 * sizeof(float));
     w.kvlen = take((size_t)d.B * sizeof(int));
     w.Qh = take(BH * w.Lp * kDH * 2);
-    w.Qz = take(BH * w.Lp * (size_t)w.DZ * 2);
+    // (per-head query-side factor vectors: only where the attention kernel does not form them itself,
+    // i.e. the unfused path up to width 256, which the backward uses too)
+    w.Qz = with_ohat && w.DZ <= 256 ? take(BH * w.Lp * (size_t)w.DZ * 2) : 0;
     w.Kh = take(BH * w.Lp * kDH * 2);
     w.Vh = take(BH * w.Lp * kDH * 2);
     w.Z2 = take((size_t)d.B * w.Lp * w.DZ * 2);

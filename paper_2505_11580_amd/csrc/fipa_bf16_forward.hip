@@ -39,7 +39,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     pk.B = d.B; pk.L = d.L; pk.Lp = w.Lp; pk.NT = w.NT; pk.H = d.H; pk.c = d.c; pk.Pq = d.Pq;
     pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.DZ;
     pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
-    pk.skip_qz = fused && w.DZ <= 256;
+    pk.skip_qz = (fused && w.DZ <= 256) || w.DZ > 256;  // those attention kernels form the factor vectors themselves
     pk.cen_out = prep_in_pack ? cen : nullptr; pk.kvlen_out = kvlen; pk.counters = counters; pk.n_counters = n_counters;
     e = launch_pack_bf16(pk, stream);
     if (e != hipSuccess) return e;
