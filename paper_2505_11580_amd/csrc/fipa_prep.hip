@@ -1,4 +1,5 @@
-// Per-batch preparation shared by both precisions: centroid of the valid translations and
+// Per-batch preparation (fp32 path, backward, and the bf16 forward with a generic head shape; the
+// AlphaFold2-shape pack kernel does this work itself): centroid of the valid translations and
 // the key-loop bound.  One workgroup per batch element.  The launch also clears the arrival
 // counters of the attention kernel's key-range split, when there are any.
 #include "fipa_internal.h"
