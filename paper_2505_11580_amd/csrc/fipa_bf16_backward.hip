@@ -191,6 +191,7 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
     for (int x = tid; x < p.DZ; x += 256) {
         const int d = x % p.cz;
         float s1 = 0.f, s2 = 0.f;
+#pragma unroll 4  // (four heads' loads in flight; the sums still run in head order)
         for (int h = 0; h < p.H; ++h) {
             const size_t bh = (size_t)b * p.H + h;
             const size_t row = (bh * p.Lp + i) * D + kDH + x;
