@@ -59,7 +59,12 @@ struct AttnCfg {
     static constexpr int KB_OFF = NIW * 4 * 1024;        // 32 per-key fp32 biases (a full 1 KiB load lands here)
     static constexpr int STAGE = KB_OFF + 1024;
     static constexpr int NSTAGE = 5 * STAGE <= 160 * 1024 ? 5 : 4;
-    static constexpr int CW_OFF = NSTAGE * STAGE;        // per-head scale vector of the query-side factors (DZ floats)
+    // Start-up of the fused kernel: the z1 rows of the tile (4 waves x 32 rows x 2 DZ bytes) pass
+    // through LDS on their way into the query-side factor fragments.  They sit behind the first
+    // three stages (which the first three key blocks fill meanwhile) and may reach past the ring.
+    static constexpr int Z1P_OFF = 3 * STAGE;
+    static constexpr int Z1P_END = Z1P_OFF + 4 * 32 * DZ * 2;
+    static constexpr int CW_OFF = Z1P_END > NSTAGE * STAGE ? Z1P_END : NSTAGE * STAGE;  // per-head scale vector of the query-side factors (DZ floats)
     static constexpr int LDS_BYTES = CW_OFF + DZ * 4;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static constexpr int NOPS = 2 * KS;      // MFMAs per pipelined iteration (KS == 2*NB)
@@ -556,7 +561,6 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     // b^{h1} = log2e * w_L * w_b[h] (.) z1 of Algorithm 1 steps 2-3 -- is formed here from z1,
     // which all heads of a residue share, instead of being read per head from memory.
     Wave<DZ> w;
-    uint4 zraw[FUSED ? C::KSZ : 1];
     {
         const bf16_t *qh = p.Qh + ((size_t)bh * p.Lp + irow) * kDH;
 #pragma unroll
@@ -579,10 +583,20 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
                 }
             }
         } else {
-            // this lane's 8-feature chunks of the z1 row; the per-head scale vector goes to LDS
-            const bf16_t *z1row = p.z1 + ((size_t)b * p.L + min(irow, p.L - 1)) * DZ + 8 * g;
+            // This wave's 32 z1 rows go to LDS as whole rows (coalesced; read per lane from memory,
+            // 16 bytes of each of 32 rows per load, they take several times as long), the 16-byte
+            // chunks of row r stored at position chunk ^ (r mod chunks-per-row) so that the reads
+            // below -- one chunk index across 32 rows -- spread over the banks.  The per-head
+            // scale vector goes to LDS as well.
+            constexpr int kRowBytes = DZ * 2, kWaveBytes = 32 * kRowBytes, kCpr = DZ / 8;
+            const char *zbase = reinterpret_cast<const char *>(p.z1 + (size_t)b * p.L * DZ);
+            const int row0 = qt * kTileQ + wave * 32;
 #pragma unroll
-            for (int ks = 0; ks < C::KSZ; ++ks) zraw[ks] = *reinterpret_cast<const uint4 *>(z1row + 16 * ks);
+            for (int k = 0; k < kWaveBytes / 1024; ++k) {
+                const int slot = 64 * k + lane, r = slot / kCpr, c = (slot % kCpr) ^ (r % kCpr);
+                int voff = min(row0 + r, p.L - 1) * kRowBytes + 16 * c;
+                dma16<0>(zbase, voff, 0, smem_lds + C::Z1P_OFF + wave * kWaveBytes + 1024 * k);
+            }
             if (tid < DZ)
                 reinterpret_cast<float *>(smem + C::CW_OFF)[tid] =
                     kLog2e * p.w_L * p.w_b[(size_t)(bh - b * p.H) * p.cz + tid % p.cz];
@@ -623,11 +637,15 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             const bool ok = irow < p.L && (p.mask ? p.mask[(size_t)b * p.L + irow] != 0 : true);
             const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
             const float *cw = reinterpret_cast<const float *>(smem + C::CW_OFF) + 8 * g;
+            constexpr int kCpr = DZ / 8;
+            const char *z1l = smem + C::Z1P_OFF + wave * (32 * DZ * 2) + li * (DZ * 2);
 #pragma unroll
             for (int ks = 0; ks < C::KSZ; ++ks) {
                 const f32x4 w0 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks);
                 const f32x4 w1 = *reinterpret_cast<const f32x4 *>(cw + 16 * ks + 4);
-                const unsigned zw[4] = {zraw[ks].x, zraw[ks].y, zraw[ks].z, zraw[ks].w};  // two bf16 values each
+                // features 16 ks + 8 g .. + 7 of row li: chunk 2 ks + g
+                const uint4 zr = *reinterpret_cast<const uint4 *>(z1l + 16 * ((2 * ks + g) ^ (li % kCpr)));
+                const unsigned zw[4] = {zr.x, zr.y, zr.z, zr.w};  // two bf16 values each
                 unsigned pk[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
@@ -638,7 +656,9 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
                 }
                 w.qf[C::KSH + ks] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
             }
-            // blocks 2 and 3 of the sequence (the steady loop waits for them)
+            // blocks 2 and 3 of the sequence (the steady loop waits for them); block 3 goes where
+            // z1 rows sit until every wave has its fragments
+            wg_barrier();
 #pragma unroll
             for (int i = 2; i < 4; ++i) {
                 if (next_blk == wrap_at) {
