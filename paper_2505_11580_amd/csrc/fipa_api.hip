@@ -134,7 +134,7 @@ int fipa_module_workspace_bytes(const fipa_desc *desc, int32_t d_s, size_t *byte
     const int rc = check_desc(desc, false);
     if (rc != FIPA_OK) return rc;
     if (desc->dtype != FIPA_DTYPE_BF16 || !module_shape_supported(*desc, d_s)) return FIPA_ERR_UNSUPPORTED;
-    if (bytes) *bytes = module_forward_workspace(*desc);
+    if (bytes) *bytes = module_forward_workspace(*desc, d_s);
     return FIPA_OK;
 }
 

@@ -87,7 +87,7 @@ size_t bf16_backward_workspace(const fipa_desc &d);
 // IPA module around the core (fipa_module.hip)
 bool module_shape_supported(const fipa_desc &d, int d_s);
 bool module_backward_shape_supported(const fipa_desc &d, int d_s);
-size_t module_forward_workspace(const fipa_desc &d);
+size_t module_forward_workspace(const fipa_desc &d, int d_s);
 hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void *ws, hipStream_t stream);
 size_t module_backward_workspace(const fipa_desc &d, int d_s);
 hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, const ModuleBwdArgs &g, void *ws,

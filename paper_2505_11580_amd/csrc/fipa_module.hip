@@ -9,6 +9,8 @@
 //     the concatenation (o_pair | o | o_pts | norms of o_pts) and the norms on the fly.
 #include "fipa_gfx950.h"
 
+#include <type_traits>
+
 namespace fipa {
 
 namespace {
@@ -95,6 +97,7 @@ struct GemmTile {
     static constexpr int CA = TM * (kGK / 8) / 256, CW = TN * (kGK / 8) / 256;  // 16-byte chunks per thread and K chunk
     static_assert(CA >= 1 && CW >= 1, "tile too small for 256 threads");
     static constexpr int LDS_BYTES = 2 * (TM + TN) * kGRS;
+    static constexpr int LDS_TOTAL = LDS_BYTES + TN * 4;   // + the tile's slice of the bias vector
 };
 
 template <class T, bool CONCAT_A, bool SCATTER>
@@ -105,6 +108,10 @@ __global__ __launch_bounds__(256) void fipa_gemm_kernel(GemmParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, kg = lane >> 5;
     const int m0 = blockIdx.x * T::TM, n0 = blockIdx.y * T::TN;
+    // the tile's slice of the bias (zero where there is none; a split-K product adds it in its first part only);
+    // the first barrier below publishes it
+    float *bias_l = reinterpret_cast<float *>(lds + T::LDS_BYTES);
+    if (tid < T::TN) bias_l[tid] = (p.bias && n0 + tid < p.N && blockIdx.z == 0) ? p.bias[n0 + tid] : 0.f;
 
     // staging: thread t moves chunks (row t/8 + 32 j, 8 k-values t%8): j < CA of A, j < CW of W
     // (fetch only requests; whatever needs the loaded values -- the float -> bfloat16 conversion
@@ -192,49 +199,69 @@ __global__ __launch_bounds__(256) void fipa_gemm_kernel(GemmParams p)
         __syncthreads();
     }
 
-    // the lane holds rows m0 + 32 (MTW wm + a) + li and output features
-    // n0 + 32 (NTW wn + b) + 8 q + 4 kg + x, x = 0..3
+    // The lane holds rows 32 (MTW wm + a) + li of the tile and output features
+    // 32 (NTW wn + b) + 8 q + 4 kg + x, x = 0..3.  Stored from here, every lane of a store would
+    // touch a different row, 8 or 16 bytes of a 64-byte line each, and the number of partial-line
+    // writes, not their bytes, is what the memory system then counts (at B*L = 4096 the input
+    // projection spent 6 of its 14 microseconds on them).  The tile goes through LDS instead, in
+    // its final type, and leaves as 16-byte pieces that are neighbours along a row.
+    // (The loop above ended with a barrier: both operand buffers are free.)
+    using OutT = std::conditional_t<SCATTER, bf16_t, float>;
+    constexpr int kPer = 16 / (int)sizeof(OutT);               // outputs per 16-byte piece
+    constexpr int kORS = T::TN * (int)sizeof(OutT) + 16;       // LDS row stride of the staged tile
+    static_assert(T::TM * kORS <= T::LDS_BYTES, "the staged output tile must fit the operand buffers");
 #pragma unroll
-    for (int a = 0; a < MTW; ++a) {
-        const int row = m0 + 32 * (MTW * wm + a) + li;
-        if (row >= p.M) continue;
+    for (int a = 0; a < MTW; ++a)
 #pragma unroll
         for (int b = 0; b < NTW; ++b)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int col = n0 + 32 * (NTW * wn + b) + 8 * q + 4 * kg;
-                if (col >= p.N) continue;
+                const int rl = 32 * (MTW * wm + a) + li, cl = 32 * (NTW * wn + b) + 8 * q + 4 * kg;
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_l + cl);
                 float val[4];
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    val[x] = acc[a][b][4 * q + x] + ((p.bias && col + x < p.N) ? p.bias[col + x] : 0.f);
+                for (int x = 0; x < 4; ++x) val[x] = acc[a][b][4 * q + x] + bv[x];
+                char *dst = lds + rl * kORS + cl * (int)sizeof(OutT);
                 if constexpr (SCATTER) {
-                    int seg = 0;
-#pragma unroll
-                    for (int s = 1; s < 6; ++s)
-                        if (col >= p.seg_start[s]) seg = s;
-                    const int start = p.seg_start[seg], width = p.seg_start[seg + 1] - start;
-                    if (col + 3 < p.seg_start[seg + 1] && ((width | (col - start)) & 3) == 0) {
-                        const unsigned lo = (unsigned)f2bf(val[0]) | ((unsigned)f2bf(val[1]) << 16);
-                        const unsigned hi = (unsigned)f2bf(val[2]) | ((unsigned)f2bf(val[3]) << 16);
-                        *reinterpret_cast<uint2 *>(p.seg_ptr[seg] + (size_t)row * width + (col - start)) = make_uint2(lo, hi);
-                    } else {
-                        for (int x = 0; x < 4 && col + x < p.N; ++x) {  // a run that crosses into the next tensor
-                            int sx = seg;
-                            while (col + x >= p.seg_start[sx + 1]) ++sx;
-                            const int wx = p.seg_start[sx + 1] - p.seg_start[sx];
-                            p.seg_ptr[sx][(size_t)row * wx + (col + x - p.seg_start[sx])] = f2bf(val[x]);
-                        }
-                    }
+                    const unsigned lo = (unsigned)f2bf(val[0]) | ((unsigned)f2bf(val[1]) << 16);
+                    const unsigned hi = (unsigned)f2bf(val[2]) | ((unsigned)f2bf(val[3]) << 16);
+                    *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
                 } else {
-                    float *C = p.C + (p.chunks_per_split > 0 ? (size_t)blockIdx.z * p.M * p.N : 0);
-                    if (col + 3 < p.N && (p.N & 3) == 0) {
-                        *reinterpret_cast<f32x4 *>(C + (size_t)row * p.N + col) = (f32x4){val[0], val[1], val[2], val[3]};
-                    } else {
-                        for (int x = 0; x < 4 && col + x < p.N; ++x) C[(size_t)row * p.N + col + x] = val[x];
-                    }
+                    *reinterpret_cast<f32x4 *>(dst) = (f32x4){val[0], val[1], val[2], val[3]};
                 }
             }
+    __syncthreads();
+    constexpr int kPieces = T::TN / kPer;  // per row
+    for (int idx = tid; idx < T::TM * kPieces; idx += 256) {
+        const int rl = idx / kPieces, pc = idx - rl * kPieces;
+        const int row = m0 + rl, col = n0 + pc * kPer;
+        if (row >= p.M || col >= p.N) continue;
+        const uint4 piece = *reinterpret_cast<const uint4 *>(lds + rl * kORS + pc * 16);
+        const OutT *vals = reinterpret_cast<const OutT *>(&piece);
+        if constexpr (SCATTER) {
+            int seg = 0;
+#pragma unroll
+            for (int sg = 1; sg < 6; ++sg)
+                if (col >= p.seg_start[sg]) seg = sg;
+            const int start = p.seg_start[seg], width = p.seg_start[seg + 1] - start;
+            if (col + kPer <= p.seg_start[seg + 1] && ((width | (col - start)) & (kPer - 1)) == 0) {
+                *reinterpret_cast<uint4 *>(p.seg_ptr[seg] + (size_t)row * width + (col - start)) = piece;
+            } else {
+                for (int x = 0; x < kPer && col + x < p.N; ++x) {  // a piece that crosses into the next tensor, or is not aligned
+                    int sx = seg;
+                    while (col + x >= p.seg_start[sx + 1]) ++sx;
+                    const int wx = p.seg_start[sx + 1] - p.seg_start[sx];
+                    p.seg_ptr[sx][(size_t)row * wx + (col + x - p.seg_start[sx])] = vals[x];
+                }
+            }
+        } else {
+            float *C = p.C + (p.chunks_per_split > 0 ? (size_t)blockIdx.z * p.M * p.N : 0);
+            if (col + kPer <= p.N && (p.N & (kPer - 1)) == 0) {
+                *reinterpret_cast<uint4 *>(C + (size_t)row * p.N + col) = piece;
+            } else {
+                for (int x = 0; x < kPer && col + x < p.N; ++x) C[(size_t)row * p.N + col + x] = vals[x];
+            }
+        }
     }
 }
 
@@ -242,21 +269,42 @@ template <class T, bool CONCAT_A, bool SCATTER>
 hipError_t launch_gemm(const GemmParams &g, hipStream_t stream)
 {
     hipError_t e = hipFuncSetAttribute((const void *)fipa_gemm_kernel<T, CONCAT_A, SCATTER>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_TOTAL);
     if (e != hipSuccess) return e;
     const int nkc = (g.K + kGK - 1) / kGK;
     const int nsplit = g.chunks_per_split > 0 ? (nkc + g.chunks_per_split - 1) / g.chunks_per_split : 1;
     hipLaunchKernelGGL((fipa_gemm_kernel<T, CONCAT_A, SCATTER>),
-                       dim3((g.M + T::TM - 1) / T::TM, (g.N + T::TN - 1) / T::TN, nsplit), dim3(256), T::LDS_BYTES,
+                       dim3((g.M + T::TM - 1) / T::TM, (g.N + T::TN - 1) / T::TN, nsplit), dim3(256), T::LDS_TOTAL,
                        stream, g);
     return hipGetLastError();
 }
 
 struct ModuleLayout {
-    size_t core, q, k, v, q_pts, k_pts, v_pts, o, o_pts, o_pair, total;
+    size_t core, q, k, v, q_pts, k_pts, v_pts, o, o_pts, o_pair, part, total;
 };
 
-ModuleLayout module_layout(const fipa_desc &d)
+// The output projection (Eq. 5) at B*L rows has few output tiles for 256 compute units (N = d_s
+// is small, K = H (c_z + c + 4 P_v) long): 64 x 128 tiles -- the float32 concatenation is then read
+// through L2 twice at d_s = 256 instead of four times -- with K split into up to four parts that
+// leave partial products, summed in a fixed order afterwards.  (Measured at B*L = 4096, d_s = 256:
+// 64 x 64 tiles unsplit 28 us; this form 16 + 5 us; 128 x 128 tiles split in eight 23 + 7 us.)
+using OutTile = GemmTile<2, 2, 1, 2>;
+struct OutSplit {
+    int chunks_per_split, nsplit;  // nsplit = 1: no partial products
+};
+OutSplit out_projection_split(int M, int d_s, int n_cat)
+{
+    const int tiles = ((M + OutTile::TM - 1) / OutTile::TM) * ((d_s + OutTile::TN - 1) / OutTile::TN);
+    const int nkc = (n_cat + kGK - 1) / kGK;
+    int want = 512 / (tiles > 0 ? tiles : 1);
+    want = want > 4 ? 4 : (want < 1 ? 1 : want);
+    OutSplit o;
+    o.chunks_per_split = (nkc + want - 1) / want;
+    o.nsplit = (nkc + o.chunks_per_split - 1) / o.chunks_per_split;
+    return o;
+}
+
+ModuleLayout module_layout(const fipa_desc &d, int d_s)
 {
     ModuleLayout w;
     const size_t M = (size_t)d.B * d.L;
@@ -276,6 +324,8 @@ ModuleLayout module_layout(const fipa_desc &d)
     w.o = take(M * d.H * d.c * 4);
     w.o_pts = take(M * d.H * d.Pv * 3 * 4);
     w.o_pair = take(M * d.H * d.cz * 4);
+    const OutSplit os = out_projection_split((int)M, d_s, d.H * (d.cz + d.c + 4 * d.Pv));
+    w.part = os.nsplit > 1 ? take((size_t)os.nsplit * M * d_s * 4) : 0;
     w.total = off;
     return w;
 }
@@ -366,15 +416,20 @@ __global__ __launch_bounds__(256) void fipa_gather6_kernel(GemmParams p, bf16_t 
     }
 }
 
-// out[i] = sum over the nsplit partial matrices (fixed order), n entries each.
+// out[i] = sum over the nsplit partial matrices (fixed order), n entries each; n is a multiple of 4
+// (every matrix summed here has d_s, a multiple of 16, as one of its dimensions).
 __global__ __launch_bounds__(256) void fipa_sum_partials_kernel(const float *__restrict__ part, float *__restrict__ out,
                                                                  size_t n, int nsplit)
 {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t i = 4 * ((size_t)blockIdx.x * 256 + threadIdx.x);
     if (i >= n) return;
-    float s = 0.f;
-    for (int z = 0; z < nsplit; ++z) s += part[(size_t)z * n + i];
-    out[i] = s;
+    f32x4 s = *reinterpret_cast<const f32x4 *>(part + i);
+    for (int z = 1; z < nsplit; ++z) {
+        const f32x4 t = *reinterpret_cast<const f32x4 *>(part + (size_t)z * n + i);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) s[x] += t[x];
+    }
+    *reinterpret_cast<f32x4 *>(out + i) = s;
 }
 
 // out[r] = sum over the C entries of row r of a bf16 matrix [R, C] (one workgroup per row, fixed order).
@@ -466,11 +521,11 @@ bool module_shape_supported(const fipa_desc &d, int d_s)
            n_cat % 16 == 0;
 }
 
-size_t module_forward_workspace(const fipa_desc &d) { return module_layout(d).total; }
+size_t module_forward_workspace(const fipa_desc &d, int d_s) { return module_layout(d, d_s).total; }
 
 hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void *ws, hipStream_t stream)
 {
-    const ModuleLayout w = module_layout(d);
+    const ModuleLayout w = module_layout(d, d_s);
     char *base = static_cast<char *>(ws);
     const int M = d.B * d.L;
 
@@ -503,8 +558,18 @@ hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void
     g2.o_pair = f.o_pair; g2.o = f.o; g2.o_pts = f.o_pts;
     g2.k_pair = d.H * d.cz; g2.k_o = d.H * d.c; g2.k_pts = d.H * d.Pv * 3;
     g2.K = g2.k_pair + g2.k_o + g2.k_pts + d.H * d.Pv;
-    g2.C = a.s_out;
-    return launch_gemm<GemmTile<2, 2, 1, 1>, true, false>(g2, stream);
+    const OutSplit os = out_projection_split(M, d_s, g2.K);
+    if (os.nsplit == 1) {
+        g2.C = a.s_out;
+        return launch_gemm<OutTile, true, false>(g2, stream);
+    }
+    g2.C = (float *)(base + w.part);
+    g2.chunks_per_split = os.chunks_per_split;
+    e = launch_gemm<OutTile, true, false>(g2, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fipa_sum_partials_kernel, dim3((unsigned)(((size_t)M * d_s / 4 + 255) / 256)), dim3(256), 0, stream,
+                       g2.C, a.s_out, (size_t)M * d_s, os.nsplit);
+    return hipGetLastError();
 }
 
 size_t module_backward_workspace(const fipa_desc &d, int d_s) { return module_bwd_layout(d, d_s).total; }
@@ -565,7 +630,7 @@ hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, con
     gw.M = d_s; gw.N = n_cat; gw.K = Mp;
     gw.A = gT; gw.W = (const bf16_t *)(base + w.catT); gw.C = (float *)(base + w.part); gw.chunks_per_split = kWgradChunks;
     FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, false>(gw, stream)));
-    hipLaunchKernelGGL(fipa_sum_partials_kernel, dim3((unsigned)(((size_t)d_s * n_cat + 255) / 256)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(fipa_sum_partials_kernel, dim3((unsigned)(((size_t)d_s * n_cat / 4 + 255) / 256)), dim3(256), 0, stream,
                        gw.C, g.d_w_out, (size_t)d_s * n_cat, nsplit);
     if (g.d_b_out) hipLaunchKernelGGL(fipa_rowsum_bf16_kernel, dim3(d_s), dim3(256), 0, stream, gT, g.d_b_out, Mp);
     FIPA_TRY(hipGetLastError());
@@ -602,7 +667,7 @@ hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, con
     gi.M = n_in; gi.N = d_s; gi.K = Mp;
     gi.A = dXT; gi.W = (const bf16_t *)(base + w.sT); gi.C = (float *)(base + w.part); gi.chunks_per_split = kWgradChunks;
     FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, false>(gi, stream)));
-    hipLaunchKernelGGL(fipa_sum_partials_kernel, dim3((unsigned)(((size_t)n_in * d_s + 255) / 256)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(fipa_sum_partials_kernel, dim3((unsigned)(((size_t)n_in * d_s / 4 + 255) / 256)), dim3(256), 0, stream,
                        gi.C, g.d_w_in, (size_t)n_in * d_s, nsplit);
     if (g.d_b_in) hipLaunchKernelGGL(fipa_rowsum_bf16_kernel, dim3(n_in), dim3(256), 0, stream, dXT, g.d_b_in, Mp);
 #undef FIPA_TRY
