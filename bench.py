@@ -48,7 +48,7 @@ def cpu_baseline(inp, flops_per_pair, budget_s=12.0):
     }
 
 
-def backward_leg(workload, steps=10, warmup=3):
+def backward_leg(workload, steps=30, warmup=10):
     """fipa_backward (recomputation of the lifted forward + the three gradient kernels + unpack) on
     the gradient workload; reported beside the headline forward number, not part of `value`."""
     import torch
@@ -80,7 +80,7 @@ def backward_leg(workload, steps=10, warmup=3):
     }
 
 
-def module_leg(workload, d_s=256, steps=50, warmup=5):
+def module_leg(workload, d_s=256, steps=300, warmup=100):
     """fipa_module_forward (input projection + core + output projection) on the headline
     workload; reported beside the headline number, not part of `value`."""
     import torch
@@ -104,7 +104,7 @@ def module_leg(workload, d_s=256, steps=50, warmup=5):
     grads = binding.alloc_module_grads(desc, d_s)
     up = torch.randn(m["dims"]["B"], m["dims"]["L"], d_s, device="cuda:0")
     bsteps = max(3, steps // 5)
-    for _ in range(2):
+    for _ in range(max(2, warmup // 10)):
         binding.module_backward(desc, d_s, dev, up, grads)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -332,25 +332,18 @@ hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream)
 
 size_t bf16_backward_workspace(const fipa_desc &d) { return bwd_layout(d).total; }
 
-hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream)
-{
-    const BwdLayout w = bwd_layout(d);
-    char *base = static_cast<char *>(ws);
-    float *cen = reinterpret_cast<float *>(base + w.f.cen);
-    int *kvlen = reinterpret_cast<int *>(base + w.f.kvlen);
-    StageTimer timer(stream);
+namespace {
 
-    // ---- forward pack and (unfused) forward attention: lifted tensors, O^, log-sum-exp -------------
-    timer.begin(0);
-    hipError_t e = launch_prep(d, a.f.trans, a.f.mask, cen, kvlen, nullptr, 0, stream);
-    if (e != hipSuccess) return e;
+PackParams bwd_pack_params(const fipa_desc &d, const FwdArgs &f, const BwdLayout &w, char *base)
+{
     PackParams pk;
-    pk.q = (const bf16_t *)a.f.q; pk.k = (const bf16_t *)a.f.k; pk.v = (const bf16_t *)a.f.v;
-    pk.q_pts = (const bf16_t *)a.f.q_pts; pk.k_pts = (const bf16_t *)a.f.k_pts;
-    pk.v_pts = (const bf16_t *)a.f.v_pts;
-    pk.z1 = (const bf16_t *)a.f.z1; pk.z2 = (const bf16_t *)a.f.z2;
-    pk.rot = a.f.rot; pk.trans = a.f.trans; pk.w_b = a.f.w_b; pk.gamma = a.f.gamma; pk.cen = cen;
-    pk.mask = a.f.mask;
+    pk.q = (const bf16_t *)f.q; pk.k = (const bf16_t *)f.k; pk.v = (const bf16_t *)f.v;
+    pk.q_pts = (const bf16_t *)f.q_pts; pk.k_pts = (const bf16_t *)f.k_pts;
+    pk.v_pts = (const bf16_t *)f.v_pts;
+    pk.z1 = (const bf16_t *)f.z1; pk.z2 = (const bf16_t *)f.z2;
+    pk.rot = f.rot; pk.trans = f.trans; pk.w_b = f.w_b; pk.gamma = f.gamma;
+    pk.cen = reinterpret_cast<float *>(base + w.f.cen);
+    pk.mask = f.mask;
     pk.Qh = (bf16_t *)(base + w.f.Qh); pk.Qz = (bf16_t *)(base + w.f.Qz);
     pk.Kh = (bf16_t *)(base + w.f.Kh); pk.Vh = (bf16_t *)(base + w.f.Vh); pk.Z2 = (bf16_t *)(base + w.f.Z2);
     pk.kbias = (float *)(base + w.f.kbias); pk.qbias = (float *)(base + w.f.qbias);
@@ -359,6 +352,18 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
     pk.skip_qz = false;
     pk.cen_out = nullptr; pk.kvlen_out = nullptr; pk.counters = nullptr; pk.n_counters = 0;
+    return pk;
+}
+
+// Forward pack and (unfused) forward attention: leaves the lifted tensors, O^ and the log-sum-exp
+// in the workspace; when f.o is set the core's outputs (steps 8-9) are produced from O^ as well.
+hipError_t backward_forward_part(const fipa_desc &d, const FwdArgs &f, const BwdLayout &w, char *base, hipStream_t stream)
+{
+    float *cen = reinterpret_cast<float *>(base + w.f.cen);
+    int *kvlen = reinterpret_cast<int *>(base + w.f.kvlen);
+    hipError_t e = launch_prep(d, f.trans, f.mask, cen, kvlen, nullptr, 0, stream);
+    if (e != hipSuccess) return e;
+    const PackParams pk = bwd_pack_params(d, f, w, base);
     e = launch_pack_bf16(pk, stream);
     if (e != hipSuccess) return e;
 
@@ -366,21 +371,40 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     at.Qh = pk.Qh; at.Qz = pk.Qz; at.Kh = pk.Kh; at.Vh = pk.Vh; at.Z2 = pk.Z2;
     at.kbias = pk.kbias; at.qbias = pk.qbias; at.kvlen = kvlen;
     at.Ohat = (float *)(base + w.f.Ohat); at.lse2 = (float *)(base + w.f.lse2);
-    at.rot = a.f.rot; at.trans = a.f.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.f.mask;
+    at.rot = f.rot; at.trans = f.trans; at.cen = cen; at.z1 = pk.z1; at.mask = f.mask;
     at.o = nullptr; at.o_pts = nullptr; at.o_pair = nullptr; at.lse = nullptr;
     at.B = d.B; at.L = d.L; at.Lp = w.f.Lp; at.H = d.H; at.NT = w.f.NT;
-    at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.f.w_b; at.w_L = d.w_L;
+    at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = f.w_b; at.w_L = d.w_L;
     at.plan = w.f.plan; at.partial = nullptr; at.counters = nullptr;  // (unfused: never split)
     e = launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || !f.o) return e;
+
+    EpiParams ep;
+    ep.Ohat = at.Ohat; ep.lse2 = at.lse2; ep.qbias = pk.qbias; ep.rot = f.rot; ep.trans = f.trans;
+    ep.cen = cen; ep.z1 = pk.z1; ep.mask = f.mask;
+    ep.o = f.o; ep.o_pts = f.o_pts; ep.o_pair = f.o_pair; ep.lse = f.lse;
+    ep.B = d.B; ep.L = d.L; ep.Lp = w.f.Lp; ep.H = d.H; ep.c = d.c; ep.Pv = d.Pv; ep.cz = d.cz;
+    ep.r = d.r; ep.DZ = w.f.DZ;
+    return launch_epilogue_bf16(ep, stream);
+}
+
+// Everything after the forward part: lifting of the upstream gradients, the three gradient
+// kernels, and the way back to the inputs.
+hipError_t backward_gradient_part(const fipa_desc &d, const BwdArgs &a, const BwdLayout &w, char *base, hipStream_t stream,
+                                  StageTimer &timer)
+{
+    float *cen = reinterpret_cast<float *>(base + w.f.cen);
+    int *kvlen = reinterpret_cast<int *>(base + w.f.kvlen);
+    const PackParams pk = bwd_pack_params(d, a.f, w, base);
+    float *Ohat = (float *)(base + w.f.Ohat);
 
     BwdPackParams bp;
     bp.d_o = a.d_o; bp.d_o_pts = a.d_o_pts; bp.d_o_pair = a.d_o_pair; bp.rot = a.f.rot;
-    bp.Ohat = at.Ohat; bp.lse2 = at.lse2; bp.z1 = pk.z1; bp.mask = a.f.mask;
+    bp.Ohat = Ohat; bp.lse2 = (float *)(base + w.f.lse2); bp.z1 = pk.z1; bp.mask = a.f.mask;
     bp.dOhat = (bf16_t *)(base + w.dOhat); bp.Dvec = (float *)(base + w.Dvec); bp.nlse = (float *)(base + w.nlse);
     bp.B = d.B; bp.L = d.L; bp.Lp = w.f.Lp; bp.H = d.H; bp.c = d.c; bp.Pv = d.Pv; bp.cz = d.cz; bp.r = d.r;
     bp.DZ = w.f.DZ;
-    e = launch_bwd_pack_bf16(bp, stream);
+    hipError_t e = launch_bwd_pack_bf16(bp, stream);
     if (e != hipSuccess) return e;
     timer.end(0);
 
@@ -389,7 +413,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     BwdParams bw;
     bw.Qh = pk.Qh; bw.Qz = pk.Qz; bw.Kh = pk.Kh; bw.Vh = pk.Vh; bw.Z2 = pk.Z2; bw.dOhat = bp.dOhat;
     bw.kbias = pk.kbias; bw.nlse = bp.nlse; bw.Dvec = bp.Dvec; bw.kvlen = kvlen;
-    bw.B = d.B; bw.Lp = w.f.Lp; bw.H = d.H; bw.total_tiles = at.total_tiles;
+    bw.B = d.B; bw.Lp = w.f.Lp; bw.H = d.H; bw.total_tiles = (w.f.Lp / kTileQ) * d.B * d.H;
     bw.out = (float *)(base + w.dQhat); bw.wsum = (float *)(base + w.rowsum);
     e = launch_bwd_bf16(bw, w.f.DZ, FIPA_BWD_DQ, stream);
     if (e != hipSuccess) return e;
@@ -409,7 +433,7 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     up.rot = a.f.rot; up.trans = a.f.trans; up.cen = cen; up.gamma = a.f.gamma; up.w_b = a.f.w_b;
     up.d_o_pair = a.d_o_pair; up.mask = a.f.mask;
     up.dQhat = (const float *)(base + w.dQhat); up.dKhat = (const float *)(base + w.dKhat);
-    up.dVhat = (const float *)(base + w.dVhat); up.Ohat = at.Ohat;
+    up.dVhat = (const float *)(base + w.dVhat); up.Ohat = Ohat;
     up.rowsum = (const float *)(base + w.rowsum); up.colsum = (const float *)(base + w.colsum);
     up.d_q = (bf16_t *)a.d_q; up.d_k = (bf16_t *)a.d_k; up.d_v = (bf16_t *)a.d_v;
     up.d_q_pts = (bf16_t *)a.d_q_pts; up.d_k_pts = (bf16_t *)a.d_k_pts; up.d_v_pts = (bf16_t *)a.d_v_pts;
@@ -422,6 +446,36 @@ hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStre
     e = launch_bwd_unpack_bf16(up, stream);
     timer.end(2);
     return e;
+}
+
+}  // namespace
+
+hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream)
+{
+    const BwdLayout w = bwd_layout(d);
+    char *base = static_cast<char *>(ws);
+    StageTimer timer(stream);
+    timer.begin(0);
+    FwdArgs f = a.f;
+    f.o = nullptr;  // (the core's outputs are not needed here)
+    const hipError_t e = backward_forward_part(d, f, w, base, stream);
+    if (e != hipSuccess) return e;
+    return backward_gradient_part(d, a, w, base, stream, timer);
+}
+
+// The same in two calls on one workspace, for a caller that needs the core's outputs before it
+// can form the upstream gradients (the module's backward): the first call also writes f.o,
+// f.o_pts, f.o_pair; the workspace must not be touched in between.
+hipError_t bf16_backward_begin(const fipa_desc &d, const FwdArgs &f, void *ws, hipStream_t stream)
+{
+    if (!f.o || !f.o_pts || !f.o_pair) return hipErrorInvalidValue;
+    return backward_forward_part(d, f, bwd_layout(d), static_cast<char *>(ws), stream);
+}
+
+hipError_t bf16_backward_finish(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream)
+{
+    StageTimer timer;  // (not timed)
+    return backward_gradient_part(d, a, bwd_layout(d), static_cast<char *>(ws), stream, timer);
 }
 
 }  // namespace fipa

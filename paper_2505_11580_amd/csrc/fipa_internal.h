@@ -59,6 +59,7 @@ struct ModuleBwdArgs {
 class StageTimer {
    public:
     explicit StageTimer(hipStream_t stream);
+    StageTimer() : stream_(nullptr), slot_(-1) {}  // never records
     void begin(int stage);  // record the start event of `stage`
     void end(int stage);    // record its stop event
 
@@ -93,5 +94,9 @@ size_t module_backward_workspace(const fipa_desc &d, int d_s);
 hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, const ModuleBwdArgs &g, void *ws,
                            hipStream_t stream);
 hipError_t bf16_backward(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream);
+// bf16_backward in two calls on one workspace: `begin` runs the forward part and also writes the
+// core's outputs f.o, f.o_pts, f.o_pair; `finish` takes the upstream gradients.
+hipError_t bf16_backward_begin(const fipa_desc &d, const FwdArgs &f, void *ws, hipStream_t stream);
+hipError_t bf16_backward_finish(const fipa_desc &d, const BwdArgs &a, void *ws, hipStream_t stream);
 
 }  // namespace fipa

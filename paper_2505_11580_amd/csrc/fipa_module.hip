@@ -606,7 +606,9 @@ hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, con
     FwdArgs f{base + w.f.q, base + w.f.k, base + w.f.v, base + w.f.q_pts, base + w.f.k_pts, base + w.f.v_pts,
               a.rot, a.trans, a.z1, a.z2, a.w_b, a.gamma, a.mask,
               (float *)(base + w.f.o), (float *)(base + w.f.o_pts), (float *)(base + w.f.o_pair), nullptr};
-    FIPA_TRY(bf16_forward(d, f, base + w.f.core, stream));
+    // (the forward part of the core's backward, which leaves O^ and the log-sum-exp for the gradient
+    // kernels, also gives the core's outputs: no separate forward call)
+    FIPA_TRY(bf16_backward_begin(d, f, base + w.f.core, stream));
 
     // ---- through Eq. 5: d cat = d s_out W_out; d W_out = d s_out^T cat; d b_out = column sums ----------
     bf16_t *g16 = (bf16_t *)(base + w.g16), *gT = (bf16_t *)(base + w.gT);
@@ -643,7 +645,7 @@ hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, con
     b.d_q = base + w.dq; b.d_k = base + w.dk; b.d_v = base + w.dv;
     b.d_q_pts = base + w.dq_pts; b.d_k_pts = base + w.dk_pts; b.d_v_pts = base + w.dv_pts;
     b.d_z1 = g.d_z1; b.d_z2 = g.d_z2; b.d_gamma = g.d_gamma; b.d_w_b = g.d_w_b; b.d_rot = g.d_rot; b.d_trans = g.d_trans;
-    FIPA_TRY(bf16_backward(d, b, base + w.f.core, stream));
+    FIPA_TRY(bf16_backward_finish(d, b, base + w.f.core, stream));
 
     // ---- through Eq. 1: d s = dX W_in; d W_in = dX^T s; d b_in = column sums of dX ---------------------
     GemmParams gx = {};
