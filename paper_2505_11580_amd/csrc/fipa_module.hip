@@ -79,13 +79,15 @@ __device__ __forceinline__ bf16x8 concat_chunk(const GemmParams &p, int row, int
 // Four waves arranged WM x WN, each computing (32 MTW) x (32 NTW) outputs; K in chunks of 64
 // staged through LDS in two buffers (the next chunk is fetched into registers while the current
 // one is multiplied; one barrier per chunk).  The products are computed transposed,
-// C^T = W A^T (MFMA rows = output features, lanes = rows of A), so that a lane ends up with
-// runs of four consecutive output features of one row: 16-byte stores.
-// At the sizes of this module (a few GFLOP, K = 256 or about 2000) the products are bound by the
-// chain of dependent memory round trips of each workgroup, not by the matrix pipe: 64 x 64
-// tiles, which give one workgroup per compute unit at B*L = 4096 rows, measured fastest (14 and
-// 28 microseconds); 128 x 128 or 32 x 256 tiles read less through L2 but leave fewer, longer
-// chains (18 and 35), 32 x 64 tiles with 256-wide K chunks become bound by L2 re-reads (19 and 35).
+// C^T = W A^T (MFMA rows = output features, lanes = rows of A); the finished tile leaves through
+// LDS (see the end of the kernel).
+// At the sizes of this module (a few GFLOP, K = 256 or about 2000) the matrix pipe is idle most
+// of the time.  Measured at B*L = 4096 rows, d_s = 256 (input / output projection, microseconds):
+// 64 x 64 tiles 10.8 / 28; 128 x 128 or 32 x 256 tiles read less through L2 but leave fewer,
+// longer chains of round trips (18 / 35 with the earlier store path); 64 x 64 tiles with 256-wide
+// K chunks, a quarter of the round trips, are 15 % slower; with loads, MFMAs and stores all taken
+// out the input projection still takes 5.  The output projection uses 64 x 128 tiles with K split
+// (see OutTile).
 constexpr int kGK = 64;               // K chunk
 constexpr int kGRS = kGK * 2 + 16;    // LDS row stride in bytes (conflict free for 16-byte row reads)
 
