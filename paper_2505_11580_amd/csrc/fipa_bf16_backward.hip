@@ -5,7 +5,7 @@
 // Chain: forward pack -> forward attention (unfused, gives O^ and the log-sum-exp) -> lift the
 // upstream gradients (dO^ = [d_o | R_i d_o_pts in the hi and lo columns | z1 (.) d_o_pair],
 // D_i = dO^_i . O^_i) -> dQ^, dK^, dV^ (MFMA kernels) -> unpack.
-#include "fipa_bf16_common.h"
+#include "fipa_gfx950.h"
 
 namespace fipa {
 
@@ -187,22 +187,47 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
         if (tid < 9) p.d_rot[((size_t)b * p.L + i) * 9 + tid] = valid ? fsm[3 + tid][0] : 0.f;
     }
 
-    // pair factors: sums over heads
-    for (int x = tid; x < p.DZ; x += 256) {
-        const int d = x % p.cz;
-        float s1 = 0.f, s2 = 0.f;
-#pragma unroll 4  // (four heads' loads in flight; the sums still run in head order)
-        for (int h = 0; h < p.H; ++h) {
+    // pair factors: sums over heads.  A thread takes four neighbouring lifted columns (16-byte loads
+    // of the four big arrays) and every kHG-th head; the partial sums of the kHG head groups meet in
+    // LDS and are added in a fixed order.
+    {
+        __shared__ float zsm[2][1024];  // [z1 | z2][head group][DZ], (256 / (DZ / 4)) * DZ = 1024 entries
+        const int NG = p.DZ / 4, HG = 256 / NG;  // DZ is 32, 64, 128 or 256
+        const int grp = tid % NG, hg = tid / NG, x0 = 4 * grp;
+        f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+        for (int h = hg; h < p.H; h += HG) {
             const size_t bh = (size_t)b * p.H + h;
-            const size_t row = (bh * p.Lp + i) * D + kDH + x;
+            const size_t row = (bh * p.Lp + i) * D + kDH + x0;
             const size_t rec = ((size_t)b * p.L + i) * p.H + h;
-            // z1: through the bias vector b^{h1} = w_L w_b z1, and through o~ = z1^T U
-            s1 += p.w_L * p.w_b[(size_t)h * p.cz + d] * p.dQhat[row] + p.d_o_pair[rec * p.cz + d] * p.Ohat[row];
-            // z2: as key feature (the log2e sits on the query side) and as value feature
-            s2 += kLn2 * p.dKhat[row] + p.dVhat[row];
+            const f32x4 dq = *reinterpret_cast<const f32x4 *>(p.dQhat + row);
+            const f32x4 dk = *reinterpret_cast<const f32x4 *>(p.dKhat + row);
+            const f32x4 dv = *reinterpret_cast<const f32x4 *>(p.dVhat + row);
+            const f32x4 oh = *reinterpret_cast<const f32x4 *>(p.Ohat + row);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int d = (x0 + e) % p.cz;
+                // z1: through the bias vector b^{h1} = w_L w_b z1, and through o~ = z1^T U
+                s1[e] += p.w_L * p.w_b[(size_t)h * p.cz + d] * dq[e] + p.d_o_pair[rec * p.cz + d] * oh[e];
+                // z2: as key feature (the log2e sits on the query side) and as value feature
+                s2[e] += kLn2 * dk[e] + dv[e];
+            }
         }
-        p.d_z1[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? s1 : 0.f);
-        p.d_z2[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? s2 : 0.f);
+        __syncthreads();  // (zsm is free: nothing above uses it)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            zsm[0][hg * p.DZ + x0 + e] = s1[e];
+            zsm[1][hg * p.DZ + x0 + e] = s2[e];
+        }
+        __syncthreads();
+        for (int x = tid; x < p.DZ; x += 256) {
+            float t1 = 0.f, t2 = 0.f;
+            for (int g = 0; g < HG; ++g) {
+                t1 += zsm[0][g * p.DZ + x];
+                t2 += zsm[1][g * p.DZ + x];
+            }
+            p.d_z1[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? t1 : 0.f);
+            p.d_z2[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? t2 : 0.f);
+        }
     }
 }
 
