@@ -37,6 +37,9 @@ def test_module_small_shapes():
     check_module(wl.make_module_inputs(1, d_s=48, B=2, L=200, H=4), "module L=200 d_s=48")
     check_module(wl.make_module_inputs(1, d_s=256, B=1, L=130, H=12, trans_scale=0.1), "module spread L=130 H=12")
     check_module(wl.make_module_inputs(1, d_s=64, B=1, L=96, H=2, cz=32, r=2), "module H=2 cz=32")
+    # three query points: the point tensors of Eq. 1's result start at columns that are no multiples
+    # of 8 and the result is 180 wide (pieces of an output row that straddle two tensors or its end)
+    check_module(wl.make_module_inputs(1, d_s=64, B=1, L=70, H=2, Pq=3), "module Pq=3")
 
 
 def test_module_masked_rows_receive_the_bias():
