@@ -101,6 +101,31 @@ int fipa_forward(const fipa_desc *desc,
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Forward on a packed batch of chains of different lengths (the variable-length inputs of the
+ * experiments in Section 3, without padding): the tensors of fipa_forward with the leading
+ * [B, L] replaced by [total], total = cu_seqlens[B], chain b occupying rows cu_seqlens[b] ..
+ * cu_seqlens[b+1] - 1; residues attend within their chain only.
+ *   desc->B          number of chains;  desc->L  an upper bound of the chain lengths (sizes the
+ *                    workspace: that of fipa_workspace_bytes for B = 1 and this L)
+ *   cu_seqlens       HOST pointer, B + 1 int32, cu_seqlens[0] = 0, non-decreasing; a chain may be
+ *                    empty; a chain longer than desc->L is FIPA_ERR_INVALID_ARG
+ *   mask             [total] bytes or NULL
+ *   lse              [H * total] float32 or NULL: chain b's block [H, len_b] starts at
+ *                    H * cu_seqlens[b]
+ * The chains are enqueued one after the other on the caller's stream (the kernels of
+ * fipa_forward with B = 1 on offset pointers, sharing the workspace), so short chains fill the
+ * chip less well than a padded batch of them would; nothing is computed for padding.
+ */
+int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens,
+                        const void *q, const void *k, const void *v,
+                        const void *q_pts, const void *k_pts, const void *v_pts,
+                        const float *rot, const float *trans,
+                        const void *z1, const void *z2,
+                        const float *w_b, const float *gamma, const uint8_t *mask,
+                        float *o, float *o_pts, float *o_pair, float *lse,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three
  * point sets, z1, z2 (same shapes and dtype as the inputs), gamma ([H], float32) and, when the
  * pointers are not NULL, the pair-bias weights w_b (d_w_b [H, cz], float32) and the frames

@@ -68,6 +68,24 @@ def test_forward_argument_checks_need_no_device():
         binding.workspace_bytes(binding.make_desc(1, -5, 4, 16, 4, 8, 16, 2, 0))
 
 
+def test_packed_forward_argument_checks_need_no_device():
+    lib = binding.lib()
+    d = binding.make_desc(3, 64, 4, 16, 4, 8, 16, 2, binding.FIPA_DTYPE_BF16)
+    fake = [ctypes.c_void_p(0x1000)] * 17
+    ws = ctypes.c_void_p(0x1000)
+
+    def call(cu, size=1 << 30):
+        arr = (ctypes.c_int32 * len(cu))(*cu)
+        return lib.fipa_forward_packed(ctypes.byref(d), arr, *fake, ws, size, None)
+
+    assert lib.fipa_forward_packed(ctypes.byref(d), None, *fake, ws, 1 << 30, None) == binding.FIPA_ERR_INVALID_ARG
+    assert call([1, 10, 20, 30]) == binding.FIPA_ERR_INVALID_ARG      # does not start at 0
+    assert call([0, 10, 5, 30]) == binding.FIPA_ERR_INVALID_ARG       # decreasing
+    assert call([0, 10, 80, 90]) == binding.FIPA_ERR_INVALID_ARG      # a chain longer than desc->L
+    assert call([0, 10, 20, 30], size=0) == binding.FIPA_ERR_WORKSPACE
+    assert call([0, 0, 0, 0]) == binding.FIPA_OK                      # only empty chains: nothing to enqueue
+
+
 def test_stage_timer_argument_checks_need_no_device():
     lib = binding.lib()
     assert lib.fipa_profile_begin_every(10, 0) == binding.FIPA_ERR_INVALID_ARG
