@@ -433,7 +433,8 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         part = lin - tile_local * nparts;
         logical = p.plan.full + tile_local;
     }
-    const int bh = logical / p.nQT, qt = logical - bh * p.nQT;
+    const int bh_pos = logical / p.nQT, qt = logical - bh_pos * p.nQT;
+    const int bh = p.deal ? dealt_pair_by_length(bh_pos, p.kvlen, p.B, p.H, threadIdx.x & 63) : bh_pos;
     const int b = bh / p.H;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

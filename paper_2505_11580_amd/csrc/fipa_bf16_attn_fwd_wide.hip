@@ -292,7 +292,8 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
     const int logical = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
     if (logical >= p.total_tiles) return;
     const int win = blockIdx.y;
-    const int bh = logical / p.nQT, qt = logical - bh * p.nQT;
+    const int bh_pos = logical / p.nQT, qt = logical - bh_pos * p.nQT;
+    const int bh = p.deal ? dealt_pair_by_length(bh_pos, p.kvlen, p.B, p.H, threadIdx.x & 63) : bh_pos;
     const int b = bh / p.H;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -401,6 +401,7 @@ hipError_t backward_forward_part(const fipa_desc &d, const FwdArgs &f, const Bwd
     at.B = d.B; at.L = d.L; at.Lp = w.f.Lp; at.H = d.H; at.NT = w.f.NT;
     at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = f.w_b; at.w_L = d.w_L;
     at.plan = w.f.plan; at.partial = nullptr; at.counters = nullptr;  // (unfused: never split)
+    at.deal = f.mask != nullptr;
     e = launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
     if (e != hipSuccess || !f.o) return e;
 
@@ -439,6 +440,7 @@ hipError_t backward_gradient_part(const fipa_desc &d, const BwdArgs &a, const Bw
     bw.Qh = pk.Qh; bw.Qz = pk.Qz; bw.Kh = pk.Kh; bw.Vh = pk.Vh; bw.Z2 = pk.Z2; bw.dOhat = bp.dOhat;
     bw.kbias = pk.kbias; bw.nlse = bp.nlse; bw.Dvec = bp.Dvec; bw.kvlen = kvlen;
     bw.B = d.B; bw.Lp = w.f.Lp; bw.H = d.H; bw.total_tiles = (w.f.Lp / kTileQ) * d.B * d.H;
+    bw.deal = a.f.mask != nullptr;
     bw.out = (float *)(base + w.dQhat); bw.wsum = (float *)(base + w.rowsum);
     e = launch_bwd_bf16(bw, w.f.DZ, FIPA_BWD_DQ, stream);
     if (e != hipSuccess) return e;

@@ -335,7 +335,8 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     const int logical = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
     if (logical >= p.total_tiles) return;
     const int nT = p.Lp / kTileQ;
-    const int bh = logical / nT, tile = logical - bh * nT;
+    const int bh_pos = logical / nT, tile = logical - bh_pos * nT;
+    const int bh = p.deal ? dealt_pair_by_length(bh_pos, p.kvlen, p.B, p.H, threadIdx.x & 63) : bh_pos;
     const int b = bh / p.H;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

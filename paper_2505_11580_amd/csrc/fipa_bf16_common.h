@@ -88,6 +88,46 @@ inline SplitPlan attn_split_plan(int total_tiles, int Lp, int DZ, int cz, bool f
     return s;
 }
 
+// The MFMA kernels give each XCD a contiguous run of work units, so that the tiles of one
+// (batch, head) pair share that XCD's L2.  In launch order the pairs of one batch element are
+// neighbours, and with chains of different lengths (a masked batch) whole XCDs would get only
+// long or only short chains (lengths 5.8k, 7.5k, 7.5k, 1.6k at H = 12: four XCDs with 1.5 times
+// the mean work, two with almost none).  deal_pair() renumbers the pairs so that position
+// `pos` of the contiguous order holds pair x, x + 8, x + 16, ... for the x-th run: every XCD
+// gets pairs of every batch element.  A bijection on [0, P) for any P.
+__device__ __forceinline__ int deal_pair(int pos, int P)
+{
+    int x = 0;
+    for (; x < 7; ++x) {
+        const int n = (P - x + 7) / 8;  // pairs with index = x (mod 8)
+        if (pos < n) break;
+        pos -= n;
+    }
+    return x + 8 * pos;
+}
+
+// The pair that a masked batch's position `pos` of the contiguous order works on: the batch
+// elements are ranked by descending chain length (kvlen; ties by index), their pairs listed in
+// that order and dealt to the XCDs with deal_pair(), so that every XCD starts with its longest
+// chains and ends with its shortest (a workgroup's run time is proportional to the length of its
+// chain; the other way round the last, long workgroups run while most compute units are idle).
+// Every lane of the wave calls it and gets the same answer.  More than 64 batch elements: no ranking.
+__device__ __forceinline__ int dealt_pair_by_length(int pos, const int *kvlen, int B, int H, int lane)
+{
+    const int pi = deal_pair(pos, B * H);
+    const int rb = pi / H, h = pi - rb * H;
+    if (B > 64) return pi;
+    const int mine = lane < B ? kvlen[lane] : -1;
+    int rank = 0;
+    for (int j = 0; j < B; ++j) {
+        const int other = __builtin_amdgcn_readlane(mine, j);
+        rank += (other > mine || (other == mine && j < lane)) ? 1 : 0;
+    }
+    const unsigned long long hit = __ballot(lane < B && rank == rb);
+    const int b = __builtin_amdgcn_readfirstlane(__ffsll((long long)hit) - 1);
+    return b * H + h;
+}
+
 // 16-byte groups per lane that one wave of one part leaves for the merge: 2 of scalars, 3 of
 // point coordinates, 1 of (reference maximum, weight sum), 4 per 32-column block of the
 // z1-contracted pair part (c_z / 32 blocks).
@@ -168,6 +208,7 @@ struct AttnParams {
     const uint8_t *mask;
     float *o, *o_pts, *o_pair, *lse;
     int B, L, Lp, H, NT, nQT, total_tiles, cz, r;
+    int deal;  // renumber the (batch, head) pairs with deal_pair(): set for masked batches
     float w_L;
     // key-range split (see SplitPlan): exchange buffer and one arrival counter per (split tile, wave)
     SplitPlan plan;
@@ -195,6 +236,7 @@ struct BwdParams {
     float *out;           // [B,H,Lp,64+DZ] dQ^ / dK^ / dV^
     float *wsum;          // [B,H,Lp] sum of the rounded dS over the streamed side, or NULL
     int B, Lp, H, total_tiles;
+    int deal;     // renumber the (batch, head) pairs with deal_pair(): set for masked batches
 };
 
 struct BwdPackParams {

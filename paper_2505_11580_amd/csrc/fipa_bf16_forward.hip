@@ -55,6 +55,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     at.B = d.B; at.L = d.L; at.Lp = w.Lp; at.H = d.H; at.NT = w.NT;
     at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.w_b; at.w_L = d.w_L;
     at.plan = w.plan; at.partial = (float *)(base + w.partial); at.counters = counters;
+    at.deal = a.mask != nullptr;
     timer.begin(1);
     e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream) : launch_attn_fwd_bf16(at, w.DZ, fused, stream);
     if (e != hipSuccess) return e;
