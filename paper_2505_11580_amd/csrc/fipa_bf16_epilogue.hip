@@ -1,6 +1,6 @@
 // Split of the lifted output, inverse frame on the point part (Eq. 4) and contraction of the
 // pair part with z1 (Algorithm 1 steps 8-9).  Memory bound: one wave per (batch, head, row).
-#include "fipa_bf16_common.h"
+#include "fipa_gfx950.h"
 
 namespace fipa {
 
@@ -20,7 +20,10 @@ __global__ __launch_bounds__(256) void fipa_epilogue_bf16_kernel(EpiParams p)
     const float *oh = p.Ohat + (bh * p.Lp + i) * DV;
     const bool valid = p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true;
 
-    for (int d = lane; d < c; d += 64) p.o[row_id * c + d] = valid ? oh[d] : 0.f;
+    // (c and c_z are multiples of 8 on this path: 16-byte accesses throughout)
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    for (int d = 4 * lane; d < c; d += 256)
+        *reinterpret_cast<f32x4 *>(p.o + row_id * c + d) = valid ? *reinterpret_cast<const f32x4 *>(oh + d) : zero4;
 
     const float *R = p.rot + ((size_t)b * p.L + i) * 9;
     const float *t = p.trans + ((size_t)b * p.L + i) * 3;
@@ -37,12 +40,18 @@ __global__ __launch_bounds__(256) void fipa_epilogue_bf16_kernel(EpiParams p)
     }
 
     const bf16_t *z1 = p.z1 + ((size_t)b * p.L + i) * p.DZ;
-    for (int d = lane; d < p.cz; d += 64) {
-        float val = 0.f;
+    for (int d = 4 * lane; d < p.cz; d += 256) {
+        f32x4 val = zero4;
         if (valid)
-            for (int rho = 0; rho < p.r; ++rho)
-                val += bf2f(z1[rho * p.cz + d]) * oh[kDH + rho * p.cz + d];
-        p.o_pair[row_id * p.cz + d] = val;
+            for (int rho = 0; rho < p.r; ++rho) {
+                const uint2 zr = *reinterpret_cast<const uint2 *>(z1 + rho * p.cz + d);  // four bf16 values
+                const f32x4 u = *reinterpret_cast<const f32x4 *>(oh + kDH + rho * p.cz + d);
+                val[0] += __uint_as_float(zr.x << 16) * u[0];
+                val[1] += __uint_as_float(zr.x & 0xFFFF0000u) * u[1];
+                val[2] += __uint_as_float(zr.y << 16) * u[2];
+                val[3] += __uint_as_float(zr.y & 0xFFFF0000u) * u[3];
+            }
+        *reinterpret_cast<f32x4 *>(p.o_pair + row_id * p.cz + d) = val;
     }
 
     // natural log-sum-exp of Eq. 3's argument: undo the log2 scaling and put back the
