@@ -63,6 +63,11 @@ def test_backward_masked():
             assert np.all(got[n][b, int(ln):] == 0), (n, b)
 
 
+def test_backward_masked_odd_pair_count():
+    # 5 x 3 = 15 (batch, head) pairs, ragged: the gradient kernels renumber the pairs of a masked batch
+    check_backward(wl.make_inputs(4, B=5, L=140, H=3, cz=32, varlen=True, min_len=10, trans_scale=0.5), "bwd varlen B=5 H=3")
+
+
 def test_backward_full_size_properties():
     # workload 4 at full size (B=2, L=4096): the oracle cannot sweep it; check properties that hold
     # at any size: finite, linear in the upstream gradient, and local-frame gradients unchanged

@@ -230,3 +230,13 @@ def test_packed_batch_matches_the_padded_oracle(cfg, kw):
     for b, ln in enumerate(lengths):
         blk = got["lse"][H * cu[b]:H * cu[b + 1]].reshape(H, ln)
         assert np.allclose(blk, padded["lse"][b, :, :ln], rtol=0, atol=2e-2 if inp["dtype"] == "bf16" else 1e-4), b
+
+
+@pytest.mark.parametrize("B,H,L", [(5, 3, 200), (66, 1, 128), (9, 2, 130)])
+def test_masked_batches_with_odd_pair_counts(B, H, L):
+    # masked batches renumber their (batch, head) pairs (ranked by chain length, dealt to the XCDs);
+    # pair counts that are no multiples of 8, more batch elements than a wave has lanes, equal lengths
+    inp = wl.make_inputs(1, B=B, H=H, L=L, varlen=True, min_len=3, cz=32)
+    gu.check(inp, label="bf16 masked B=%d H=%d L=%d" % (B, H, L))
+    inp = wl.make_inputs(1, B=B, H=H, L=L, varlen=True, min_len=L, cz=32)   # a mask, all chains full length
+    gu.check(inp, label="bf16 masked, equal lengths B=%d H=%d" % (B, H))
