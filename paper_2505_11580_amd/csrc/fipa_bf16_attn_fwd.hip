@@ -439,7 +439,8 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, g = lane >> 5;
-    const int kvlen = p.kvlen[b];
+    // (without a mask every chain has L residues: no dependent load in front of everything else)
+    const int kvlen = p.deal ? p.kvlen[b] : p.L;
     const int nkb = (kvlen + kBlk - 1) / kBlk;      // key blocks of this chain
     const int irow = qt * kTileQ + wave * 32 + li;  // < Lp always
 

@@ -298,7 +298,7 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, g = lane >> 5;
-    const int kvlen = p.kvlen[b];
+    const int kvlen = p.deal ? p.kvlen[b] : p.L;  // (no mask: every chain has L residues)
     const int nblk = (kvlen + kKB - 1) / kKB;
     const int irow = qt * kTileQ + wave * 32 + li;
 

@@ -439,7 +439,7 @@ hipError_t backward_gradient_part(const fipa_desc &d, const BwdArgs &a, const Bw
     BwdParams bw;
     bw.Qh = pk.Qh; bw.Qz = pk.Qz; bw.Kh = pk.Kh; bw.Vh = pk.Vh; bw.Z2 = pk.Z2; bw.dOhat = bp.dOhat;
     bw.kbias = pk.kbias; bw.nlse = bp.nlse; bw.Dvec = bp.Dvec; bw.kvlen = kvlen;
-    bw.B = d.B; bw.Lp = w.f.Lp; bw.H = d.H; bw.total_tiles = (w.f.Lp / kTileQ) * d.B * d.H;
+    bw.B = d.B; bw.L = d.L; bw.Lp = w.f.Lp; bw.H = d.H; bw.total_tiles = (w.f.Lp / kTileQ) * d.B * d.H;
     bw.deal = a.f.mask != nullptr;
     bw.out = (float *)(base + w.dQhat); bw.wsum = (float *)(base + w.rowsum);
     e = launch_bwd_bf16(bw, w.f.DZ, FIPA_BWD_DQ, stream);

@@ -341,7 +341,7 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, g = lane >> 5;
-    const int kvlen = p.kvlen[b];
+    const int kvlen = p.deal ? p.kvlen[b] : p.L;  // (no mask: every chain has L residues)
     const int nblk = (kvlen + kSB - 1) / kSB;       // streamed blocks: residues past the last valid one contribute nothing
     const int srow = tile * kTileQ + wave * 32 + li;  // stationary row of this lane, < Lp
 

@@ -208,7 +208,7 @@ struct AttnParams {
     const uint8_t *mask;
     float *o, *o_pts, *o_pair, *lse;
     int B, L, Lp, H, NT, nQT, total_tiles, cz, r;
-    int deal;  // renumber the (batch, head) pairs with deal_pair(): set for masked batches
+    int deal;  // set for masked batches: chain lengths come from kvlen, and the (batch, head) pairs are renumbered (see dealt_pair_by_length)
     float w_L;
     // key-range split (see SplitPlan): exchange buffer and one arrival counter per (split tile, wave)
     SplitPlan plan;
@@ -235,8 +235,8 @@ struct BwdParams {
     const int *kvlen;
     float *out;           // [B,H,Lp,64+DZ] dQ^ / dK^ / dV^
     float *wsum;          // [B,H,Lp] sum of the rounded dS over the streamed side, or NULL
-    int B, Lp, H, total_tiles;
-    int deal;     // renumber the (batch, head) pairs with deal_pair(): set for masked batches
+    int B, L, Lp, H, total_tiles;
+    int deal;     // set for masked batches: chain lengths come from kvlen, and the (batch, head) pairs are renumbered (see dealt_pair_by_length)
 };
 
 struct BwdPackParams {
