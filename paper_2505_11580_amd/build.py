@@ -16,16 +16,19 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
-# Per-file additions.  The forward attention kernels are compiled with the MFMA results selected
-# in the general vector-register class, so that the register allocator decides per value between
-# architectural and accumulation registers: the S^T accumulator, which the softmax reads right
-# away, then needs no copies out of accumulation registers (16 per key block), and the rare
-# rescaling of the output accumulator works in place (a third of the instructions).  Measured:
-# -3.5 % on the fused attention at B=2, L=2048, -2.7 % on the rank-4 kernel; the gradient kernels
-# get 1.6 % slower with it and stay as they are.
+# Per-file additions.  The MFMA kernels are compiled with the MFMA results selected in the general
+# vector-register class, so that the register allocator decides per value between architectural
+# and accumulation registers: accumulators that the vector ALU reads (S^T, dP, the output
+# accumulator when it is rescaled) then need no copies out of accumulation registers, while the
+# stationary fragments are pinned to accumulation registers in the source.  Measured against
+# the default (every MFMA result in accumulation registers): fused attention -3.5 % at B=2,
+# L=2048, rank-4 kernel -2.7 %, gradient kernels -4 / -6 / -10 % (dV^, dQ^, dK^; without the pins
+# they got 1.6 % slower).
+_VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
 PER_FILE = {
-    "fipa_bf16_attn_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
-    "fipa_bf16_attn_fwd_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "fipa_bf16_attn_fwd.hip": _VGPR_FORM,
+    "fipa_bf16_attn_fwd_wide.hip": _VGPR_FORM,
+    "fipa_bf16_bwd_kernel.hip": _VGPR_FORM,
 }
 
 

@@ -426,6 +426,15 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
             y2f[ks] = *reinterpret_cast<const bf16x8 *>(s2);
         }
     }
+    // The stationary fragments go to accumulation registers, from where the MFMAs read their B
+    // operand directly; the accumulators and the small products, which the vector ALU works on,
+    // are left to the register allocator (this file is compiled with the MFMA results in the
+    // general vector-register class: see build.py).
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) {
+        asm volatile("" : "+a"(y1f[ks]));
+        if (kNeedDP) asm volatile("" : "+a"(y2f[ks]));
+    }
     const float slane = slane_src[srow];
     const float dlane = dlane_src ? dlane_src[srow] : 0.f;
 
