@@ -158,6 +158,12 @@ __device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, con
     constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
     constexpr int kEntries = C::NIW + C::NSC;
     constexpr int kLA = 3, kRing = 4;
+    // The load entries of the next block go out with the first kDmaSteps k-steps.  The block has
+    // to have landed when the next step begins (three stages: one block of lead), so entries
+    // issued late in the step are waited for; spread over all k-steps the last ones were.  In the
+    // first quarter: dV^ -6 %, dQ^ -2 %; dK^, whose step is the longest, is 4 % slower that way
+    // and keeps the even spread.
+    constexpr int kDmaSteps = MODE == FIPA_BWD_DK ? C::KS : (C::KS >= 4 ? C::KS / 4 : 1);
     auto fetch = [&](auto J) -> bf16x8 {
         constexpr auto o = O::op(decltype(J)::value);
         if constexpr (o.kind == 0) {
@@ -224,8 +230,8 @@ __device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, con
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], y1f[o.idx], sacc, 0, 0, 0);
             if (next_stage != 0xFFFFFFFFu) {
 #pragma unroll
-                for (int e = o.idx * kEntries / C::KS; e < (o.idx + 1) * kEntries / C::KS; ++e)
-                    bwd_issue_entry<DZ, MODE>(dma, next_stage, e);
+                for (int e = o.idx * kEntries / kDmaSteps; e < (o.idx + 1) * kEntries / kDmaSteps; ++e)
+                    if (e < kEntries) bwd_issue_entry<DZ, MODE>(dma, next_stage, e);
             }
         } else if constexpr (o.kind == 1) {
             dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], y2f[kNeedDP ? o.idx : 0], dpacc, 0, 0, 0);
