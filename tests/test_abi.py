@@ -92,3 +92,14 @@ def test_stage_timer_argument_checks_need_no_device():
     assert lib.fipa_profile_begin_every(0, 1) == binding.FIPA_ERR_INVALID_ARG
     assert lib.fipa_profile_begin_every(5000, 1) == binding.FIPA_ERR_INVALID_ARG
     assert lib.fipa_profile_end(None, None) == binding.FIPA_ERR_INVALID_ARG  # timing is not active
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU only: the benchmark says so instead of running on a subset
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2
+    assert "single-GPU" in res.stderr
