@@ -131,8 +131,9 @@ int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens,
  * pointers are not NULL, the pair-bias weights w_b (d_w_b [H, cz], float32) and the frames
  * (d_rot [B, L, 3, 3] and d_trans [B, L, 3], float32, both or neither; every entry of R_i is
  * taken as a free variable of R_i x + t_i in Eq. 3 and of R_i^T (. - t_i) in Eq. 4), given
- * the upstream gradients d_o, d_o_pts, d_o_pair (float32, shapes of o, o_pts, o_pair) and
- * the forward results o, o_pts, o_pair, lse.
+ * the upstream gradients d_o, d_o_pts, d_o_pair (float32, shapes of o, o_pts, o_pair).
+ * The forward results o, o_pts, o_pair, lse are accepted for callers that keep them but are not
+ * read (the attention weights and outputs are recomputed from the inputs); each may be NULL.
  * d_gamma, d_w_b, d_rot and d_trans are overwritten (not accumulated).  The paper gives no backward; it is the chain
  * rule through Eqs. 3-4 and z_ij = z1_i^T z2_j.
  * Supported for FIPA_DTYPE_BF16 with r*cz <= 256; otherwise FIPA_ERR_UNSUPPORTED.

@@ -404,3 +404,229 @@ void ipa_oracle_pair_backward(int L, int r, int cz, const double *z1, const doub
                     dz2[((size_t)j * r + rho) * cz + d] += g * z1[((size_t)i * r + rho) * cz + d];
                 }
 }
+
+/*
+ * Backward for sizes where the dense pair tensor does not fit: the same chain rule as
+ * ipa_oracle_backward (Eq. 4 -> softmax -> Eq. 3 -> z_ij = z1_i^T z2_j of Section 2.4), walked
+ * one query row at a time with that row's z_i [L, cz] formed on the spot from the factors
+ * z1, z2 [L, r, cz].  Every query row is visited (the key-side gradients and the parameter
+ * gradients are sums over all of them), but only the gradients of the n_s sampled residues
+ * S[0..n_s) are kept; entry a of an output belongs to residue S[a]:
+ *   dq, dk, dv [n_s,H,c]; dq_pts, dk_pts [n_s,H,Pq,3]; dv_pts [n_s,H,Pv,3];
+ *   dz1, dz2 [n_s,r,cz]; drot [n_s,3,3]; dtrans [n_s,3]   (a residue's frame gradient needs both
+ *   of its roles, as query row and as key column)
+ * and in full dgamma [H], dw_b [H,cz].
+ * Pinned by equality with ipa_oracle_backward + ipa_oracle_pair_backward at small L.
+ * Rows are spread over threads; each thread sums into its own copy of the outputs and the
+ * copies are added in thread order at the end.
+ */
+int ipa_oracle_backward_sampled(int L, int H, int c, int Pq, int Pv, int cz, int r,
+                                const double *q, const double *k, const double *v,
+                                const double *q_pts, const double *k_pts, const double *v_pts,
+                                const double *rot, const double *trans,
+                                const double *z1, const double *z2,
+                                const double *w_b, const double *gamma, double w_L, double w_C,
+                                const uint8_t *mask,
+                                const double *d_o, const double *d_o_pts, const double *d_o_pair,
+                                int n_s, const int32_t *S,
+                                double *dq, double *dk, double *dv,
+                                double *dq_pts, double *dk_pts, double *dv_pts,
+                                double *dz1, double *dz2, double *drot, double *dtrans,
+                                double *dgamma, double *dw_b)
+{
+    /* one flat buffer per thread holding all twelve outputs */
+    const size_t n_sc = (size_t)n_s * H * c, n_qp = (size_t)n_s * H * Pq * 3, n_vp = (size_t)n_s * H * Pv * 3,
+                 n_zf = (size_t)n_s * r * cz;
+    const size_t o_dq = 0, o_dk = o_dq + n_sc, o_dv = o_dk + n_sc, o_dqp = o_dv + n_sc, o_dkp = o_dqp + n_qp,
+                 o_dvp = o_dkp + n_qp, o_dz1 = o_dvp + n_vp, o_dz2 = o_dz1 + n_zf, o_drot = o_dz2 + n_zf,
+                 o_dtr = o_drot + (size_t)n_s * 9, o_dg = o_dtr + (size_t)n_s * 3, o_dwb = o_dg + (size_t)H,
+                 n_all = o_dwb + (size_t)H * cz;
+    int *slot = (int *)malloc(sizeof(int) * (size_t)L); /* residue -> index in S, or -1 */
+    for (int i = 0; i < L; ++i)
+        slot[i] = -1;
+    for (int a = 0; a < n_s; ++a)
+        slot[S[a]] = a;
+    const int nt = ipa_oracle_num_threads();
+    double *all = (double *)calloc(n_all * (size_t)nt, sizeof(double));
+
+#pragma omp parallel num_threads(nt)
+    {
+#ifdef _OPENMP
+        double *acc = all + n_all * (size_t)omp_get_thread_num();
+#else
+        double *acc = all;
+#endif
+        double *z_i = (double *)malloc(sizeof(double) * (size_t)L * cz);
+        double *dz_i = (double *)malloc(sizeof(double) * (size_t)L * cz);
+        double *s = (double *)malloc(sizeof(double) * (size_t)L);
+        double *a = (double *)malloc(sizeof(double) * (size_t)L);
+        double *D = (double *)malloc(sizeof(double) * (size_t)L);
+        double *da = (double *)malloc(sizeof(double) * (size_t)L);
+        double *dG = (double *)malloc(sizeof(double) * (size_t)Pv * 3);
+        double *Gacc = (double *)malloc(sizeof(double) * (size_t)Pv * 3);
+#pragma omp for schedule(static)
+        for (int i = 0; i < L; ++i) {
+            if (mask && !mask[i])
+                continue;
+            const int ai = slot[i];
+            /* z_i[j, d] = sum_rho z1_i[rho, d] z2_j[rho, d]   (Section 2.4) */
+            for (int j = 0; j < L; ++j)
+                for (int d = 0; d < cz; ++d) {
+                    double zz = 0.0;
+                    for (int rho = 0; rho < r; ++rho)
+                        zz += z1[((size_t)i * r + rho) * cz + d] * z2[((size_t)j * r + rho) * cz + d];
+                    z_i[(size_t)j * cz + d] = zz;
+                    dz_i[(size_t)j * cz + d] = 0.0;
+                }
+            for (int h = 0; h < H; ++h) {
+                logits_row(L, H, c, Pq, cz, i, h, q, k, q_pts, k_pts, rot, trans, z_i, w_b, gamma, w_L, w_C, s, D);
+                softmax_row(L, mask, s, a);
+                const double *go = d_o + ((size_t)i * H + h) * c;
+                const double *gp = d_o_pts + ((size_t)i * H + h) * Pv * 3;
+                const double *gz = d_o_pair + ((size_t)i * H + h) * cz;
+                for (int p = 0; p < Pv; ++p)
+                    rot_apply(rot + 9 * (size_t)i, gp + 3 * p, dG + 3 * p);
+                for (int x = 0; x < 3 * Pv; ++x)
+                    Gacc[x] = 0.0;
+                /* Eq. 4: derivative with respect to the weights (da) and to the values of key j */
+                double dot = 0.0;
+                for (int j = 0; j < L; ++j) {
+                    const int aj = slot[j];
+                    double g = 0.0;
+                    for (int d = 0; d < c; ++d)
+                        g += go[d] * v[((size_t)j * H + h) * c + d];
+                    for (int d = 0; d < cz; ++d) {
+                        g += gz[d] * z_i[(size_t)j * cz + d];
+                        dz_i[(size_t)j * cz + d] += a[j] * gz[d];
+                    }
+                    if (aj >= 0)
+                        for (int d = 0; d < c; ++d)
+                            acc[o_dv + ((size_t)aj * H + h) * c + d] += a[j] * go[d];
+                    for (int p = 0; p < Pv; ++p) {
+                        const double *vl = v_pts + (((size_t)j * H + h) * Pv + p) * 3;
+                        double V[3], aG[3], loc[3];
+                        frame_apply(rot + 9 * (size_t)j, trans + 3 * (size_t)j, vl, V);
+                        for (int x = 0; x < 3; ++x) {
+                            g += dG[3 * p + x] * V[x];
+                            aG[x] = a[j] * dG[3 * p + x];
+                            Gacc[3 * p + x] += a[j] * V[x];
+                        }
+                        if (aj >= 0) {
+                            for (int x = 0; x < 3; ++x) {
+                                acc[o_dtr + 3 * (size_t)aj + x] += aG[x];
+                                for (int y = 0; y < 3; ++y)
+                                    acc[o_drot + 9 * (size_t)aj + 3 * x + y] += aG[x] * vl[y];
+                            }
+                            rot_transpose_apply(rot + 9 * (size_t)j, aG, loc);
+                            for (int x = 0; x < 3; ++x)
+                                acc[o_dvp + (((size_t)aj * H + h) * Pv + p) * 3 + x] += loc[x];
+                        }
+                    }
+                    da[j] = g;
+                    dot += a[j] * g;
+                }
+                if (ai >= 0) /* o_pts = R_i^T (G - t_i) as a function of the frame of i */
+                    for (int p = 0; p < Pv; ++p)
+                        for (int x = 0; x < 3; ++x) {
+                            acc[o_dtr + 3 * (size_t)ai + x] -= dG[3 * p + x];
+                            for (int y = 0; y < 3; ++y)
+                                acc[o_drot + 9 * (size_t)ai + 3 * x + y] +=
+                                    (Gacc[3 * p + x] - trans[3 * (size_t)i + x]) * gp[3 * p + y];
+                        }
+                /* softmax, then Eq. 3 term by term */
+                const double sc = w_L / sqrt((double)c);
+                const double pc = w_L * gamma[h] * w_C;
+                for (int j = 0; j < L; ++j) {
+                    if (mask && !mask[j])
+                        continue;
+                    const int aj = slot[j];
+                    const double ds = a[j] * (da[j] - dot);
+                    if (ai >= 0)
+                        for (int d = 0; d < c; ++d)
+                            acc[o_dq + ((size_t)ai * H + h) * c + d] += ds * sc * k[((size_t)j * H + h) * c + d];
+                    if (aj >= 0)
+                        for (int d = 0; d < c; ++d)
+                            acc[o_dk + ((size_t)aj * H + h) * c + d] += ds * sc * q[((size_t)i * H + h) * c + d];
+                    for (int d = 0; d < cz; ++d) {
+                        dz_i[(size_t)j * cz + d] += ds * w_L * w_b[(size_t)h * cz + d];
+                        acc[o_dwb + (size_t)h * cz + d] += ds * w_L * z_i[(size_t)j * cz + d];
+                    }
+                    acc[o_dg + h] += ds * (-w_L * w_C / 2.0) * D[j];
+                    if (ai < 0 && aj < 0)
+                        continue;
+                    for (int p = 0; p < Pq; ++p) {
+                        const double *ql = q_pts + (((size_t)i * H + h) * Pq + p) * 3;
+                        const double *kl = k_pts + (((size_t)j * H + h) * Pq + p) * 3;
+                        double Qg[3], Kg[3], gQ[3], gK[3], loc[3];
+                        frame_apply(rot + 9 * (size_t)i, trans + 3 * (size_t)i, ql, Qg);
+                        frame_apply(rot + 9 * (size_t)j, trans + 3 * (size_t)j, kl, Kg);
+                        for (int x = 0; x < 3; ++x) {
+                            gQ[x] = -ds * pc * (Qg[x] - Kg[x]);
+                            gK[x] = ds * pc * (Qg[x] - Kg[x]);
+                        }
+                        if (ai >= 0) {
+                            for (int x = 0; x < 3; ++x) {
+                                acc[o_dtr + 3 * (size_t)ai + x] += gQ[x];
+                                for (int y = 0; y < 3; ++y)
+                                    acc[o_drot + 9 * (size_t)ai + 3 * x + y] += gQ[x] * ql[y];
+                            }
+                            rot_transpose_apply(rot + 9 * (size_t)i, gQ, loc);
+                            for (int x = 0; x < 3; ++x)
+                                acc[o_dqp + (((size_t)ai * H + h) * Pq + p) * 3 + x] += loc[x];
+                        }
+                        if (aj >= 0) {
+                            for (int x = 0; x < 3; ++x) {
+                                acc[o_dtr + 3 * (size_t)aj + x] += gK[x];
+                                for (int y = 0; y < 3; ++y)
+                                    acc[o_drot + 9 * (size_t)aj + 3 * x + y] += gK[x] * kl[y];
+                            }
+                            rot_transpose_apply(rot + 9 * (size_t)j, gK, loc);
+                            for (int x = 0; x < 3; ++x)
+                                acc[o_dkp + (((size_t)aj * H + h) * Pq + p) * 3 + x] += loc[x];
+                        }
+                    }
+                }
+            }
+            /* z_ij = z1_i^T z2_j: the row's dz_i [L, cz] goes to z1_i (if sampled) and to the sampled z2_j */
+            for (int j = 0; j < L; ++j) {
+                const int aj = slot[j];
+                if (ai < 0 && aj < 0)
+                    continue;
+                for (int rho = 0; rho < r; ++rho)
+                    for (int d = 0; d < cz; ++d) {
+                        const double g = dz_i[(size_t)j * cz + d];
+                        if (ai >= 0)
+                            acc[o_dz1 + ((size_t)ai * r + rho) * cz + d] += g * z2[((size_t)j * r + rho) * cz + d];
+                        if (aj >= 0)
+                            acc[o_dz2 + ((size_t)aj * r + rho) * cz + d] += g * z1[((size_t)i * r + rho) * cz + d];
+                    }
+            }
+        }
+        free(z_i);
+        free(dz_i);
+        free(s);
+        free(a);
+        free(D);
+        free(da);
+        free(dG);
+        free(Gacc);
+    }
+    for (int t = 1; t < nt; ++t)
+        for (size_t x = 0; x < n_all; ++x)
+            all[x] += all[n_all * (size_t)t + x];
+    memcpy(dq, all + o_dq, sizeof(double) * n_sc);
+    memcpy(dk, all + o_dk, sizeof(double) * n_sc);
+    memcpy(dv, all + o_dv, sizeof(double) * n_sc);
+    memcpy(dq_pts, all + o_dqp, sizeof(double) * n_qp);
+    memcpy(dk_pts, all + o_dkp, sizeof(double) * n_qp);
+    memcpy(dv_pts, all + o_dvp, sizeof(double) * n_vp);
+    memcpy(dz1, all + o_dz1, sizeof(double) * n_zf);
+    memcpy(dz2, all + o_dz2, sizeof(double) * n_zf);
+    memcpy(drot, all + o_drot, sizeof(double) * (size_t)n_s * 9);
+    memcpy(dtrans, all + o_dtr, sizeof(double) * (size_t)n_s * 3);
+    memcpy(dgamma, all + o_dg, sizeof(double) * (size_t)H);
+    memcpy(dw_b, all + o_dwb, sizeof(double) * (size_t)H * cz);
+    free(all);
+    free(slot);
+    return 0;
+}

@@ -33,6 +33,8 @@ def lib():
         L.ipa_oracle_backward.argtypes = [i] * 6 + [dp] * 11 + [d, d, bp] + [dp] * 3 + [dp] * 11
         L.ipa_oracle_pair_backward.restype = None
         L.ipa_oracle_pair_backward.argtypes = [i, i, i, dp, dp, dp, dp, dp]
+        L.ipa_oracle_backward_sampled.restype = ctypes.c_int
+        L.ipa_oracle_backward_sampled.argtypes = [i] * 7 + [dp] * 12 + [d, d, bp] + [dp] * 3 + [i, ip] + [dp] * 12
         _LIB = L
     return _LIB
 
@@ -170,4 +172,43 @@ def backward(inp, d_o, d_o_pts, d_o_pair):
             d1, d2 = np.zeros_like(z1b), np.zeros_like(z2b)
             lib().ipa_oracle_pair_backward(L, r, cz, _p(z1b), _p(z2b), _p(outs[6]), _p(d1), _p(d2))
             g["dz1"][b], g["dz2"][b] = d1, d2
+    return g
+
+
+def backward_sampled(inp, d_o, d_o_pts, d_o_pair, samples):
+    """The gradients of backward() at sizes where the dense pair tensor does not fit: inp must hold
+    factors z1, z2; samples is one index array per batch element (equal lengths n).  Returns dq, dk,
+    dv [B,n,H,c], dq_pts, dk_pts [B,n,H,Pq,3], dv_pts [B,n,H,Pv,3], dz1, dz2 [B,n,r,cz], drot [B,n,3,3],
+    dtrans [B,n,3] for the sampled residues (entry a <-> residue samples[b][a]) and the full dgamma [H],
+    dw_b [H,cz]."""
+    B, L, H, c, Pq, Pv, cz = _dims(inp)
+    r = np.asarray(inp["z1"]).shape[2]
+    samples = [np.ascontiguousarray(x, dtype=np.int32) for x in samples]
+    n = len(samples[0])
+    assert all(len(x) == n and len(set(x.tolist())) == n for x in samples)
+    w_b, gamma = _f64(inp["w_b"]), _f64(inp["gamma"])
+    mask = inp.get("mask")
+    shapes = (("dq", (n, H, c)), ("dk", (n, H, c)), ("dv", (n, H, c)), ("dq_pts", (n, H, Pq, 3)),
+              ("dk_pts", (n, H, Pq, 3)), ("dv_pts", (n, H, Pv, 3)), ("dz1", (n, r, cz)), ("dz2", (n, r, cz)),
+              ("drot", (n, 3, 3)), ("dtrans", (n, 3)))
+    g = {key: np.zeros((B,) + shp) for key, shp in shapes}
+    g["dgamma"] = np.zeros(H)
+    g["dw_b"] = np.zeros((H, cz))
+    for b in range(B):
+        arrs = [_f64(inp[key][b]) for key in
+                ("q", "k", "v", "q_pts", "k_pts", "v_pts", "rot", "trans", "z1", "z2")]
+        mp = ctypes.POINTER(ctypes.c_uint8)()
+        if mask is not None:
+            m = np.ascontiguousarray(np.asarray(mask[b]) != 0, dtype=np.uint8)
+            mp = m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+        ups = [_f64(d_o[b]), _f64(d_o_pts[b]), _f64(d_o_pair[b])]
+        outs = [np.zeros(shp) for _, shp in shapes] + [np.zeros(H), np.zeros((H, cz))]
+        lib().ipa_oracle_backward_sampled(
+            L, H, c, Pq, Pv, cz, r, *[_p(a) for a in arrs], _p(w_b), _p(gamma),
+            float(inp["w_L"]), float(inp["w_C"]), mp, *[_p(a) for a in ups], n,
+            samples[b].ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), *[_p(a) for a in outs])
+        for (key, _), arr in zip(shapes, outs[:10]):
+            g[key][b] = arr
+        g["dgamma"] += outs[10]
+        g["dw_b"] += outs[11]
     return g

@@ -152,13 +152,17 @@ int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const voi
 {
     int rc = check_desc(desc, true);
     if (rc != FIPA_OK) return rc;
-    const void *req[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, o, o_pts, o_pair, lse,
+    const void *req[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma,
                          d_o, d_o_pts, d_o_pair, d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2,
                          d_gamma, workspace};
     for (const void *ptr : req) {
         if (!ptr) return FIPA_ERR_INVALID_ARG;
         if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
     }
+    // (the saved forward results are not read: everything is recomputed from the inputs)
+    const void *saved[] = {o, o_pts, o_pair, lse};
+    for (const void *ptr : saved)
+        if (ptr && !aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
     if (d_w_b && !aligned16(d_w_b)) return FIPA_ERR_ALIGNMENT;
     if ((d_rot == nullptr) != (d_trans == nullptr)) return FIPA_ERR_INVALID_ARG;
     if (d_rot && (!aligned16(d_rot) || !aligned16(d_trans))) return FIPA_ERR_ALIGNMENT;

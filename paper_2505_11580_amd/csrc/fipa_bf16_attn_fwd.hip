@@ -998,8 +998,8 @@ template <int DZ, bool FUSED>
 hipError_t launch(const AttnParams &p, hipStream_t stream)
 {
     using C = AttnCfg<DZ>;
-    hipError_t e = hipFuncSetAttribute((const void *)fipa_attn_fwd_bf16_kernel<DZ, FUSED>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    static LdsLimit lds_limit;
+    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_attn_fwd_bf16_kernel<DZ, FUSED>, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     if (p.plan.full % 8 != 0 || p.plan.full + p.plan.rem != p.total_tiles || p.plan.S < 1 ||
         (p.plan.S > 1 && (!FUSED || p.cz < 32)))

@@ -466,8 +466,8 @@ hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, hipStream_t st
 {
     if (DZ != 512) return hipErrorInvalidValue;
     using C = WideCfg<512, 2>;
-    hipError_t e = hipFuncSetAttribute((const void *)fipa_attn_fwd_wide_kernel<512, 2>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    static LdsLimit lds_limit;
+    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_attn_fwd_wide_kernel<512, 2>, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     const int chunk = (p.total_tiles + 7) / 8;
     hipLaunchKernelGGL((fipa_attn_fwd_wide_kernel<512, 2>), dim3(chunk * 8, 2), dim3(256), C::LDS_BYTES, stream, p);

@@ -506,8 +506,8 @@ template <int DZ, int MODE>
 hipError_t launch(const BwdParams &p, hipStream_t stream)
 {
     using C = BwdCfg<DZ, MODE>;
-    hipError_t e = hipFuncSetAttribute((const void *)fipa_bwd_kernel<DZ, MODE>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    static LdsLimit lds_limit;
+    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_bwd_kernel<DZ, MODE>, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     const int chunk = (p.total_tiles + 7) / 8;
     hipLaunchKernelGGL((fipa_bwd_kernel<DZ, MODE>), dim3(chunk * 8), dim3(256), C::LDS_BYTES, stream, p);

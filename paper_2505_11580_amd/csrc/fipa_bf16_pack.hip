@@ -355,8 +355,8 @@ hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream)
         hipLaunchKernelGGL(fipa_pack_heads_af2_bf16_kernel, dim3(3 * nbh + nbz), dim3(256), 0, stream, p, nbh);
     } else {
         const size_t lds_heads = (size_t)4 * 3 * 64 * kRowStride * sizeof(bf16_t);
-        e = hipFuncSetAttribute((const void *)fipa_pack_heads_bf16_kernel,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_heads);
+        static LdsLimit lds_limit;
+        e = raise_lds_limit(lds_limit, (const void *)fipa_pack_heads_bf16_kernel, (int)lds_heads);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(fipa_pack_heads_bf16_kernel, dim3(p.NT, (p.H + 3) / 4, p.B), dim3(256),
                            lds_heads, stream, p);

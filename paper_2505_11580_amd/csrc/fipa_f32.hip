@@ -331,12 +331,13 @@ hipError_t f32_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream
     timer.begin(1);  // the fp32 kernel contains the epilogue; stage 2 stays empty
 
 #define FIPA_F32_CASE(N)                                                                        \
-    case N:                                                                                     \
-        e = hipFuncSetAttribute((const void *)fipa_attn_f32_kernel<N>,                          \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+    case N: {                                                                                   \
+        static LdsLimit lim;                                                                    \
+        e = raise_lds_limit(lim, (const void *)fipa_attn_f32_kernel<N>, (int)lds);              \
         if (e != hipSuccess) return e;                                                          \
         hipLaunchKernelGGL(fipa_attn_f32_kernel<N>, grid, dim3(256), lds, stream, p);           \
-        break;
+        break;                                                                                  \
+    }
     switch (MC) {
         FIPA_F32_CASE(1)
         FIPA_F32_CASE(2)

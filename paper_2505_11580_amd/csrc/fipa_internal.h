@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -13,6 +14,25 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Dynamic-LDS limit of a kernel, raised once per device instead of on every launch: `state` is a
+// function-local static of the launching function (one per kernel instantiation) that remembers
+// the largest limit already set on each device.
+struct LdsLimit {
+    std::atomic<int> set[32] = {};
+};
+inline hipError_t raise_lds_limit(LdsLimit &state, const void *kernel, int bytes)
+{
+    int dev = 0;
+    const bool known = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 32;
+    if (known && state.set[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && known) {
+        int cur = state.set[dev].load(std::memory_order_relaxed);
+        while (cur < bytes && !state.set[dev].compare_exchange_weak(cur, bytes, std::memory_order_release)) {}
+    }
+    return e;
+}
 
 // All tensor arguments of fipa_forward, as passed by the caller.
 struct FwdArgs {

@@ -270,8 +270,8 @@ __global__ __launch_bounds__(256) void fipa_gemm_kernel(GemmParams p)
 template <class T, bool CONCAT_A, bool SCATTER>
 hipError_t launch_gemm(const GemmParams &g, hipStream_t stream)
 {
-    hipError_t e = hipFuncSetAttribute((const void *)fipa_gemm_kernel<T, CONCAT_A, SCATTER>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_TOTAL);
+    static LdsLimit lds_limit;
+    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_gemm_kernel<T, CONCAT_A, SCATTER>, T::LDS_TOTAL);
     if (e != hipSuccess) return e;
     const int nkc = (g.K + kGK - 1) / kGK;
     const int nsplit = g.chunks_per_split > 0 ? (nkc + g.chunks_per_split - 1) / g.chunks_per_split : 1;

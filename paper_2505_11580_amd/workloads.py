@@ -148,18 +148,26 @@ def make_module_inputs(cfg, d_s=256, seed=None, **override):
     return m
 
 
-def select_rows(inp, n_rows, seed=0):
+def select_rows(inp, n_rows, seed=0, tile=128):
     """Query rows for sampled parity at sizes the oracle cannot sweep: per batch element the
-    first row, the last valid row, the first padded row (if any) and random valid rows."""
+    first row, the last valid row, the first padded row (if any), one row at a random position
+    inside every `tile`-row query tile that holds valid rows, and random valid rows up to n_rows
+    (all distinct; every batch element gets the same count)."""
     rng = np.random.default_rng(seed)
     L = inp["dims"]["L"]
     rows = []
     for b, ln in enumerate(inp["lengths"]):
         ln = int(ln)
-        fixed = [0, ln - 1] + ([ln] if ln < L else [])
-        rest = rng.choice(ln, size=max(0, n_rows - len(fixed)), replace=False) if ln > 3 else []
-        rows.append(np.array((fixed + list(rest))[:n_rows], dtype=np.int32))
+        picked = [0, ln - 1] + ([ln] if ln < L else [])
+        for t0 in range(0, ln, tile):
+            picked.append(int(rng.integers(t0, min(t0 + tile, ln))))
+        picked = list(dict.fromkeys(picked))  # distinct, order kept
+        if len(picked) < n_rows and ln > len(picked):
+            rest = [int(x) for x in rng.permutation(ln) if int(x) not in set(picked)]
+            picked += rest[:n_rows - len(picked)]
+        rows.append(np.array(picked, dtype=np.int32))
     n = min(len(r) for r in rows)
+    # (a short chain may offer fewer rows than a long one: drop from the random tail, never the fixed rows)
     return [r[:n] for r in rows]
 
 

@@ -29,17 +29,28 @@ def run_gpu_backward(inp):
     return {n: grads[n].float().cpu().numpy().astype(np.float64) for n, _ in GRADS}
 
 
-def check_backward(inp, label, tol=2e-2):
+def check_backward(inp, label, tol=2e-2, samples=None):
+    """All gradients against the oracle: every element (dense oracle backward), or -- at sizes the
+    dense pair tensor does not fit -- the gradients of the sampled residues (one index array per
+    batch element) from the oracle's row-walking backward, plus the full d_gamma and d_w_b."""
     got = run_gpu_backward(inp)
-    want = ipa_oracle.backward(inp, inp["d_o"], inp["d_o_pts"], inp["d_o_pair"])
-    errs = {}
+    if samples is None:
+        want = ipa_oracle.backward(inp, inp["d_o"], inp["d_o_pts"], inp["d_o_pair"])
+    else:
+        want = ipa_oracle.backward_sampled(inp, inp["d_o"], inp["d_o_pts"], inp["d_o_pair"], samples)
+        for n, _ in GRADS:
+            if n not in ("d_gamma", "d_w_b"):
+                got[n] = np.stack([got[n][b][samples[b]] for b in range(len(samples))])
+    errs, elem = {}, {}
     # a gradient that is exactly zero in the oracle (a single key: constant softmax) is measured
     # against the scale of the value gradient instead of its own
     floor = 1e-3 * float(np.abs(want["dv"]).max())
     for n, o in GRADS:
         assert np.all(np.isfinite(got[n])), (label, n)
         errs[n] = float(np.abs(got[n] - want[o]).max()) / max(float(np.abs(want[o]).max()), floor)
-    print(label, {k: "%.1e" % v for k, v in errs.items()}, flush=True)
+        elem[n] = gu.elem_err(got[n], want[o])
+    print(label, "max-norm", {k: "%.1e" % v for k, v in errs.items()},
+          "element-wise", {k: "%.1e" % v for k, v in elem.items()}, flush=True)
     for n, _ in GRADS:
         assert errs[n] <= tol, (label, n, errs[n])
 
@@ -66,6 +77,14 @@ def test_backward_masked():
 def test_backward_masked_odd_pair_count():
     # 5 x 3 = 15 (batch, head) pairs, ragged: the gradient kernels renumber the pairs of a masked batch
     check_backward(wl.make_inputs(4, B=5, L=140, H=3, cz=32, varlen=True, min_len=10, trans_scale=0.5), "bwd varlen B=5 H=3")
+
+
+def test_backward_workload4_full_size_sampled():
+    # workload 4 at full size (B=2, L=4096): the gradients of 256 residues per batch element (first,
+    # last, one in every 128-row tile, the rest random; each both as query row and as key column)
+    # and the full d_gamma, d_w_b against the oracle's row-walking backward
+    inp = wl.make_inputs(4)
+    check_backward(inp, "cfg4 full size, 256 sampled residues", samples=wl.select_rows(inp, 256))
 
 
 def test_backward_full_size_properties():

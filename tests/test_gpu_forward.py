@@ -87,9 +87,9 @@ def test_bf16_workload1_full():
     gu.check(wl.make_inputs(1), label="cfg1 bf16 full")
 
 
-def test_bf16_workload2_sampled_rows():
-    inp = wl.make_inputs(2)
-    gu.check(inp, rows=wl.select_rows(inp, 96), label="cfg2 bf16 sampled rows")
+def test_bf16_workload2_full():
+    # every element of every output (the oracle sweeps the rows in chunks of 256)
+    gu.check(wl.make_inputs(2), label="cfg2 bf16 full", chunk=256)
 
 
 def test_bf16_rank4_small():
@@ -99,10 +99,11 @@ def test_bf16_rank4_small():
 
 
 def test_bf16_workload3_sampled_rows():
-    # variable-length padded batch, lengths U[1024, 8192], r = 4: first / last valid / first padded /
-    # random rows of every batch element against the oracle's row-subset form
+    # variable-length padded batch, lengths U[1024, 8192], r = 4: 256 rows of every batch element
+    # (first / last valid / first padded, one in every 128-row query tile, the rest random) against
+    # the oracle's row-subset form
     inp = wl.make_inputs(3)
-    gu.check(inp, rows=wl.select_rows(inp, 24), label="cfg3 bf16 sampled rows")
+    gu.check(inp, rows=wl.select_rows(inp, 256), label="cfg3 bf16 sampled rows", chunk=64)
     got = gu.run_gpu(inp)
     for b, ln in enumerate(inp["lengths"]):
         for n in gu.NAMES:
@@ -111,7 +112,7 @@ def test_bf16_workload3_sampled_rows():
 
 def test_bf16_workload4_forward_sampled_rows():
     inp = wl.make_inputs(4, with_grads=False)
-    gu.check(inp, rows=wl.select_rows(inp, 48), label="cfg4 fwd bf16 sampled rows")
+    gu.check(inp, rows=wl.select_rows(inp, 256), label="cfg4 fwd bf16 sampled rows", chunk=128)
 
 
 def test_se3_invariance_on_gpu():
