@@ -101,6 +101,29 @@ int fipa_forward(const fipa_desc *desc,
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * fipa_forward without a workspace argument, for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, same kernels and same results as fipa_forward, with the scratch memory taken from an
+ * array of FIPA_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the
+ * library is used on holds one copy until the process ends).  Calls nothing that allocates.
+ *   - FIPA_ERR_WORKSPACE when fipa_workspace_bytes(desc) exceeds FIPA_STATIC_SCRATCH_BYTES
+ *     (bf16, H = 12, c_z = 128, r = 2: up to about 8000 residues in total over the batch);
+ *     FIPA_ERR_LAUNCH when the array's device address cannot be obtained.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *     streams, or threads) race; calls enqueued one after the other on one stream are safe.  The
+ *     array keeps the last call's contents; every call clears what it needs cleared itself.
+ */
+#define FIPA_STATIC_SCRATCH_BYTES (64u << 20)
+int fipa_forward_static(const fipa_desc *desc,
+                        const void *q, const void *k, const void *v,
+                        const void *q_pts, const void *k_pts, const void *v_pts,
+                        const float *rot, const float *trans,
+                        const void *z1, const void *z2,
+                        const float *w_b, const float *gamma, const uint8_t *mask,
+                        float *o, float *o_pts, float *o_pair, float *lse,
+                        void *hip_stream);
+
+/*
  * Forward on a packed batch of chains of different lengths (the variable-length inputs of the
  * experiments in Section 3, without padding): the tensors of fipa_forward with the leading
  * [B, L] replaced by [total], total = cu_seqlens[B], chain b occupying rows cu_seqlens[b] ..

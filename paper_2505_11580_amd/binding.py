@@ -24,7 +24,7 @@ FIPA_DTYPE_F32 = 0
 FIPA_DTYPE_BF16 = 1
 
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
-           "fipa_forward_packed", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
+           "fipa_forward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
            "fipa_module_backward_workspace_bytes", "fipa_module_backward",
            "fipa_profile_begin", "fipa_profile_begin_every", "fipa_profile_end")
 PROFILE_STAGES = 3
@@ -61,6 +61,8 @@ def lib():
         L.fipa_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.fipa_forward.restype = ctypes.c_int
         L.fipa_forward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 17 + [vp, sz, vp]
+        L.fipa_forward_static.restype = ctypes.c_int
+        L.fipa_forward_static.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 17 + [vp]
         L.fipa_forward_packed.restype = ctypes.c_int
         L.fipa_forward_packed.argtypes = [ctypes.POINTER(FipaDesc), ctypes.POINTER(ctypes.c_int32)] + [vp] * 17 + [vp, sz, vp]
         L.fipa_backward.restype = ctypes.c_int
@@ -123,6 +125,19 @@ def fipa_forward(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, ga
                             ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
     if rc != FIPA_OK:
         raise FipaError(rc, "fipa_forward")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20  # FIPA_STATIC_SCRATCH_BYTES of include/fipa.h
+
+
+def fipa_forward_static(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,
+                        o, o_pts, o_pair, lse):
+    """Enqueue fipa_forward_static (the library's own scratch array instead of a workspace) on
+    torch's current stream."""
+    args = [q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask, o, o_pts, o_pair, lse]
+    rc = lib().fipa_forward_static(ctypes.byref(desc), *[_ptr(t) for t in args], _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_forward_static")
 
 
 def fipa_forward_packed(desc, cu_seqlens, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,

@@ -36,6 +36,29 @@ int check_desc(const fipa_desc *d, bool backward)
 
 }  // namespace
 
+namespace fipa {
+
+int check_forward_args(const fipa_desc *desc, const FwdArgs &a)
+{
+    const int rc = check_desc(desc, false);
+    if (rc != FIPA_OK) return rc;
+    const void *req[] = {a.q, a.k, a.v, a.q_pts, a.k_pts, a.v_pts, a.rot, a.trans, a.z1, a.z2, a.w_b, a.gamma,
+                         a.o, a.o_pts, a.o_pair};
+    for (const void *ptr : req)
+        if (!ptr) return FIPA_ERR_INVALID_ARG;
+    for (const void *ptr : req)
+        if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
+    if (!aligned16(a.lse)) return FIPA_ERR_ALIGNMENT;
+    return FIPA_OK;
+}
+
+hipError_t enqueue_forward(const fipa_desc &desc, const FwdArgs &a, void *workspace, hipStream_t stream)
+{
+    return desc.dtype == FIPA_DTYPE_F32 ? f32_forward(desc, a, workspace, stream) : bf16_forward(desc, a, workspace, stream);
+}
+
+}  // namespace fipa
+
 extern "C" {
 
 int fipa_version(void) { return 100; }
@@ -73,23 +96,16 @@ int fipa_forward(const fipa_desc *desc, const void *q, const void *k, const void
                  const float *gamma, const uint8_t *mask, float *o, float *o_pts, float *o_pair,
                  float *lse, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_desc(desc, false);
+    const FwdArgs a{q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask, o, o_pts, o_pair, lse};
+    const int rc = check_forward_args(desc, a);
     if (rc != FIPA_OK) return rc;
-    const void *req[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, o, o_pts, o_pair, workspace};
-    for (const void *ptr : req)
-        if (!ptr) return FIPA_ERR_INVALID_ARG;
-    const void *al[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, o, o_pts, o_pair, lse, workspace};
-    for (const void *ptr : al)
-        if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
+    if (!workspace) return FIPA_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return FIPA_ERR_ALIGNMENT;
     size_t need = 0;
     fipa_workspace_bytes(desc, &need, nullptr);
     if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
-
-    FwdArgs a{q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask, o, o_pts, o_pair, lse};
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const hipError_t e = desc->dtype == FIPA_DTYPE_F32 ? f32_forward(*desc, a, workspace, stream)
-                                                       : bf16_forward(*desc, a, workspace, stream);
-    return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
+    return enqueue_forward(*desc, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? FIPA_OK
+                                                                                                  : FIPA_ERR_LAUNCH;
 }
 
 int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens, const void *q, const void *k, const void *v,

@@ -74,6 +74,11 @@ struct ModuleBwdArgs {
     float *d_gamma, *d_w_b, *d_rot, *d_trans;             // d_w_b and the frame pair may be null
 };
 
+// Host-side checks of fipa_forward's description and tensor pointers (null, alignment; the
+// workspace is the caller's business), and the dispatch to the fp32 or bf16 chain.
+int check_forward_args(const fipa_desc *desc, const FwdArgs &a);
+hipError_t enqueue_forward(const fipa_desc &desc, const FwdArgs &a, void *workspace, hipStream_t stream);
+
 // Stage timing (fipa_profile_begin / fipa_profile_end).  A StageTimer is created per API call;
 // when profiling is inactive every method is a no-op.
 class StageTimer {
