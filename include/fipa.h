@@ -57,8 +57,17 @@ typedef struct fipa_desc {
     int32_t dtype; /* FIPA_DTYPE_* : type of q,k,v,q_pts,k_pts,v_pts,z1,z2 and of their gradients */
     float w_L, w_C;
     float qk_scale;
-    uint32_t flags; /* reserved, must be 0 */
+    uint32_t flags; /* 0, or FIPA_FLAG_* bits; other bits are reserved and must be 0 */
 } fipa_desc;
+
+/*
+ * fipa_forward, bf16, c = 16, Pv = 8, cz in {32, 64, 128, 256}, r*cz <= 256: run the fused attention
+ * (Algorithm 1 step 7) with the variant of the kernel that gives every SIMD two waves -- one forming
+ * S^T and the softmax, one accumulating P V -- instead of one wave doing both.  Same results within
+ * the stated tolerance; slower than the default on every shape measured so far, kept as a measured
+ * alternative.  Ignored where it does not apply.
+ */
+#define FIPA_FLAG_WAVE_SPECIALISED 1u
 
 /* Library version, major*10000 + minor*100 + patch. */
 int fipa_version(void);

@@ -27,6 +27,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
 _VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
 PER_FILE = {
     "fipa_bf16_attn_fwd.hip": _VGPR_FORM,
+    "fipa_bf16_attn_fwd_ws.hip": _VGPR_FORM,
     "fipa_bf16_attn_fwd_wide.hip": _VGPR_FORM,
     "fipa_bf16_bwd_kernel.hip": _VGPR_FORM,
 }

@@ -15,7 +15,7 @@ int check_desc(const fipa_desc *d, bool backward)
         d->r <= 0)
         return FIPA_ERR_INVALID_ARG;
     if (d->dtype != FIPA_DTYPE_F32 && d->dtype != FIPA_DTYPE_BF16) return FIPA_ERR_INVALID_ARG;
-    if (d->flags != 0) return FIPA_ERR_INVALID_ARG;
+    if ((d->flags & ~(uint32_t)FIPA_FLAG_WAVE_SPECIALISED) != 0) return FIPA_ERR_INVALID_ARG;
     if (!(d->w_L == d->w_L) || !(d->w_C == d->w_C) || !(d->qk_scale == d->qk_scale))
         return FIPA_ERR_INVALID_ARG;
     const long long DZ = (long long)d->r * d->cz;

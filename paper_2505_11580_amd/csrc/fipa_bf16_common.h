@@ -214,6 +214,9 @@ struct AttnParams {
     SplitPlan plan;
     float *partial;
     int *counters;
+    // wave-specialised kernel: an address at or below Kh, Vh, Z2 and kbias, all of which lie less
+    // than 4 GiB above it (the start of the workspace that holds them)
+    const char *ws_base;
 };
 
 struct EpiParams {
@@ -269,6 +272,8 @@ hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream);
 
 hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream);
 hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream);
+bool attn_fwd_ws_supported(int DZ, int cz);  // shapes of the wave-specialised fused kernel
+hipError_t launch_attn_fwd_ws_bf16(const AttnParams &p, int DZ, hipStream_t stream);
 hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, hipStream_t stream);  // r*cz = 512
 hipError_t launch_epilogue_bf16(const EpiParams &p, hipStream_t stream);
 

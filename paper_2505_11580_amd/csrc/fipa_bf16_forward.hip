@@ -56,8 +56,14 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.w_b; at.w_L = d.w_L;
     at.plan = w.plan; at.partial = (float *)(base + w.partial); at.counters = counters;
     at.deal = a.mask != nullptr;
+    at.ws_base = base;
+    // (the wave-specialised kernel is an opt-in variant: it measured slower than the default on every shape tried)
+    const bool ws_kernel = (d.flags & FIPA_FLAG_WAVE_SPECIALISED) && fused && attn_fwd_ws_supported(w.DZ, d.cz) &&
+                           w.total < (1ull << 32);
     timer.begin(1);
-    e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream) : launch_attn_fwd_bf16(at, w.DZ, fused, stream);
+    e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream)
+        : ws_kernel ? launch_attn_fwd_ws_bf16(at, w.DZ, stream)
+                    : launch_attn_fwd_bf16(at, w.DZ, fused, stream);
     if (e != hipSuccess) return e;
     timer.end(1);
     if (fused) return hipSuccess;  // steps 8-9 ran inside the attention kernel
