@@ -22,14 +22,16 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 
-def cpu_baseline(inp, flops_per_pair, budget_s=12.0):
-    """Time the oracle (as it stands) on whole passes over the same workload, about budget_s seconds."""
+def cpu_baseline(inp, flops_per_pair, budget_s=12.0, single_budget_s=6.0):
+    """Time the oracle (as it stands) on whole passes over the same workload, about budget_s seconds on
+    all host threads, then on a row sample with one thread."""
     import numpy as np
     from oracle import ipa_oracle
     d = inp["dims"]
     L, H, B = d["L"], d["H"], d["B"]
     rows = [np.arange(int(n), dtype=np.int32) for n in inp["lengths"]]  # every valid query row
     n_rows = sum(len(r) for r in rows)
+    threads = ipa_oracle.num_threads()
     passes, secs = 0, 0.0
     while secs < budget_s and passes < 50:
         t0 = time.perf_counter()
@@ -37,15 +39,57 @@ def cpu_baseline(inp, flops_per_pair, budget_s=12.0):
         secs += time.perf_counter() - t0
         passes += 1
     pairs = passes * n_rows * L * H
+    # one thread: the first rows of every chain, sized from the all-thread rate to about single_budget_s
+    per_row_s = secs / (passes * n_rows) * threads
+    n1 = int(max(4, min(min(len(r) for r in rows), single_budget_s / max(per_row_s, 1e-9) / B)))
+    ipa_oracle.set_num_threads(1)
+    t0 = time.perf_counter()
+    ipa_oracle.forward(inp, rows=[r[:n1] for r in rows])
+    secs1 = time.perf_counter() - t0
+    ipa_oracle.set_num_threads(threads)
     return {
         "value": pairs * flops_per_pair / secs / 1e12,
         "unit": "TFLOP/s",
         "residues_per_s": passes * n_rows / secs,
-        "cores": ipa_oracle.num_threads(),
+        "cores": threads,
         "kind": "oracle",
         "sample": "%d whole pass(es) of the fp64 C oracle (OpenMP) over the same workload "
                   "(all %d query rows, %d keys, %d heads), %.1f s" % (passes, n_rows, L, H, secs),
+        "single_thread": {"value": n1 * B * L * H * flops_per_pair / secs1 / 1e12, "unit": "TFLOP/s",
+                          "residues_per_s": n1 * B / secs1, "cores": 1,
+                          "sample": "the first %d query rows of each of the %d chains, %.1f s" % (n1, B, secs1)},
     }
+
+
+def measured_peaks():
+    """What this machine sustains: an MFMA-only kernel (bf16 32x32x16, independent accumulators) and a plain
+    256 MiB elementwise copy.  Second denominators beside the published peaks; HIP-event timing."""
+    import torch
+    from paper_2505_11580_amd import binding
+    wgs, iters = 1024, 4000
+    buf = torch.empty(wgs * 256, dtype=torch.float32, device="cuda:0")
+    for _ in range(3):
+        flop = binding.probe_mfma(iters, wgs, buf)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        binding.probe_mfma(iters, wgs, buf)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma = 5 * flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    n = 256 << 20
+    src = torch.ones(n // 4, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.mul(src, 1.0, out=dst)
+    e0.record()
+    for _ in range(10):
+        torch.mul(src, 1.0, out=dst)
+    e1.record()
+    torch.cuda.synchronize()
+    copy = 10 * 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return {"mfma_bf16_tflops": mfma, "copy_read_plus_write_gbs": copy,
+            "how": "MFMA-only kernel (%d workgroups x 4 waves x %d x 16 MFMAs) and a 256 MiB elementwise copy, HIP events" % (wgs, iters)}
 
 
 def backward_leg(workload, steps=30, warmup=10):
@@ -126,9 +170,10 @@ def calibrate_copy(nbytes=256 << 20):
     torch.cuda.synchronize()
 
 
-# HBM traffic of one launch of the attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this script (see profiles/), scaled by what the same counters read for calibrate_copy().
-MEASURED_TRAFFIC_BYTES = {2: 163.3e6}  # workload 2: 107.0 MB fetched + 56.3 MB written
+# HBM traffic of one launch of the attention kernel: NOT measured in this run.  The figure comes from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read
+# for calibrate_copy(); the summary with the commands is the file named here.
+MEASURED_TRAFFIC = {2: (163.3e6, "profiles/attn_fwd_bf16_workload2_hbm_traffic.md")}  # 107.0 MB fetched + 56.3 MB written
 
 
 def main():
@@ -147,6 +192,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true", help="skip the fipa_backward leg (workload 4)")
     ap.add_argument("--no-module", action="store_true", help="skip the module leg (fipa_module_forward / backward)")
+    ap.add_argument("--no-measured-peaks", action="store_true", help="skip the MFMA-only and copy probes")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB copy kernel (for scaling hardware counters)")
     args = ap.parse_args()
@@ -170,7 +216,8 @@ def main():
     residues = int(inp["lengths"].sum())
 
     clock_warmup_steps = max(0, args.clock_warmup - args.warmup)
-    for _ in range(clock_warmup_steps + args.warmup):
+    warmup_run = clock_warmup_steps + args.warmup  # untimed steps actually run
+    for _ in range(warmup_run):
         binding.forward(desc, dev, out)
     torch.cuda.synchronize()
 
@@ -199,7 +246,8 @@ def main():
         "residues_per_s": residues / (ms_per_step * 1e-3),
         "n_gpus": 1,
         "steps": args.steps,
-        "warmup": args.warmup,
+        "warmup": warmup_run,
+        "warmup_requested": args.warmup,
         "clock_warmup_steps": clock_warmup_steps,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
@@ -214,11 +262,18 @@ def main():
                    "valid_pairs": pairs, "flops_per_pair": fpp},
         "stage_ms": {"pack": stage_ms[0], "attention": stage_ms[1], "epilogue": stage_ms[2],
                      "timed_calls": n_timed, "timed_every": every},
-        "roofline": {"kernel": "fipa_attn_fwd_bf16_kernel", "bound": "mfma", "achieved": attn_tflops,
+        "roofline": {"kernel": "fipa_attn_fwd_wide_kernel" if dims["r"] * dims["cz"] > 256 else "fipa_attn_fwd_bf16_kernel",
+                     "bound": "mfma", "achieved": attn_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)},
+                     "traffic": MEASURED_TRAFFIC.get(args.workload, (None, None))[0],
+                     "traffic_source": MEASURED_TRAFFIC.get(args.workload, (None, "not measured for this workload"))[1]},
     }
+    if not args.no_measured_peaks:
+        pk = measured_peaks()
+        result["roofline"]["peak_measured"] = pk["mfma_bf16_tflops"]
+        result["roofline"]["frac_of_measured_peak"] = attn_tflops / pk["mfma_bf16_tflops"] if pk["mfma_bf16_tflops"] > 0 else None
+        result["measured_peaks"] = pk
     if args.calibrate_copy:
         calibrate_copy()
     del out, dev

@@ -260,6 +260,16 @@ int fipa_profile_begin(int capacity);
 int fipa_profile_begin_every(int capacity, int every);
 int fipa_profile_end(float *stage_ms, int *n_calls);
 
+/*
+ * Measured denominator for roofline figures: enqueues a kernel of `workgroups` x 4 waves that does
+ * nothing but `iters` x 16 independent bf16 32x32x16 MFMAs per wave (operands in registers), and
+ * writes the number of floating-point operations that launch performs to *flop (HOST pointer, may
+ * be NULL).  out: device buffer of workgroups * 256 floats (receives a checksum).  The caller times
+ * the launch.  A measuring aid, not part of the method: roofline fractions are quoted against the
+ * published peak; this shows what the matrix pipes sustain at the clock they hold under load.
+ */
+int fipa_probe_mfma(int iters, int workgroups, float *out, void *hip_stream, double *flop);
+
 #ifdef __cplusplus
 }
 #endif

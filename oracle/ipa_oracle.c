@@ -65,6 +65,17 @@ int ipa_oracle_num_threads(void)
 #endif
 }
 
+/* Number of threads the row loops may use from now on (benchmark legs time the oracle on one core too). */
+void ipa_oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0)
+        omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /*
  * Dense pair rows from the factors (Section 2.4: z_ij = z1_i^T z2_j, the
  * contraction runs over the rank index):

@@ -25,6 +25,8 @@ def lib():
         bp = ctypes.POINTER(ctypes.c_uint8)
         i, d = ctypes.c_int, ctypes.c_double
         L.ipa_oracle_num_threads.restype = ctypes.c_int
+        L.ipa_oracle_set_num_threads.restype = None
+        L.ipa_oracle_set_num_threads.argtypes = [ctypes.c_int]
         L.ipa_oracle_pair_rows.restype = None
         L.ipa_oracle_pair_rows.argtypes = [i, i, i, dp, dp, i, ip, dp]
         L.ipa_oracle_forward_rows.restype = ctypes.c_int
@@ -41,6 +43,11 @@ def lib():
 
 def num_threads():
     return int(lib().ipa_oracle_num_threads())
+
+
+def set_num_threads(n):
+    """Threads the oracle's row loops use from now on (marshalling only: omp_set_num_threads)."""
+    lib().ipa_oracle_set_num_threads(int(n))
 
 
 def _f64(a):

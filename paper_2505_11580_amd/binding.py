@@ -26,7 +26,7 @@ FIPA_DTYPE_BF16 = 1
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
            "fipa_forward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
            "fipa_module_backward_workspace_bytes", "fipa_module_backward",
-           "fipa_profile_begin", "fipa_profile_begin_every", "fipa_profile_end")
+           "fipa_profile_begin", "fipa_profile_begin_every", "fipa_profile_end", "fipa_probe_mfma")
 PROFILE_STAGES = 3
 
 
@@ -81,6 +81,8 @@ def lib():
         L.fipa_profile_begin_every.argtypes = [ctypes.c_int, ctypes.c_int]
         L.fipa_profile_end.restype = ctypes.c_int
         L.fipa_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+        L.fipa_probe_mfma.restype = ctypes.c_int
+        L.fipa_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, ctypes.POINTER(ctypes.c_double)]
         _LIB = L
     return _LIB
 
@@ -207,6 +209,15 @@ def fipa_profile_end():
 
 
 # ---- conveniences for tests and the benchmark (allocation + upload; no arithmetic) ----------
+
+def probe_mfma(iters, workgroups, out):
+    """Enqueue the MFMA-only probe kernel on torch's current stream; returns the flop it performs."""
+    flop = ctypes.c_double(0.0)
+    rc = lib().fipa_probe_mfma(int(iters), int(workgroups), _ptr(out), _stream(), ctypes.byref(flop))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_probe_mfma")
+    return flop.value
+
 
 def upload(inp, device="cuda:0"):
     """numpy workload dict (workloads.make_inputs) -> device tensors + desc."""

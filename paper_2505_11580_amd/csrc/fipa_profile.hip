@@ -87,3 +87,39 @@ extern "C" int fipa_profile_end(float *stage_ms, int *n_calls)
     g_prof.capacity = g_prof.used = 0;
     return rc;
 }
+
+// ---- measured denominators for the benchmark -------------------------------------------------------
+// A loop of independent 32x32x16 bf16 MFMAs (four accumulators per wave, operands in registers, no
+// memory traffic): what the matrix pipes of this chip sustain at the clock they hold under that
+// load.  2 * 32*32*16 flop per MFMA per wave.
+namespace {
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+
+__global__ __launch_bounds__(256) void fipa_probe_mfma_kernel(float *out, int iters)
+{
+    probe_bf16x8 a, b;
+    for (int x = 0; x < 8; ++x) {
+        a[x] = (__bf16)(float)((threadIdx.x + x) & 3);
+        b[x] = (__bf16)1.0f;
+    }
+    probe_f32x16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j & 3], 0, 0, 0);
+    }
+    float r = 0.f;
+    for (int i = 0; i < 4; ++i) r += acc[i][0];
+    if (out) out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
+}
+}  // namespace
+
+extern "C" int fipa_probe_mfma(int iters, int workgroups, float *out, void *hip_stream, double *flop)
+{
+    if (iters <= 0 || workgroups <= 0 || !out) return FIPA_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(fipa_probe_mfma_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(hip_stream), out, iters);
+    if (flop) *flop = (double)workgroups * 4.0 * (double)iters * 16.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return hipGetLastError() == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
+}
