@@ -193,6 +193,11 @@ def main():
     ap.add_argument("--no-backward", action="store_true", help="skip the fipa_backward leg (workload 4)")
     ap.add_argument("--no-module", action="store_true", help="skip the module leg (fipa_module_forward / backward)")
     ap.add_argument("--no-measured-peaks", action="store_true", help="skip the MFMA-only and copy probes")
+    ap.add_argument("--wave-specialised", action="store_true",
+                    help="run the forward leg with FIPA_FLAG_WAVE_SPECIALISED (the opt-in attention kernel with two "
+                         "waves per SIMD); the JSON line says so in config.attention_kernel")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (same generators)")
+    ap.add_argument("--seq-len", type=int, default=0, help="override the workload's sequence length (same generators)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB copy kernel (for scaling hardware counters)")
     args = ap.parse_args()
@@ -207,9 +212,16 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
 
-    inp = workloads.make_inputs(args.workload, with_grads=False)
+    over = {}
+    if args.batch > 0:
+        over["B"] = args.batch
+    if args.seq_len > 0:
+        over["L"] = args.seq_len
+    inp = workloads.make_inputs(args.workload, with_grads=False, **over)
     dims = inp["dims"]
     desc, dev = binding.upload(inp)
+    if args.wave_specialised:
+        desc.flags = binding.FIPA_FLAG_WAVE_SPECIALISED
     out = binding.alloc_outputs(desc)
     pairs = workloads.valid_pairs(inp)
     fpp = workloads.fwd_flops_per_pair(dims)
@@ -259,15 +271,19 @@ def main():
                                "accumulate, random-walk chain frames, forward only"
                                % (args.workload, dims["B"], dims["L"], dims["H"], dims["c"], dims["Pq"],
                                   dims["Pv"], dims["cz"], dims["r"]),
-                   "valid_pairs": pairs, "flops_per_pair": fpp},
+                   "valid_pairs": pairs, "flops_per_pair": fpp,
+                   "attention_kernel": "wave-specialised (opt-in)" if args.wave_specialised else "default",
+                   "shape_override": over or None},
         "stage_ms": {"pack": stage_ms[0], "attention": stage_ms[1], "epilogue": stage_ms[2],
                      "timed_calls": n_timed, "timed_every": every},
-        "roofline": {"kernel": "fipa_attn_fwd_wide_kernel" if dims["r"] * dims["cz"] > 256 else "fipa_attn_fwd_bf16_kernel",
+        "roofline": {"kernel": "fipa_attn_fwd_wide_kernel" if dims["r"] * dims["cz"] > 256
+                     else ("fipa_attn_fwd_ws_kernel" if args.wave_specialised else "fipa_attn_fwd_bf16_kernel"),
                      "bound": "mfma", "achieved": attn_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC.get(args.workload, (None, None))[0],
-                     "traffic_source": MEASURED_TRAFFIC.get(args.workload, (None, "not measured for this workload"))[1]},
+                     "traffic": None if over or args.wave_specialised else MEASURED_TRAFFIC.get(args.workload, (None, None))[0],
+                     "traffic_source": "not measured for this variant" if over or args.wave_specialised
+                     else MEASURED_TRAFFIC.get(args.workload, (None, "not measured for this workload"))[1]},
     }
     if not args.no_measured_peaks:
         pk = measured_peaks()

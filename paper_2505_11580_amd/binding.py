@@ -22,6 +22,7 @@ FIPA_ERR_ALIGNMENT = -4
 FIPA_ERR_LAUNCH = -5
 FIPA_DTYPE_F32 = 0
 FIPA_DTYPE_BF16 = 1
+FIPA_FLAG_WAVE_SPECIALISED = 1  # desc.flags bit: opt-in attention kernel with two waves per SIMD
 
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
            "fipa_forward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",

@@ -8,9 +8,10 @@ NAMES = ("o", "o_pts", "o_pair")
 TOL = {"fp32": 1e-4, "bf16": 2e-2}  # max|gpu - oracle| / max|oracle| per output tensor
 
 
-def run_gpu(inp):
+def run_gpu(inp, flags=0):
     import torch
     desc, dev = binding.upload(inp)
+    desc.flags = flags
     out = binding.alloc_outputs(desc)
     for n in NAMES:
         out[n].fill_(float("nan"))  # every element must be overwritten
@@ -44,10 +45,11 @@ def oracle_forward_chunked(inp, rows=None, chunk=512):
     return {k: np.concatenate([p[k] for p in parts], axis=1) for k in NAMES}
 
 
-def check(inp, rows=None, tol=None, label="", chunk=512):
-    """Compare the HIP path with the oracle (all rows, or the given row lists)."""
+def check(inp, rows=None, tol=None, label="", chunk=512, flags=0):
+    """Compare the HIP path with the oracle (all rows, or the given row lists); `flags` goes into
+    the description's flags field (FIPA_FLAG_* bits)."""
     tol = TOL[inp["dtype"]] if tol is None else tol
-    got = run_gpu(inp)
+    got = run_gpu(inp, flags=flags)
     want = oracle_forward_chunked(inp, rows=rows, chunk=chunk)
     errs, elem = {}, {}
     for n in NAMES:

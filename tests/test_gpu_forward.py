@@ -83,6 +83,29 @@ def test_bf16_key_range_split(B, H, L):
         assert np.array_equal(got[0][n], got[1][n]) and np.array_equal(got[0][n], got[2][n]), n
 
 
+@pytest.mark.parametrize("cz,r", [(32, 1), (32, 2), (128, 1), (128, 2)])
+def test_bf16_wave_specialised_kernel(cz, r):
+    # the opt-in attention kernel with two waves per SIMD (FIPA_FLAG_WAVE_SPECIALISED): one to a few
+    # key blocks (the peeled start and end of its loop), whole tiles, ragged and masked chains, the
+    # reference raised late (spread geometry, far-apart i.i.d. geometry)
+    ws = binding.FIPA_FLAG_WAVE_SPECIALISED
+    for L in (20, 50, 97, 131, 300):
+        gu.check(wl.make_inputs(1, B=1, L=L, H=2, cz=cz, r=r), label="ws L=%d DZ=%d" % (L, cz * r), flags=ws)
+    gu.check(wl.make_inputs(1, B=3, L=600, H=3, cz=cz, r=r, varlen=True, min_len=30),
+             label="ws varlen DZ=%d" % (cz * r), flags=ws)
+    gu.check(wl.make_inputs(1, B=1, L=400, H=2, cz=cz, r=r, trans_scale=0.05), label="ws spread DZ=%d" % (cz * r), flags=ws)
+    gu.check(wl.make_inputs(1, B=1, L=256, H=4, cz=cz, r=r, chain=False), label="ws iid DZ=%d" % (cz * r), flags=ws)
+
+
+def test_bf16_wave_specialised_kernel_workload2_sampled_rows():
+    inp = wl.make_inputs(2)
+    rows = wl.select_rows(inp, 256)
+    gu.check(inp, rows=rows, label="cfg2 ws 256 rows", chunk=128, flags=binding.FIPA_FLAG_WAVE_SPECIALISED)
+    got = [gu.run_gpu(inp, flags=binding.FIPA_FLAG_WAVE_SPECIALISED) for _ in range(2)]
+    for n in gu.NAMES + ("lse",):
+        assert np.array_equal(got[0][n], got[1][n]), n
+
+
 def test_bf16_workload1_full():
     gu.check(wl.make_inputs(1), label="cfg1 bf16 full")
 
