@@ -159,6 +159,61 @@ def module_leg(workload, d_s=256, steps=300, warmup=100):
     return out
 
 
+def packed_leg(B=32, lo=64, hi=512, steps=100, warmup=30):
+    """Variable-length batch of short chains (lengths drawn as in the paper's protein training sets, Table 2:
+    up to 512 residues), stored back to back: fipa_forward_packed / fipa_backward_packed as one set of
+    launches, chain after chain, and the same chains padded to the longest with a mask through
+    fipa_forward / fipa_backward.  Opt-in (--packed-leg); not part of `value`."""
+    import numpy as np
+    import torch
+    from paper_2505_11580_amd import binding, workloads
+    inp = workloads.make_inputs(1, B=B, L=hi, varlen=True, min_len=lo, with_grads=True)
+    lengths = [int(x) for x in inp["lengths"]]
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    desc, dev = binding.upload(inp)
+    names = ("q", "k", "v", "q_pts", "k_pts", "v_pts", "rot", "trans", "z1", "z2")
+    pk = {n: torch.cat([dev[n][b, :ln] for b, ln in enumerate(lengths)], dim=0).contiguous()
+          for n in names + ("d_o", "d_o_pts", "d_o_pair")}
+    total, H = int(cu[-1]), desc.H
+    f = dict(dtype=torch.float32, device="cuda:0")
+    o = [torch.empty(total, H, desc.c, **f), torch.empty(total, H, desc.Pv, 3, **f), torch.empty(total, H, desc.cz, **f),
+         torch.empty(H * total, **f)]
+    g = [torch.empty_like(pk[n]) for n in ("q", "k", "v", "q_pts", "k_pts", "v_pts", "z1", "z2")]
+    g += [torch.empty(H, **f), torch.empty(H, desc.cz, **f), torch.empty(total, 3, 3, **f), torch.empty(total, 3, **f)]
+    out = binding.alloc_outputs(desc)
+    grads = binding.alloc_grads(desc)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    res = {"workload": "B=%d chains of %d..%d residues (total %d, longest %d), H=%d cz=%d r=%d, bf16"
+                       % (B, lo, hi, total, max(lengths), H, desc.cz, desc.r)}
+    for label, flags in (("one_launch", 0), ("per_chain", binding.FIPA_FLAG_PACKED_PER_CHAIN)):
+        desc.flags = flags
+        fwd_b, bwd_b = binding.packed_workspace_bytes(desc, cu)
+        ws = torch.empty(max(fwd_b, bwd_b, 16), dtype=torch.uint8, device="cuda:0")
+        fwd = timed(lambda: binding.fipa_forward_packed(desc, cu, *[pk[n] for n in names], dev["w_b"], dev["gamma"], None,
+                                                        o[0], o[1], o[2], o[3], ws))
+        bwd = timed(lambda: binding.fipa_backward_packed(desc, cu, *[pk[n] for n in names], dev["w_b"], dev["gamma"], None,
+                                                         pk["d_o"], pk["d_o_pts"], pk["d_o_pair"], *g, ws))
+        res[label] = {"forward_ms": fwd, "backward_ms": bwd, "forward_workspace_mb": fwd_b / 1e6,
+                      "backward_workspace_mb": bwd_b / 1e6}
+        del ws
+    desc.flags = 0
+    res["padded_with_mask"] = {"forward_ms": timed(lambda: binding.forward(desc, dev, out)),
+                               "backward_ms": timed(lambda: binding.backward(desc, dev, out, grads)),
+                               "forward_workspace_mb": binding.workspace_bytes(desc)[0] / 1e6,
+                               "backward_workspace_mb": binding.workspace_bytes(desc)[1] / 1e6}
+    return res
+
+
 def calibrate_copy(nbytes=256 << 20):
     """A plain elementwise copy of known size (reads nbytes, writes nbytes), so that a counter run of
     this script sees a kernel whose HBM traffic is known next to the attention kernel."""
@@ -198,6 +253,8 @@ def main():
                          "waves per SIMD); the JSON line says so in config.attention_kernel")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (same generators)")
     ap.add_argument("--seq-len", type=int, default=0, help="override the workload's sequence length (same generators)")
+    ap.add_argument("--packed-leg", action="store_true",
+                    help="also time a packed batch of 32 short chains (one launch / chain after chain / padded)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB copy kernel (for scaling hardware counters)")
     args = ap.parse_args()
@@ -298,6 +355,8 @@ def main():
         result["module"] = module_leg(args.workload)
     if not args.no_backward:
         result["backward"] = backward_leg(4)
+    if args.packed_leg:
+        result["packed"] = packed_leg()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, fpp)
     print(json.dumps(result), flush=True)

@@ -133,21 +133,36 @@ int fipa_forward_static(const fipa_desc *desc,
                         void *hip_stream);
 
 /*
- * Forward on a packed batch of chains of different lengths (the variable-length inputs of the
- * experiments in Section 3, without padding): the tensors of fipa_forward with the leading
- * [B, L] replaced by [total], total = cu_seqlens[B], chain b occupying rows cu_seqlens[b] ..
- * cu_seqlens[b+1] - 1; residues attend within their chain only.
- *   desc->B          number of chains;  desc->L  an upper bound of the chain lengths (sizes the
- *                    workspace: that of fipa_workspace_bytes for B = 1 and this L)
+ * Packed batches: chains of different lengths stored back to back (the variable-length inputs of
+ * the experiments in Section 3, without padding).  The tensors of fipa_forward / fipa_backward
+ * with the leading [B, L] replaced by [total], total = cu_seqlens[B], chain b occupying rows
+ * cu_seqlens[b] .. cu_seqlens[b+1] - 1; residues attend within their chain only.
+ *   desc->B          number of chains;  desc->L  an upper bound of the chain lengths
  *   cu_seqlens       HOST pointer, B + 1 int32, cu_seqlens[0] = 0, non-decreasing; a chain may be
- *                    empty; a chain longer than desc->L is FIPA_ERR_INVALID_ARG
+ *                    empty; a chain longer than desc->L is FIPA_ERR_INVALID_ARG.  Read during the
+ *                    call only.
  *   mask             [total] bytes or NULL
  *   lse              [H * total] float32 or NULL: chain b's block [H, len_b] starts at
  *                    H * cu_seqlens[b]
- * The chains are enqueued one after the other on the caller's stream (the kernels of
- * fipa_forward with B = 1 on offset pointers, sharing the workspace), so short chains fill the
- * chip less well than a padded batch of them would; nothing is computed for padding.
+ *   workspace        at least what fipa_packed_workspace_bytes reports for the same desc and
+ *                    cu_seqlens
+ * Two ways of running, chosen from the lengths alone (so the workspace query and the call agree):
+ *   - bf16, and padding every chain to the longest would at most double the 128-row tiles: ONE set
+ *     of launches over all chains -- the kernels of fipa_forward / fipa_backward reading and
+ *     writing the packed tensors through the row offsets, skipping query tiles and key blocks
+ *     past each chain's end.  Workspace: that of a padded batch of B chains of the longest length,
+ *     plus the offsets.  This is what fills the chip when chains are short or many.
+ *   - otherwise (one chain much longer than the rest; fp32 mode; or FIPA_FLAG_PACKED_PER_CHAIN in
+ *     desc->flags, which asks for the smallest workspace): chain after chain on the caller's
+ *     stream, as B = 1 problems on offset pointers sharing a workspace sized for the longest
+ *     chain; the backward adds the chains' d_gamma and d_w_b in chain order.
+ * Nothing is computed for padding either way.  fipa_backward_packed: bf16, r*cz <= 256; gradient
+ * tensors packed like their inputs, d_gamma [H] and d_w_b [H, cz] (or NULL) summed over all chains,
+ * d_rot / d_trans [total, 3, 3] / [total, 3] (both or neither).
  */
+#define FIPA_FLAG_PACKED_PER_CHAIN 2u
+int fipa_packed_workspace_bytes(const fipa_desc *desc, const int32_t *cu_seqlens,
+                                size_t *forward_bytes, size_t *backward_bytes);
 int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens,
                         const void *q, const void *k, const void *v,
                         const void *q_pts, const void *k_pts, const void *v_pts,
@@ -156,6 +171,18 @@ int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens,
                         const float *w_b, const float *gamma, const uint8_t *mask,
                         float *o, float *o_pts, float *o_pair, float *lse,
                         void *workspace, size_t workspace_bytes, void *hip_stream);
+int fipa_backward_packed(const fipa_desc *desc, const int32_t *cu_seqlens,
+                         const void *q, const void *k, const void *v,
+                         const void *q_pts, const void *k_pts, const void *v_pts,
+                         const float *rot, const float *trans,
+                         const void *z1, const void *z2,
+                         const float *w_b, const float *gamma, const uint8_t *mask,
+                         const float *d_o, const float *d_o_pts, const float *d_o_pair,
+                         void *d_q, void *d_k, void *d_v,
+                         void *d_q_pts, void *d_k_pts, void *d_v_pts,
+                         void *d_z1, void *d_z2, float *d_gamma, float *d_w_b,
+                         float *d_rot, float *d_trans,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three

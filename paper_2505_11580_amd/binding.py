@@ -23,9 +23,10 @@ FIPA_ERR_LAUNCH = -5
 FIPA_DTYPE_F32 = 0
 FIPA_DTYPE_BF16 = 1
 FIPA_FLAG_WAVE_SPECIALISED = 1  # desc.flags bit: opt-in attention kernel with two waves per SIMD
+FIPA_FLAG_PACKED_PER_CHAIN = 2  # desc.flags bit: packed batches run chain after chain (smallest workspace)
 
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
-           "fipa_forward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
+           "fipa_packed_workspace_bytes", "fipa_forward_packed", "fipa_backward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
            "fipa_module_backward_workspace_bytes", "fipa_module_backward",
            "fipa_profile_begin", "fipa_profile_begin_every", "fipa_profile_end", "fipa_probe_mfma")
 PROFILE_STAGES = 3
@@ -66,6 +67,11 @@ def lib():
         L.fipa_forward_static.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 17 + [vp]
         L.fipa_forward_packed.restype = ctypes.c_int
         L.fipa_forward_packed.argtypes = [ctypes.POINTER(FipaDesc), ctypes.POINTER(ctypes.c_int32)] + [vp] * 17 + [vp, sz, vp]
+        L.fipa_packed_workspace_bytes.restype = ctypes.c_int
+        L.fipa_packed_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.POINTER(ctypes.c_int32),
+                                                  ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.fipa_backward_packed.restype = ctypes.c_int
+        L.fipa_backward_packed.argtypes = [ctypes.POINTER(FipaDesc), ctypes.POINTER(ctypes.c_int32)] + [vp] * 28 + [vp, sz, vp]
         L.fipa_backward.restype = ctypes.c_int
         L.fipa_backward.argtypes = [ctypes.POINTER(FipaDesc)] + [vp] * 32 + [vp, sz, vp]
         L.fipa_module_workspace_bytes.restype = ctypes.c_int
@@ -153,6 +159,30 @@ def fipa_forward_packed(desc, cu_seqlens, q, k, v, q_pts, k_pts, v_pts, rot, tra
                                    ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
     if rc != FIPA_OK:
         raise FipaError(rc, "fipa_forward_packed")
+
+
+def packed_workspace_bytes(desc, cu_seqlens):
+    """(forward bytes, backward bytes) that the packed calls need for these chain lengths."""
+    cu = (ctypes.c_int32 * len(cu_seqlens))(*[int(x) for x in cu_seqlens])
+    fwd, bwd = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    rc = lib().fipa_packed_workspace_bytes(ctypes.byref(desc), cu, ctypes.byref(fwd), ctypes.byref(bwd))
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_packed_workspace_bytes")
+    return fwd.value, bwd.value
+
+
+def fipa_backward_packed(desc, cu_seqlens, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,
+                         d_o, d_o_pts, d_o_pair, d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2,
+                         d_gamma, d_w_b, d_rot, d_trans, workspace):
+    """Enqueue fipa_backward_packed: tensors with a leading [total] axis, `cu_seqlens` a host
+    sequence of B + 1 row offsets; d_w_b and (d_rot, d_trans) may be None."""
+    cu = (ctypes.c_int32 * len(cu_seqlens))(*[int(x) for x in cu_seqlens])
+    args = [q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask, d_o, d_o_pts, d_o_pair,
+            d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2, d_gamma, d_w_b, d_rot, d_trans]
+    rc = lib().fipa_backward_packed(ctypes.byref(desc), cu, *[_ptr(t) for t in args], _ptr(workspace),
+                                    ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_backward_packed")
 
 
 def fipa_backward(desc, q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask,

@@ -4,7 +4,7 @@
 
 using namespace fipa;
 
-namespace {
+namespace fipa {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -15,7 +15,7 @@ int check_desc(const fipa_desc *d, bool backward)
         d->r <= 0)
         return FIPA_ERR_INVALID_ARG;
     if (d->dtype != FIPA_DTYPE_F32 && d->dtype != FIPA_DTYPE_BF16) return FIPA_ERR_INVALID_ARG;
-    if ((d->flags & ~(uint32_t)FIPA_FLAG_WAVE_SPECIALISED) != 0) return FIPA_ERR_INVALID_ARG;
+    if ((d->flags & ~(uint32_t)(FIPA_FLAG_WAVE_SPECIALISED | FIPA_FLAG_PACKED_PER_CHAIN)) != 0) return FIPA_ERR_INVALID_ARG;
     if (!(d->w_L == d->w_L) || !(d->w_C == d->w_C) || !(d->qk_scale == d->qk_scale))
         return FIPA_ERR_INVALID_ARG;
     const long long DZ = (long long)d->r * d->cz;
@@ -33,10 +33,6 @@ int check_desc(const fipa_desc *d, bool backward)
     }
     return FIPA_OK;
 }
-
-}  // namespace
-
-namespace fipa {
 
 int check_forward_args(const fipa_desc *desc, const FwdArgs &a)
 {
@@ -106,55 +102,6 @@ int fipa_forward(const fipa_desc *desc, const void *q, const void *k, const void
     if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
     return enqueue_forward(*desc, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? FIPA_OK
                                                                                                   : FIPA_ERR_LAUNCH;
-}
-
-int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens, const void *q, const void *k, const void *v,
-                        const void *q_pts, const void *k_pts, const void *v_pts, const float *rot,
-                        const float *trans, const void *z1, const void *z2, const float *w_b,
-                        const float *gamma, const uint8_t *mask, float *o, float *o_pts, float *o_pair,
-                        float *lse, void *workspace, size_t workspace_bytes, void *hip_stream)
-{
-    int rc = check_desc(desc, false);
-    if (rc != FIPA_OK) return rc;
-    if (!cu_seqlens || cu_seqlens[0] != 0) return FIPA_ERR_INVALID_ARG;
-    for (int b = 0; b < desc->B; ++b) {
-        const long long len = (long long)cu_seqlens[b + 1] - cu_seqlens[b];
-        if (len < 0 || len > desc->L) return FIPA_ERR_INVALID_ARG;
-    }
-    const void *req[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, o, o_pts, o_pair, workspace};
-    for (const void *ptr : req)
-        if (!ptr) return FIPA_ERR_INVALID_ARG;
-    const void *al[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, o, o_pts, o_pair, lse, workspace};
-    for (const void *ptr : al)
-        if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
-    fipa_desc one = *desc;
-    one.B = 1;
-    size_t need = 0;
-    fipa_workspace_bytes(&one, &need, nullptr);  // (workspace sizes grow with L: the bound covers every chain)
-    if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
-
-    // bytes per residue of each tensor
-    const size_t es = desc->dtype == FIPA_DTYPE_F32 ? 4 : 2;
-    const size_t H = desc->H, n_s = H * desc->c, n_q = H * desc->Pq * 3, n_v = H * desc->Pv * 3,
-                 n_z = (size_t)desc->r * desc->cz;
-    auto at = [](const void *base, size_t row, size_t row_bytes) -> const void * {
-        return static_cast<const char *>(base) + row * row_bytes;
-    };
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    for (int b = 0; b < desc->B; ++b) {
-        const size_t r0 = (size_t)cu_seqlens[b];
-        one.L = cu_seqlens[b + 1] - cu_seqlens[b];
-        if (one.L == 0) continue;
-        FwdArgs a{at(q, r0, n_s * es), at(k, r0, n_s * es), at(v, r0, n_s * es),
-                  at(q_pts, r0, n_q * es), at(k_pts, r0, n_q * es), at(v_pts, r0, n_v * es),
-                  rot + r0 * 9, trans + r0 * 3, at(z1, r0, n_z * es), at(z2, r0, n_z * es), w_b, gamma,
-                  mask ? mask + r0 : nullptr,
-                  o + r0 * n_s, o_pts + r0 * n_v, o_pair + r0 * H * desc->cz, lse ? lse + r0 * H : nullptr};
-        const hipError_t e = desc->dtype == FIPA_DTYPE_F32 ? f32_forward(one, a, workspace, stream)
-                                                           : bf16_forward(one, a, workspace, stream);
-        if (e != hipSuccess) return FIPA_ERR_LAUNCH;
-    }
-    return FIPA_OK;
 }
 
 int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const void *v,

@@ -441,6 +441,9 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
     const int li = lane & 31, g = lane >> 5;
     // (without a mask every chain has L residues: no dependent load in front of everything else)
     const int kvlen = p.deal ? p.kvlen[b] : p.L;
+    // rows of this chain in the caller's tensors (a packed batch stores the chains back to back)
+    const int ulen = user_len(p, b);
+    const size_t urow0 = user_row(p, b, 0);
     const int nkb = (kvlen + kBlk - 1) / kBlk;      // key blocks of this chain
     const int irow = qt * kTileQ + wave * 32 + li;  // < Lp always
 
@@ -455,15 +458,15 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
                 for (int a = 0; a < 4; ++a)
                     *reinterpret_cast<f32x4 *>(orow + 32 * nb + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
             if (g == 0) p.lse2[(size_t)bh * p.Lp + irow] = -INFINITY;
-        } else if (irow < p.L && part == 0) {
-            const size_t row = ((size_t)b * p.L + irow) * p.H + (bh - b * p.H);
+        } else if (irow < ulen && part == 0) {
+            const size_t row = (urow0 + irow) * p.H + (bh - b * p.H);
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int a = 0; a < 2; ++a) *reinterpret_cast<f32x4 *>(p.o + row * 16 + 8 * a + 4 * g) = zero;
 #pragma unroll
             for (int a = 0; a < 3; ++a) *reinterpret_cast<f32x4 *>(p.o_pts + row * 24 + 12 * g + 4 * a) = zero;
             for (int d = 4 * g; d < p.cz; d += 8) *reinterpret_cast<f32x4 *>(p.o_pair + row * p.cz + d) = zero;
-            if (p.lse && g == 0) p.lse[(size_t)bh * p.L + irow] = 0.f;
+            if (p.lse && g == 0) p.lse[user_lse_index(p, b, bh - b * p.H, irow)] = 0.f;
         }
         return;
     }
@@ -591,12 +594,12 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             // below -- one chunk index across 32 rows -- spread over the banks.  The per-head
             // scale vector goes to LDS as well.
             constexpr int kRowBytes = DZ * 2, kWaveBytes = 32 * kRowBytes, kCpr = DZ / 8;
-            const char *zbase = reinterpret_cast<const char *>(p.z1 + (size_t)b * p.L * DZ);
+            const char *zbase = reinterpret_cast<const char *>(p.z1 + urow0 * DZ);
             const int row0 = qt * kTileQ + wave * 32;
 #pragma unroll
             for (int k = 0; k < kWaveBytes / 1024; ++k) {
                 const int slot = 64 * k + lane, r = slot / kCpr, c = (slot % kCpr) ^ (r % kCpr);
-                int voff = min(row0 + r, p.L - 1) * kRowBytes + 16 * c;
+                int voff = min(row0 + r, ulen - 1) * kRowBytes + 16 * c;
                 dma16<0>(zbase, voff, 0, smem_lds + C::Z1P_OFF + wave * kWaveBytes + 1024 * k);
             }
             if (tid < DZ)
@@ -636,7 +639,7 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             wg_barrier();
         if constexpr (FUSED) {
             // q^ pair part: bf16(scale[col] * z1[row, col]); rows that do not exist or are masked get 0
-            const bool ok = irow < p.L && (p.mask ? p.mask[(size_t)b * p.L + irow] != 0 : true);
+            const bool ok = irow < ulen && (p.mask ? p.mask[urow0 + irow] != 0 : true);
             const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
             const float *cw = reinterpret_cast<const float *>(smem + C::CW_OFF) + 8 * g;
             constexpr int kCpr = DZ / 8;
@@ -734,12 +737,12 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         const int room = min(C::NSTAGE - f0, 3) * C::STAGE;                // free bytes before the ring wraps
         const int n_head = min(4, room / kWaveBytes);                     // waves that fit there; the rest start at 0
         z1_off = wave < n_head ? f0 * C::STAGE + wave * kWaveBytes : (wave - n_head) * kWaveBytes;
-        const char *zbase = reinterpret_cast<const char *>(p.z1 + (size_t)b * p.L * DZ);
+        const char *zbase = reinterpret_cast<const char *>(p.z1 + urow0 * DZ);
         const int row0 = qt * kTileQ + wave * 32;
 #pragma unroll
         for (int k = 0; k < kWaveBytes / 1024; ++k) {
             const int slot = 64 * k + lane, r = slot / kCpr, c = (slot % kCpr) ^ (r % kCpr);
-            int voff = min(row0 + r, p.L - 1) * kRowBytes + 16 * c;
+            int voff = min(row0 + r, ulen - 1) * kRowBytes + 16 * c;
             dma16<0>(zbase, voff, 0, smem_lds + z1_off + 1024 * k);
         }
     }
@@ -787,8 +790,8 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         //   the scalar columns, the global points (hi + lo parts), and the contraction with z1.
         constexpr int c = 16, Pv = 8;
         constexpr int NZB = C::NB - C::NBH;  // 32-column blocks of the pair part
-        const bool in_range = irow < p.L;
-        const int irow_c = min(irow, p.L - 1);  // rows past the end compute on a valid address and store nothing
+        const bool in_range = irow < ulen;
+        const int irow_c = min(irow, ulen - 1);  // rows past the end compute on a valid address and store nothing
         const int cz = p.cz;
         const int bps = cz / 32;                // 32-column blocks per factor slice (cz >= 32)
         // point part: this half owns points 4g .. 4g+3, hi parts in slots u = 0..11, lo parts in
@@ -916,9 +919,9 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         const float lse2 = l_tot > 0.f ? w.m_ref + __log2f(l_tot) : -INFINITY;
         const int h = bh - b * p.H;
-        const bool valid = (p.mask ? p.mask[(size_t)b * p.L + irow_c] != 0 : true) && l_tot > 0.f;
+        const bool valid = (p.mask ? p.mask[urow0 + irow_c] != 0 : true) && l_tot > 0.f;
         const float sc = valid ? inv : 0.f;
-        const size_t row = ((size_t)b * p.L + irow_c) * p.H + h;
+        const size_t row = (urow0 + irow_c) * p.H + h;
         if (in_range) {
             // scalar part: columns 8a + 4g + x, a = 0, 1
 #pragma unroll
@@ -930,8 +933,8 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
             }
         }
         {
-            const float *R = p.rot + ((size_t)b * p.L + irow_c) * 9;
-            const float *tr = p.trans + ((size_t)b * p.L + irow_c) * 3;
+            const float *R = p.rot + (urow0 + irow_c) * 9;
+            const float *tr = p.trans + (urow0 + irow_c) * 3;
             float Rm[9], tc[3];
 #pragma unroll
             for (int a = 0; a < 9; ++a) Rm[a] = R[a];
@@ -989,7 +992,7 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_bf16_kernel(AttnParams p
                 }
             }
             if (p.lse && g == 0)
-                p.lse[(size_t)bh * p.L + irow] = valid ? lse2 * kLn2 - p.qbias[(size_t)bh * p.Lp + irow] : 0.f;
+                p.lse[user_lse_index(p, b, h, irow)] = valid ? lse2 * kLn2 - p.qbias[(size_t)bh * p.Lp + irow] : 0.f;
         }
     }
 }

@@ -378,9 +378,11 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
             float *cw = reinterpret_cast<float *>(smem + C::CW_OFF);
             for (int x = tid; x < DZ; x += 256) cw[x] = kLog2e * p.w_L * p.w_b[(size_t)(bh - b * p.H) * p.cz + x % p.cz];
             __syncthreads();
-            const bool ok = irow < p.L && (p.mask ? p.mask[(size_t)b * p.L + irow] != 0 : true);
+            const int ulen = user_len(p, b);
+            const size_t urow0 = user_row(p, b, 0);  // (a packed batch stores the chains back to back)
+            const bool ok = irow < ulen && (p.mask ? p.mask[urow0 + irow] != 0 : true);
             const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
-            const bf16_t *z1row = p.z1 + ((size_t)b * p.L + min(irow, p.L - 1)) * DZ + 8 * g;
+            const bf16_t *z1row = p.z1 + (urow0 + min(irow, ulen - 1)) * DZ + 8 * g;
 #pragma unroll
             for (int ks = 0; ks < C::KS - C::KSH; ++ks) {
                 const uint4 zr = *reinterpret_cast<const uint4 *>(z1row + 16 * ks);

@@ -21,9 +21,10 @@ __global__ __launch_bounds__(256) void fipa_bwd_pack_bf16_kernel(BwdPackParams p
     const size_t bh = row_id / p.Lp;
     const int h = (int)(bh % p.H), b = (int)(bh / p.H);
     const int c = p.c, D = kDH + p.DZ, PH = (p.Pv + 1) / 2;
-    const bool valid = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
-    const size_t rec = valid ? ((size_t)b * p.L + i) * p.H + h : 0;
-    const float *R = p.rot + (valid ? ((size_t)b * p.L + i) * 9 : 0);
+    const size_t urow = user_row(p, b, i);  // (only used where i < the chain's length)
+    const bool valid = i < user_len(p, b) && (p.mask ? p.mask[urow] != 0 : true);
+    const size_t rec = valid ? urow * p.H + h : 0;
+    const float *R = p.rot + (valid ? urow * 9 : 0);
     const float *oh = p.Ohat + row_id * D;
     bf16_t *dst = p.dOhat + row_id * D;
     float dsum = 0.f;
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(256) void fipa_bwd_pack_bf16_kernel(BwdPackParams p
                 }
             } else {
                 const int x = col - kDH;
-                val = bf2f(p.z1[((size_t)b * p.L + i) * p.DZ + x]) * p.d_o_pair[rec * p.cz + x % p.cz];
+                val = bf2f(p.z1[urow * p.DZ + x]) * p.d_o_pair[rec * p.cz + x % p.cz];
             }
         }
         const bf16_t bv = f2bf(val);
@@ -66,9 +67,11 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
     const int b = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
     const int c = p.c, Pq = p.Pq, Pv = p.Pv, nq = 3 * Pq, D = kDH + p.DZ;
     const int NTASK = 2 * Pq + Pv + 3;
-    const bool valid = p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true;
-    const float *R = p.rot + ((size_t)b * p.L + i) * 9;
-    const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+    if (i >= user_len(p, b)) return;  // (packed batch: the grid covers the longest chain)
+    const size_t urow = user_row(p, b, i);
+    const bool valid = p.mask ? p.mask[urow] != 0 : true;
+    const float *R = p.rot + urow * 9;
+    const float *t = p.trans + urow * 3;
     float Rm[9], tc[3];
     for (int a = 0; a < 9; ++a) Rm[a] = R[a];
     for (int a = 0; a < 3; ++a) tc[a] = t[a] - p.cen[4 * b + a];
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
         const int h = active ? h0 + hl : 0, tk = active ? tid - hl * NTASK : 0;
         if (active) {
             const size_t bh = (size_t)b * p.H + h;
-            const size_t rec = ((size_t)b * p.L + i) * p.H + h;
+            const size_t rec = urow * p.H + h;
             const float *dQ = p.dQhat + (bh * p.Lp + i) * D;
             const float *dK = p.dKhat + (bh * p.Lp + i) * D;
             const float *dV = p.dVhat + (bh * p.Lp + i) * D;
@@ -183,8 +186,8 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
                 for (int x = 0; x < 12; ++x) fsm[x][tid] += fsm[x][tid + st];
             __syncthreads();
         }
-        if (tid < 3) p.d_trans[((size_t)b * p.L + i) * 3 + tid] = valid ? fsm[tid][0] : 0.f;
-        if (tid < 9) p.d_rot[((size_t)b * p.L + i) * 9 + tid] = valid ? fsm[3 + tid][0] : 0.f;
+        if (tid < 3) p.d_trans[urow * 3 + tid] = valid ? fsm[tid][0] : 0.f;
+        if (tid < 9) p.d_rot[urow * 9 + tid] = valid ? fsm[3 + tid][0] : 0.f;
     }
 
     // pair factors: sums over heads.  A thread takes four neighbouring lifted columns (16-byte loads
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
         for (int h = hg; h < p.H; h += HG) {
             const size_t bh = (size_t)b * p.H + h;
             const size_t row = (bh * p.Lp + i) * D + kDH + x0;
-            const size_t rec = ((size_t)b * p.L + i) * p.H + h;
+            const size_t rec = urow * p.H + h;
             const f32x4 dq = *reinterpret_cast<const f32x4 *>(p.dQhat + row);
             const f32x4 dk = *reinterpret_cast<const f32x4 *>(p.dKhat + row);
             const f32x4 dv = *reinterpret_cast<const f32x4 *>(p.dVhat + row);
@@ -225,21 +228,24 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
                 t1 += zsm[0][g * p.DZ + x];
                 t2 += zsm[1][g * p.DZ + x];
             }
-            p.d_z1[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? t1 : 0.f);
-            p.d_z2[((size_t)b * p.L + i) * p.DZ + x] = f2bf(valid ? t2 : 0.f);
+            p.d_z1[urow * p.DZ + x] = f2bf(valid ? t1 : 0.f);
+            p.d_z2[urow * p.DZ + x] = f2bf(valid ? t2 : 0.f);
         }
     }
 }
 
 // d gamma^h = -(w_L w_C / 2) * sum over (batch, residue) of the partial sums, in a fixed order.
+// (cu: row offsets of a packed batch, whose chain b has cu[b+1] - cu[b] residues, or null.)
 __global__ __launch_bounds__(256) void fipa_bwd_gamma_kernel(const float *gpart, float *d_gamma, int B, int H,
-                                                             int L, int Lp, float coef)
+                                                             int L, int Lp, const int *cu, float coef)
 {
     __shared__ float red[256];
     const int h = blockIdx.x, tid = threadIdx.x;
     float s = 0.f;
-    for (int b = 0; b < B; ++b)
-        for (int i = tid; i < L; i += 256) s += gpart[((size_t)b * H + h) * Lp + i];
+    for (int b = 0; b < B; ++b) {
+        const int len = cu ? cu[b + 1] - cu[b] : L;
+        for (int i = tid; i < len; i += 256) s += gpart[((size_t)b * H + h) * Lp + i];
+    }
     red[tid] = s;
     __syncthreads();
     for (int st = 128; st > 0; st >>= 1) {
@@ -258,14 +264,26 @@ constexpr int kWbChunk = 32;
 __global__ __launch_bounds__(256) void fipa_bwd_wb_partial_kernel(BwdUnpackParams p)
 {
     const int h = blockIdx.y, chunk = blockIdx.x, D = kDH + p.DZ;
-    const int nres = p.B * p.L;
+    const int nres = p.total_rows;  // rows of the caller's tensors: B L, or the packed batch's total
     for (int x = threadIdx.x; x < p.DZ; x += 256) {
         float s4[4] = {0.f, 0.f, 0.f, 0.f};  // four independent chains of loads; summed in a fixed order
         for (int t0 = 0; t0 < kWbChunk; t0 += 4) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int bi = min(chunk * kWbChunk + t0 + u, nres - 1);
-                const int b = bi / p.L, i = bi - b * p.L;
+                int b, i;
+                if (p.cu) {  // the chain that holds row bi: last b with cu[b] <= bi
+                    int lo = 0, hi = p.B - 1;
+                    while (lo < hi) {
+                        const int mid = (lo + hi + 1) >> 1;
+                        if (p.cu[mid] <= bi) lo = mid; else hi = mid - 1;
+                    }
+                    b = lo;
+                    i = bi - p.cu[b];
+                } else {
+                    b = bi / p.L;
+                    i = bi - b * p.L;
+                }
                 const bool valid = chunk * kWbChunk + t0 + u < nres && (p.mask ? p.mask[bi] != 0 : true);
                 const float prod = bf2f(p.z1[(size_t)bi * p.DZ + x]) * p.dQhat[(((size_t)b * p.H + h) * p.Lp + i) * D + kDH + x];
                 s4[u] += valid ? prod : 0.f;
@@ -346,9 +364,9 @@ hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fipa_bwd_gamma_kernel, dim3(p.H), dim3(256), 0, stream, p.gpart, p.d_gamma, p.B, p.H, p.L,
-                       p.Lp, -0.5f * p.w_L * p.w_C);
+                       p.Lp, p.cu, -0.5f * p.w_L * p.w_C);
     if (p.d_w_b) {
-        const int nchunk = (p.B * p.L + kWbChunk - 1) / kWbChunk;
+        const int nchunk = (p.total_rows + kWbChunk - 1) / kWbChunk;
         hipLaunchKernelGGL(fipa_bwd_wb_partial_kernel, dim3(nchunk, p.H), dim3(256), 0, stream, p);
         hipLaunchKernelGGL(fipa_bwd_wb_reduce_kernel, dim3(p.H), dim3(256), 0, stream, p, nchunk);
     }
@@ -368,7 +386,7 @@ PackParams bwd_pack_params(const fipa_desc &d, const FwdArgs &f, const BwdLayout
     pk.z1 = (const bf16_t *)f.z1; pk.z2 = (const bf16_t *)f.z2;
     pk.rot = f.rot; pk.trans = f.trans; pk.w_b = f.w_b; pk.gamma = f.gamma;
     pk.cen = reinterpret_cast<float *>(base + w.f.cen);
-    pk.mask = f.mask;
+    pk.mask = f.mask; pk.cu = f.cu;
     pk.Qh = (bf16_t *)(base + w.f.Qh); pk.Qz = (bf16_t *)(base + w.f.Qz);
     pk.Kh = (bf16_t *)(base + w.f.Kh); pk.Vh = (bf16_t *)(base + w.f.Vh); pk.Z2 = (bf16_t *)(base + w.f.Z2);
     pk.kbias = (float *)(base + w.f.kbias); pk.qbias = (float *)(base + w.f.qbias);
@@ -386,7 +404,7 @@ hipError_t backward_forward_part(const fipa_desc &d, const FwdArgs &f, const Bwd
 {
     float *cen = reinterpret_cast<float *>(base + w.f.cen);
     int *kvlen = reinterpret_cast<int *>(base + w.f.kvlen);
-    hipError_t e = launch_prep(d, f.trans, f.mask, cen, kvlen, nullptr, 0, stream);
+    hipError_t e = launch_prep(d, f.trans, f.mask, f.cu, cen, kvlen, nullptr, 0, stream);
     if (e != hipSuccess) return e;
     const PackParams pk = bwd_pack_params(d, f, w, base);
     e = launch_pack_bf16(pk, stream);
@@ -396,18 +414,18 @@ hipError_t backward_forward_part(const fipa_desc &d, const FwdArgs &f, const Bwd
     at.Qh = pk.Qh; at.Qz = pk.Qz; at.Kh = pk.Kh; at.Vh = pk.Vh; at.Z2 = pk.Z2;
     at.kbias = pk.kbias; at.qbias = pk.qbias; at.kvlen = kvlen;
     at.Ohat = (float *)(base + w.f.Ohat); at.lse2 = (float *)(base + w.f.lse2);
-    at.rot = f.rot; at.trans = f.trans; at.cen = cen; at.z1 = pk.z1; at.mask = f.mask;
+    at.rot = f.rot; at.trans = f.trans; at.cen = cen; at.z1 = pk.z1; at.mask = f.mask; at.cu = f.cu;
     at.o = nullptr; at.o_pts = nullptr; at.o_pair = nullptr; at.lse = nullptr;
     at.B = d.B; at.L = d.L; at.Lp = w.f.Lp; at.H = d.H; at.NT = w.f.NT;
     at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = f.w_b; at.w_L = d.w_L;
     at.plan = w.f.plan; at.partial = nullptr; at.counters = nullptr;  // (unfused: never split)
-    at.deal = f.mask != nullptr;
+    at.deal = f.mask != nullptr || f.cu != nullptr;
     e = launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
     if (e != hipSuccess || !f.o) return e;
 
     EpiParams ep;
     ep.Ohat = at.Ohat; ep.lse2 = at.lse2; ep.qbias = pk.qbias; ep.rot = f.rot; ep.trans = f.trans;
-    ep.cen = cen; ep.z1 = pk.z1; ep.mask = f.mask;
+    ep.cen = cen; ep.z1 = pk.z1; ep.mask = f.mask; ep.cu = f.cu;
     ep.o = f.o; ep.o_pts = f.o_pts; ep.o_pair = f.o_pair; ep.lse = f.lse;
     ep.B = d.B; ep.L = d.L; ep.Lp = w.f.Lp; ep.H = d.H; ep.c = d.c; ep.Pv = d.Pv; ep.cz = d.cz;
     ep.r = d.r; ep.DZ = w.f.DZ;
@@ -419,6 +437,7 @@ hipError_t backward_forward_part(const fipa_desc &d, const FwdArgs &f, const Bwd
 hipError_t backward_gradient_part(const fipa_desc &d, const BwdArgs &a, const BwdLayout &w, char *base, hipStream_t stream,
                                   StageTimer &timer)
 {
+    const int total_rows = a.f.cu ? a.f.total_rows : d.B * d.L;  // rows of the caller's tensors
     float *cen = reinterpret_cast<float *>(base + w.f.cen);
     int *kvlen = reinterpret_cast<int *>(base + w.f.kvlen);
     const PackParams pk = bwd_pack_params(d, a.f, w, base);
@@ -426,7 +445,7 @@ hipError_t backward_gradient_part(const fipa_desc &d, const BwdArgs &a, const Bw
 
     BwdPackParams bp;
     bp.d_o = a.d_o; bp.d_o_pts = a.d_o_pts; bp.d_o_pair = a.d_o_pair; bp.rot = a.f.rot;
-    bp.Ohat = Ohat; bp.lse2 = (float *)(base + w.f.lse2); bp.z1 = pk.z1; bp.mask = a.f.mask;
+    bp.Ohat = Ohat; bp.lse2 = (float *)(base + w.f.lse2); bp.z1 = pk.z1; bp.mask = a.f.mask; bp.cu = a.f.cu;
     bp.dOhat = (bf16_t *)(base + w.dOhat); bp.Dvec = (float *)(base + w.Dvec); bp.nlse = (float *)(base + w.nlse);
     bp.B = d.B; bp.L = d.L; bp.Lp = w.f.Lp; bp.H = d.H; bp.c = d.c; bp.Pv = d.Pv; bp.cz = d.cz; bp.r = d.r;
     bp.DZ = w.f.DZ;
@@ -440,7 +459,7 @@ hipError_t backward_gradient_part(const fipa_desc &d, const BwdArgs &a, const Bw
     bw.Qh = pk.Qh; bw.Qz = pk.Qz; bw.Kh = pk.Kh; bw.Vh = pk.Vh; bw.Z2 = pk.Z2; bw.dOhat = bp.dOhat;
     bw.kbias = pk.kbias; bw.nlse = bp.nlse; bw.Dvec = bp.Dvec; bw.kvlen = kvlen;
     bw.B = d.B; bw.L = d.L; bw.Lp = w.f.Lp; bw.H = d.H; bw.total_tiles = (w.f.Lp / kTileQ) * d.B * d.H;
-    bw.deal = a.f.mask != nullptr;
+    bw.deal = a.f.mask != nullptr || a.f.cu != nullptr;
     bw.out = (float *)(base + w.dQhat); bw.wsum = (float *)(base + w.rowsum);
     e = launch_bwd_bf16(bw, w.f.DZ, FIPA_BWD_DQ, stream);
     if (e != hipSuccess) return e;
@@ -458,7 +477,8 @@ hipError_t backward_gradient_part(const fipa_desc &d, const BwdArgs &a, const Bw
     up.q_pts = pk.q_pts; up.k_pts = pk.k_pts; up.v_pts = pk.v_pts; up.z1 = pk.z1;
     up.d_o_pts = a.d_o_pts; up.d_rot = a.d_rot; up.d_trans = a.d_trans; up.dOhat = bp.dOhat;
     up.rot = a.f.rot; up.trans = a.f.trans; up.cen = cen; up.gamma = a.f.gamma; up.w_b = a.f.w_b;
-    up.d_o_pair = a.d_o_pair; up.mask = a.f.mask;
+    up.d_o_pair = a.d_o_pair; up.mask = a.f.mask; up.cu = a.f.cu;
+    up.total_rows = total_rows;
     up.dQhat = (const float *)(base + w.dQhat); up.dKhat = (const float *)(base + w.dKhat);
     up.dVhat = (const float *)(base + w.dVhat); up.Ohat = Ohat;
     up.rowsum = (const float *)(base + w.rowsum); up.colsum = (const float *)(base + w.colsum);

@@ -50,6 +50,27 @@ __host__ __device__ __forceinline__ int v_cols_needed(int c, int Pv)
     return c + 8 * ((6 * PH + 3) / 4);
 }
 
+// Rows of the caller's tensors.  A padded batch keeps residue i of batch element b at row b L + i and
+// every element has L residues; a packed batch (p.cu set: B + 1 row offsets in device memory, the
+// variable-length batches of Section 3 stored back to back) keeps chain b at rows cu[b] .. cu[b+1] - 1.
+// The workspace is laid out [B, .., Lp, ..] either way, Lp covering the longest chain.
+template <class P>
+__device__ __forceinline__ size_t user_row(const P &p, int b, int i)
+{
+    return p.cu ? (size_t)(p.cu[b] + i) : (size_t)b * p.L + i;
+}
+template <class P>
+__device__ __forceinline__ int user_len(const P &p, int b)
+{
+    return p.cu ? p.cu[b + 1] - p.cu[b] : p.L;
+}
+// Element (b, h, i) of the log-sum-exp output: [B, H, L], or chain b's [H, len_b] block at H cu[b].
+template <class P>
+__device__ __forceinline__ size_t user_lse_index(const P &p, int b, int h, int i)
+{
+    return p.cu ? (size_t)p.cu[b] * p.H + (size_t)h * (p.cu[b + 1] - p.cu[b]) + i : ((size_t)b * p.H + h) * p.L + i;
+}
+
 // Key-range split of the fused attention launch.  A launch of T query tiles runs in ceil(T/256)
 // rounds on the 256 compute units of the chip; when the last round would be at most half full,
 // its tiles are cut into S parts along the key axis (each part one workgroup), so that the last
@@ -183,6 +204,7 @@ struct PackParams {
     const bf16_t *q, *k, *v, *q_pts, *k_pts, *v_pts, *z1, *z2;
     const float *rot, *trans, *w_b, *gamma, *cen;
     const uint8_t *mask;
+    const int *cu;  // packed batch: row offsets of the chains (see user_row), else null
     bf16_t *Qh, *Qz, *Kh, *Vh, *Z2;
     float *kbias, *qbias;
     int B, L, Lp, NT, H, c, Pq, Pv, cz, r, DZ;
@@ -206,6 +228,7 @@ struct AttnParams {
     const float *rot, *trans, *cen, *w_b;
     const bf16_t *z1;
     const uint8_t *mask;
+    const int *cu;  // packed batch: row offsets of the chains (see user_row), else null
     float *o, *o_pts, *o_pair, *lse;
     int B, L, Lp, H, NT, nQT, total_tiles, cz, r;
     int deal;  // set for masked batches: chain lengths come from kvlen, and the (batch, head) pairs are renumbered (see dealt_pair_by_length)
@@ -223,6 +246,7 @@ struct EpiParams {
     const float *Ohat, *lse2, *qbias, *rot, *trans, *cen;
     const bf16_t *z1;
     const uint8_t *mask;
+    const int *cu;  // packed batch: row offsets of the chains (see user_row), else null
     float *o, *o_pts, *o_pair, *lse;
     int B, L, Lp, H, c, Pv, cz, r, DZ;
 };
@@ -246,6 +270,7 @@ struct BwdPackParams {
     const float *d_o, *d_o_pts, *d_o_pair, *rot, *Ohat, *lse2;
     const bf16_t *z1;
     const uint8_t *mask;
+    const int *cu;  // packed batch: row offsets of the chains (see user_row), else null
     bf16_t *dOhat;
     float *Dvec, *nlse;
     int B, L, Lp, H, c, Pv, cz, r, DZ;
@@ -255,6 +280,7 @@ struct BwdUnpackParams {
     const bf16_t *q_pts, *k_pts, *v_pts, *z1, *dOhat;
     const float *rot, *trans, *cen, *gamma, *w_b, *d_o_pair, *d_o_pts;
     const uint8_t *mask;
+    const int *cu;  // packed batch: row offsets of the chains (see user_row), else null
     const float *dQhat, *dKhat, *dVhat, *Ohat, *rowsum, *colsum;
     bf16_t *d_q, *d_k, *d_v, *d_q_pts, *d_k_pts, *d_v_pts, *d_z1, *d_z2;
     float *gpart;   // [B,H,Lp] per-(b,h,i) contribution to d gamma
@@ -263,6 +289,7 @@ struct BwdUnpackParams {
     float *d_rot, *d_trans;  // [B, L, 3, 3], [B, L, 3] or null
     float *wpart;   // [H, ceil(B*L/32), DZ] partial sums of d w_b
     int B, L, Lp, H, c, Pq, Pv, cz, r, DZ;
+    int total_rows;  // rows of the caller's tensors: B L, or the total of a packed batch
     float w_L, w_C, qk_scale;
 };
 

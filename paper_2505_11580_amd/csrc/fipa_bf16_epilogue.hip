@@ -9,24 +9,27 @@ namespace {
 __global__ __launch_bounds__(256) void fipa_epilogue_bf16_kernel(EpiParams p)
 {
     const int lane = threadIdx.x & 63;
-    const size_t row_id = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // over B*L*H, h fastest
-    if (row_id >= (size_t)p.B * p.L * p.H) return;
-    const int h = (int)(row_id % p.H);
-    const size_t bi = row_id / p.H;
+    const size_t grid_id = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // over B*L*H, h fastest
+    if (grid_id >= (size_t)p.B * p.L * p.H) return;
+    const int h = (int)(grid_id % p.H);
+    const size_t bi = grid_id / p.H;
     const int i = (int)(bi % p.L);
     const int b = (int)(bi / p.L);
+    if (i >= user_len(p, b)) return;  // (packed batch: L is only an upper bound of the chain lengths)
+    const size_t urow = user_row(p, b, i);
+    const size_t row_id = urow * p.H + h;  // row of the outputs
     const int c = p.c, nv = 3 * p.Pv, DV = kDH + p.DZ;
     const size_t bh = (size_t)b * p.H + h;
     const float *oh = p.Ohat + (bh * p.Lp + i) * DV;
-    const bool valid = p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true;
+    const bool valid = p.mask ? p.mask[urow] != 0 : true;
 
     // (c and c_z are multiples of 8 on this path: 16-byte accesses throughout)
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     for (int d = 4 * lane; d < c; d += 256)
         *reinterpret_cast<f32x4 *>(p.o + row_id * c + d) = valid ? *reinterpret_cast<const f32x4 *>(oh + d) : zero4;
 
-    const float *R = p.rot + ((size_t)b * p.L + i) * 9;
-    const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+    const float *R = p.rot + urow * 9;
+    const float *t = p.trans + urow * 3;
     for (int idx = lane; idx < nv; idx += 64) {
         const int pp = idx / 3, x = idx - 3 * pp;
         float val = 0.f;
@@ -39,7 +42,7 @@ __global__ __launch_bounds__(256) void fipa_epilogue_bf16_kernel(EpiParams p)
         p.o_pts[row_id * nv + idx] = val;
     }
 
-    const bf16_t *z1 = p.z1 + ((size_t)b * p.L + i) * p.DZ;
+    const bf16_t *z1 = p.z1 + urow * p.DZ;
     for (int d = 4 * lane; d < p.cz; d += 256) {
         f32x4 val = zero4;
         if (valid)
@@ -58,7 +61,7 @@ __global__ __launch_bounds__(256) void fipa_epilogue_bf16_kernel(EpiParams p)
     // per-query |Q|^2 term that was left out of the logits
     if (p.lse && lane == 0) {
         const float l2 = p.lse2[bh * p.Lp + i];
-        p.lse[bh * p.L + i] = (valid && l2 > -INFINITY) ? l2 * kLn2 - p.qbias[bh * p.Lp + i] : 0.f;
+        p.lse[user_lse_index(p, b, h, i)] = (valid && l2 > -INFINITY) ? l2 * kLn2 - p.qbias[bh * p.Lp + i] : 0.f;
     }
 }
 

@@ -21,7 +21,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     const bool prep_in_pack = d.c == 16 && d.Pq == 4 && d.Pv == 8;
     hipError_t e = hipSuccess;
     if (!prep_in_pack) {
-        e = launch_prep(d, a.trans, a.mask, cen, kvlen, counters, n_counters, stream);
+        e = launch_prep(d, a.trans, a.mask, a.cu, cen, kvlen, counters, n_counters, stream);
         if (e != hipSuccess) return e;
     }
 
@@ -31,7 +31,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     pk.v_pts = (const bf16_t *)a.v_pts;
     pk.z1 = (const bf16_t *)a.z1; pk.z2 = (const bf16_t *)a.z2;
     pk.rot = a.rot; pk.trans = a.trans; pk.w_b = a.w_b; pk.gamma = a.gamma; pk.cen = cen;
-    pk.mask = a.mask;
+    pk.mask = a.mask; pk.cu = a.cu;
     pk.Qh = (bf16_t *)(base + w.Qh); pk.Qz = (bf16_t *)(base + w.Qz);
     pk.Kh = (bf16_t *)(base + w.Kh); pk.Z2 = (bf16_t *)(base + w.Z2);
     pk.Vh = (bf16_t *)(base + w.Vh);
@@ -50,16 +50,16 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     at.kbias = pk.kbias; at.qbias = pk.qbias; at.kvlen = kvlen;
     at.Ohat = fused ? nullptr : (float *)(base + w.Ohat);
     at.lse2 = (float *)(base + w.lse2);
-    at.rot = a.rot; at.trans = a.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.mask;
+    at.rot = a.rot; at.trans = a.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.mask; at.cu = a.cu;
     at.o = a.o; at.o_pts = a.o_pts; at.o_pair = a.o_pair; at.lse = a.lse;
     at.B = d.B; at.L = d.L; at.Lp = w.Lp; at.H = d.H; at.NT = w.NT;
     at.nQT = w.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = a.w_b; at.w_L = d.w_L;
     at.plan = w.plan; at.partial = (float *)(base + w.partial); at.counters = counters;
-    at.deal = a.mask != nullptr;
+    at.deal = a.mask != nullptr || a.cu != nullptr;  // chains of different lengths
     at.ws_base = base;
     // (the wave-specialised kernel is an opt-in variant: it measured slower than the default on every shape tried)
     const bool ws_kernel = (d.flags & FIPA_FLAG_WAVE_SPECIALISED) && fused && attn_fwd_ws_supported(w.DZ, d.cz) &&
-                           w.total < (1ull << 32);
+                           w.total < (1ull << 32) && !a.cu;
     timer.begin(1);
     e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream)
         : ws_kernel ? launch_attn_fwd_ws_bf16(at, w.DZ, stream)
@@ -70,7 +70,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
 
     EpiParams ep;
     ep.Ohat = at.Ohat; ep.lse2 = at.lse2; ep.qbias = pk.qbias; ep.rot = a.rot; ep.trans = a.trans;
-    ep.cen = cen; ep.z1 = pk.z1; ep.mask = a.mask;
+    ep.cen = cen; ep.z1 = pk.z1; ep.mask = a.mask; ep.cu = a.cu;
     ep.o = a.o; ep.o_pts = a.o_pts; ep.o_pair = a.o_pair; ep.lse = a.lse;
     ep.B = d.B; ep.L = d.L; ep.Lp = w.Lp; ep.H = d.H; ep.c = d.c; ep.Pv = d.Pv; ep.cz = d.cz;
     ep.r = d.r; ep.DZ = w.DZ;

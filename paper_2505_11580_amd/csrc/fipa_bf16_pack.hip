@@ -27,15 +27,16 @@ __global__ __launch_bounds__(256) void fipa_pack_heads_bf16_kernel(PackParams p)
         rk[x] = 0;
         rv[x] = 0;
     }
-    const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    const size_t urow = user_row(p, b, i);  // (only used where i < the chain's length)
+    const bool ok = i < user_len(p, b) && (p.mask ? p.mask[urow] != 0 : true);
     float kb = -INFINITY, qb = 0.f;
     if (ok) {
-        const float *R = p.rot + ((size_t)b * p.L + i) * 9;
-        const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+        const float *R = p.rot + urow * 9;
+        const float *t = p.trans + urow * 3;
         float Rm[9], tc[3];
         for (int a = 0; a < 9; ++a) Rm[a] = R[a];
         for (int a = 0; a < 3; ++a) tc[a] = t[a] - p.cen[4 * b + a];
-        const size_t row = ((size_t)b * p.L + i) * p.H + h;
+        const size_t row = urow * p.H + h;
         const float pscale = p.gamma[h] * p.w_L * p.w_C;  // weight of Q.K in the expanded distance
         const float kscale = kLog2e * pscale;
         const float sscale = kLog2e * p.w_L * p.qk_scale;
@@ -112,9 +113,10 @@ __device__ __forceinline__ void pack_z2_chunk(const PackParams &p, size_t idx)
     const int cc = (int)(idx % cpr);
     const size_t bi = idx / cpr;
     const int i = (int)(bi % p.Lp), b = (int)(bi / p.Lp);
-    const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    const size_t urow = user_row(p, b, i);
+    const bool ok = i < user_len(p, b) && (p.mask ? p.mask[urow] != 0 : true);
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (ok) val = *reinterpret_cast<const uint4 *>(p.z2 + ((size_t)b * p.L + i) * p.DZ + cc * 8);
+    if (ok) val = *reinterpret_cast<const uint4 *>(p.z2 + urow * p.DZ + cc * 8);
     *reinterpret_cast<uint4 *>(p.Z2 + ((size_t)b * p.Lp + i) * p.DZ + cc * 8) = val;
 }
 
@@ -136,11 +138,12 @@ __global__ __launch_bounds__(256) void fipa_pack_qz_bf16_kernel(PackParams p)
     const int i = (int)(rest % p.Lp);
     rest /= p.Lp;
     const int h = (int)(rest % p.H), b = (int)(rest / p.H);
-    const bool ok = i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    const size_t urow = user_row(p, b, i);
+    const bool ok = i < user_len(p, b) && (p.mask ? p.mask[urow] != 0 : true);
     __attribute__((aligned(16))) bf16_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (ok) {
         const float bscale = kLog2e * p.w_L;
-        const uint4 val = *reinterpret_cast<const uint4 *>(p.z1 + ((size_t)b * p.L + i) * p.DZ + cc * 8);
+        const uint4 val = *reinterpret_cast<const uint4 *>(p.z1 + urow * p.DZ + cc * 8);
         const bf16_t *e = reinterpret_cast<const bf16_t *>(&val);
         const int col0 = (cc * 8) % p.cz;  // cz is a multiple of 8: the chunk stays inside one factor slice
         const float *wb = p.w_b + (size_t)h * p.cz + col0;
@@ -164,20 +167,21 @@ __device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i,
 {
     constexpr int c = 16, Pq = 4, Pv = 8;
     const size_t bh = (size_t)b * p.H + h;
-    const bool ok = active && i < p.L && (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true);
+    const size_t urow = user_row(p, b, i);
+    const bool ok = active && i < user_len(p, b) && (p.mask ? p.mask[urow] != 0 : true);
     __attribute__((aligned(16))) bf16_t row[kDH];
 #pragma unroll
     for (int x = 0; x < kDH; ++x) row[x] = 0;
     float bias = ROLE == 1 ? -INFINITY : 0.f;
     if (ok) {
-        const float *R = p.rot + ((size_t)b * p.L + i) * 9;
-        const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+        const float *R = p.rot + urow * 9;
+        const float *t = p.trans + urow * 3;
         float Rm[9], tc[3];
 #pragma unroll
         for (int a = 0; a < 9; ++a) Rm[a] = R[a];
 #pragma unroll
         for (int a = 0; a < 3; ++a) tc[a] = t[a] - cen[a];
-        const size_t rec = ((size_t)b * p.L + i) * p.H + h;
+        const size_t rec = urow * p.H + h;
         const float pscale = p.gamma[h] * p.w_L * p.w_C;  // weight of Q.K in the expanded distance
         const bf16_t *sc_src = ROLE == 0 ? p.q : (ROLE == 1 ? p.k : p.v);
         __attribute__((aligned(16))) bf16_t sc[c];
@@ -260,11 +264,13 @@ __device__ __forceinline__ void pack_head_row(const PackParams &p, int b, int i,
 __device__ __forceinline__ void batch_reference(const PackParams &p, int b, float (&cen)[3], int &kvlen)
 {
     const int lane = threadIdx.x & 63;
-    int last = p.L;
+    const int len = user_len(p, b);
+    const size_t row0 = user_row(p, b, 0);
+    int last = len;
     if (p.mask) {
-        const uint8_t *m = p.mask + (size_t)b * p.L;
+        const uint8_t *m = p.mask + row0;
         last = 0;
-        for (int i = lane; i < p.L; i += 64)
+        for (int i = lane; i < len; i += 64)
             if (m[i] != 0) last = i + 1;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o));
@@ -273,8 +279,8 @@ __device__ __forceinline__ void batch_reference(const PackParams &p, int b, floa
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (kvlen > 0) {
         const int i = (int)(((long long)lane * kvlen) >> 6);
-        if (p.mask ? p.mask[(size_t)b * p.L + i] != 0 : true) {
-            const float *t = p.trans + ((size_t)b * p.L + i) * 3;
+        if (p.mask ? p.mask[row0 + i] != 0 : true) {
+            const float *t = p.trans + (row0 + i) * 3;
             v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = 1.f;
         }
     }

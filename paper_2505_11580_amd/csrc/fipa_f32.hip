@@ -293,7 +293,7 @@ hipError_t f32_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream
 
     StageTimer timer(stream);
     timer.begin(0);
-    hipError_t e = launch_prep(d, a.trans, a.mask, cen, kvlen, nullptr, 0, stream);
+    hipError_t e = launch_prep(d, a.trans, a.mask, nullptr, cen, kvlen, nullptr, 0, stream);
     if (e != hipSuccess) return e;
 
     hipLaunchKernelGGL(fipa_pack_points_f32_kernel, dim3((d.L * d.H + 255) / 256, d.B), dim3(256),

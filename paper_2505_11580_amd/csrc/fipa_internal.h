@@ -42,6 +42,11 @@ struct FwdArgs {
     const float *w_b, *gamma;
     const uint8_t *mask;
     float *o, *o_pts, *o_pair, *lse;
+    // Packed batch (fipa_forward_packed / fipa_backward_packed): DEVICE pointer to B + 1 row offsets;
+    // the tensors above then have [total] leading rows instead of [B, L], chain b at rows
+    // cu[b] .. cu[b+1] - 1, and desc.L is an upper bound of the chain lengths.  Null: padded batch.
+    const int *cu = nullptr;
+    int total_rows = 0;  // with cu: the host's copy of cu[B]
 };
 
 struct BwdArgs {
@@ -74,6 +79,11 @@ struct ModuleBwdArgs {
     float *d_gamma, *d_w_b, *d_rot, *d_trans;             // d_w_b and the frame pair may be null
 };
 
+// Host-side checks of a description (sizes, dtype, flags, shapes the kernels are built for;
+// backward: the shapes fipa_backward supports) and of a pointer's 16-byte alignment.
+int check_desc(const fipa_desc *d, bool backward);
+bool aligned16(const void *p);
+
 // Host-side checks of fipa_forward's description and tensor pointers (null, alignment; the
 // workspace is the caller's business), and the dispatch to the fp32 or bf16 chain.
 int check_forward_args(const fipa_desc *desc, const FwdArgs &a);
@@ -98,7 +108,8 @@ class StageTimer {
 // of leading key slots that must be visited (1 + index of the last valid residue).
 //   cen   [B,4] floats (x, y, z, unused),  kvlen [B] ints
 // Also sets counters[0 .. n_counters) to zero (n_counters may be 0).
-hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, float *cen,
+// cu: row offsets of a packed batch (see FwdArgs), or null.
+hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, const int *cu, float *cen,
                        int *kvlen, int *counters, int n_counters, hipStream_t stream);
 
 // fp32 direct path (fipa_f32.hip)

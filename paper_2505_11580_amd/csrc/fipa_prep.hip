@@ -1,13 +1,15 @@
 // Per-batch preparation (fp32 path, backward, and the bf16 forward with a generic head shape; the
 // AlphaFold2-shape pack kernel does this work itself): centroid of the valid translations and
 // the key-loop bound.  One workgroup per batch element.  The launch also clears the arrival
-// counters of the attention kernel's key-range split, when there are any.
+// counters of the attention kernel's key-range split, when there are any.  `cu` (or null): row
+// offsets of a packed batch, chain b at rows cu[b] .. cu[b+1] - 1 instead of b L .. b L + L - 1.
 #include "fipa_internal.h"
 
 namespace fipa {
 
 __global__ __launch_bounds__(256) void fipa_prep_kernel(const float *__restrict__ trans,
                                                         const uint8_t *__restrict__ mask, int L,
+                                                        const int *__restrict__ cu,
                                                         float *__restrict__ cen,
                                                         int *__restrict__ kvlen,
                                                         int *__restrict__ counters, int n_counters)
@@ -17,10 +19,12 @@ __global__ __launch_bounds__(256) void fipa_prep_kernel(const float *__restrict_
     for (int i = b * 256 + tid; i < n_counters; i += gridDim.x * 256) counters[i] = 0;
     float sx = 0.f, sy = 0.f, sz = 0.f;
     int cnt = 0, last = 0;
-    for (int i = tid; i < L; i += 256) {
-        const bool ok = mask ? (mask[(size_t)b * L + i] != 0) : true;
+    const size_t row0 = cu ? (size_t)cu[b] : (size_t)b * L;
+    const int len = cu ? cu[b + 1] - cu[b] : L;
+    for (int i = tid; i < len; i += 256) {
+        const bool ok = mask ? (mask[row0 + i] != 0) : true;
         if (ok) {
-            const float *t = trans + ((size_t)b * L + i) * 3;
+            const float *t = trans + (row0 + i) * 3;
             sx += t[0];
             sy += t[1];
             sz += t[2];
@@ -53,10 +57,10 @@ __global__ __launch_bounds__(256) void fipa_prep_kernel(const float *__restrict_
     }
 }
 
-hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, float *cen,
+hipError_t launch_prep(const fipa_desc &d, const float *trans, const uint8_t *mask, const int *cu, float *cen,
                        int *kvlen, int *counters, int n_counters, hipStream_t stream)
 {
-    hipLaunchKernelGGL(fipa_prep_kernel, dim3(d.B), dim3(256), 0, stream, trans, mask, d.L, cen,
+    hipLaunchKernelGGL(fipa_prep_kernel, dim3(d.B), dim3(256), 0, stream, trans, mask, d.L, cu, cen,
                        kvlen, counters, n_counters);
     return hipGetLastError();
 }

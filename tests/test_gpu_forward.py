@@ -207,55 +207,6 @@ def test_stage_timer_samples_every_nth_call():
     assert stage_ms[0] > 0 and stage_ms[1] > 0
 
 
-def _packed_run(inp):
-    """fipa_forward_packed on the valid rows of a ragged (prefix-masked) workload."""
-    import torch
-    desc, dev = binding.upload(inp)
-    lengths = [int(x) for x in inp["lengths"]]
-    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
-    total = int(cu[-1])
-
-    def pack(t):  # [B, L, ...] -> [total, ...]
-        return torch.cat([t[b, :ln] for b, ln in enumerate(lengths)], dim=0).contiguous()
-
-    pk = {n: pack(dev[n]) for n in ("q", "k", "v", "q_pts", "k_pts", "v_pts", "rot", "trans", "z1", "z2")}
-    H = desc.H
-    f = dict(dtype=torch.float32, device="cuda:0")
-    out = dict(o=torch.full((total, H, desc.c), float("nan"), **f), o_pts=torch.full((total, H, desc.Pv, 3), float("nan"), **f),
-               o_pair=torch.full((total, H, desc.cz), float("nan"), **f), lse=torch.full((H * total,), float("nan"), **f))
-    one = binding.make_desc(1, desc.L, H, desc.c, desc.Pq, desc.Pv, desc.cz, desc.r, desc.dtype, inp["w_L"], inp["w_C"])
-    ws = torch.empty(max(binding.workspace_bytes(one)[0], 16), dtype=torch.uint8, device="cuda:0")
-    binding.fipa_forward_packed(desc, cu, pk["q"], pk["k"], pk["v"], pk["q_pts"], pk["k_pts"], pk["v_pts"], pk["rot"],
-                                pk["trans"], pk["z1"], pk["z2"], dev["w_b"], dev["gamma"], None,
-                                out["o"], out["o_pts"], out["o_pair"], out["lse"], ws)
-    torch.cuda.synchronize()
-    return {n: t.cpu().numpy().astype(np.float64) for n, t in out.items()}, cu, lengths
-
-
-@pytest.mark.parametrize("cfg,kw", [(0, dict(B=3, L=96, min_len=5, trans_scale=0.2)),
-                                    (1, dict(B=4, L=300, H=2, min_len=1)),
-                                    (3, dict(B=2, L=260, H=2, min_len=40))])
-def test_packed_batch_matches_the_padded_oracle(cfg, kw):
-    # chains of different lengths stored back to back, one of them possibly very short: every valid
-    # row must agree with the oracle's result for the padded, masked batch (a masked key contributes
-    # nothing, so the two are the same function), and the log-sum-exp with the padded GPU run
-    inp = wl.make_inputs(cfg, varlen=True, **kw)
-    got, cu, lengths = _packed_run(inp)
-    want = ipa_oracle_forward(inp)
-    padded = gu.run_gpu(inp)
-    tol = gu.TOL[inp["dtype"]]
-    H = inp["dims"]["H"]
-    for n in gu.NAMES:
-        assert np.all(np.isfinite(got[n])), n
-        w = np.concatenate([want[n][b, :ln] for b, ln in enumerate(lengths)], axis=0)
-        err = gu.rel_err(got[n], w)
-        print("packed cfg%d" % cfg, n, "%.2e" % err, "lengths", lengths, flush=True)
-        assert err <= tol, (n, err)
-    for b, ln in enumerate(lengths):
-        blk = got["lse"][H * cu[b]:H * cu[b + 1]].reshape(H, ln)
-        assert np.allclose(blk, padded["lse"][b, :, :ln], rtol=0, atol=2e-2 if inp["dtype"] == "bf16" else 1e-4), b
-
-
 @pytest.mark.parametrize("B,H,L", [(5, 3, 200), (66, 1, 128), (9, 2, 130)])
 def test_masked_batches_with_odd_pair_counts(B, H, L):
     # masked batches renumber their (batch, head) pairs (ranked by chain length, dealt to the XCDs);
