@@ -86,6 +86,39 @@ def test_packed_forward_argument_checks_need_no_device():
     assert call([0, 0, 0, 0]) == binding.FIPA_OK                      # only empty chains: nothing to enqueue
 
 
+def test_packed_workspace_query_and_backward_argument_checks_need_no_device():
+    lib = binding.lib()
+    d = binding.make_desc(4, 900, 12, 16, 4, 8, 128, 2, binding.FIPA_DTYPE_BF16)
+    one = binding.make_desc(1, 900, 12, 16, 4, 8, 128, 2, binding.FIPA_DTYPE_BF16)
+    even = binding.make_desc(4, 700, 12, 16, 4, 8, 128, 2, binding.FIPA_DTYPE_BF16)
+    # chains of similar lengths: one set of launches, workspace of the padded batch (at the longest chain) + offsets
+    fwd, bwd = binding.packed_workspace_bytes(d, [0, 700, 1300, 1900, 2500])
+    pf, pb = binding.workspace_bytes(even)
+    assert pf < fwd <= pf + 1024 and pb < bwd <= pb + 1024
+    # one dominant chain: chain after chain, workspace of the longest chain alone (+ the per-chain gamma / w_b sums)
+    fwd, bwd = binding.packed_workspace_bytes(d, [0, 900, 940, 973, 1043])
+    assert fwd == binding.workspace_bytes(one)[0]
+    assert binding.workspace_bytes(one)[1] < bwd <= binding.workspace_bytes(one)[1] + 4 * 4 * (12 + 12 * 128) + 1024
+    # the flag forces it
+    d.flags = binding.FIPA_FLAG_PACKED_PER_CHAIN
+    per = binding.make_desc(1, 700, 12, 16, 4, 8, 128, 2, binding.FIPA_DTYPE_BF16)
+    assert binding.packed_workspace_bytes(d, [0, 700, 1300, 1900, 2500])[0] == binding.workspace_bytes(per)[0]
+    d.flags = 0
+    with pytest.raises(binding.FipaError):
+        binding.packed_workspace_bytes(d, [0, 950, 1000, 1100, 1200])  # a chain longer than desc->L
+    fake = [ctypes.c_void_p(0x1000)] * 28
+    fake[12] = None  # mask
+    cu = (ctypes.c_int32 * 5)(0, 700, 1300, 1900, 2500)
+    ws = ctypes.c_void_p(0x1000)
+    assert lib.fipa_backward_packed(ctypes.byref(d), cu, *fake, ws, 0, None) == binding.FIPA_ERR_WORKSPACE
+    assert lib.fipa_backward_packed(ctypes.byref(d), None, *fake, ws, 1 << 40, None) == binding.FIPA_ERR_INVALID_ARG
+    only_rot = list(fake)
+    only_rot[27] = None  # d_trans without d_rot's partner
+    assert lib.fipa_backward_packed(ctypes.byref(d), cu, *only_rot, ws, 1 << 40, None) == binding.FIPA_ERR_INVALID_ARG
+    f32 = binding.make_desc(4, 900, 12, 16, 4, 8, 16, 2, binding.FIPA_DTYPE_F32)
+    assert lib.fipa_backward_packed(ctypes.byref(f32), cu, *fake, ws, 1 << 40, None) == binding.FIPA_ERR_UNSUPPORTED
+
+
 def test_stage_timer_argument_checks_need_no_device():
     lib = binding.lib()
     assert lib.fipa_profile_begin_every(10, 0) == binding.FIPA_ERR_INVALID_ARG
