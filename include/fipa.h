@@ -185,6 +185,30 @@ int fipa_backward_packed(const fipa_desc *desc, const int32_t *cu_seqlens,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * k-nearest-neighbour distogram features (Section 2.5: only the distances to the k nearest
+ * neighbours are kept, [L, k, n_bins] instead of [L, L, n_bins], with the neighbours' indices).
+ * The paper gives no formula; this call fixes:
+ *   - distance of residues i, j = Euclidean distance of the frame origins trans[b, i], trans[b, j];
+ *   - candidates are the valid residues (mask, [B, L] bytes or NULL) of the same batch element other
+ *     than i itself; an invalid residue has no neighbours; fewer than k candidates leave the last
+ *     slots empty (index -1, squared distance +inf, bin -1);
+ *   - neighbours are listed by increasing distance, equal distances by increasing index;
+ *   - n_bins bins with edges e_m = d_min + m (d_max - d_min)/(n_bins - 1), m = 0 .. n_bins - 2;
+ *     bin = number of edges e_m <= distance (bin 0: below d_min; bin n_bins - 1: at or above d_max);
+ *   - all decisions in float32 on the squared distance ((dx*dx + dy*dy) + dz*dz) and the squared
+ *     edges, one rounding per operation.
+ * Outputs (device, 4-byte aligned, fully overwritten): nbr_idx [B, L, k] int32, nbr_d2 [B, L, k]
+ * float32 (squared distances), nbr_bin [B, L, k] int32.  A one-hot distogram is
+ * feat[b, i, s, nbr_bin[b, i, s]] = 1; the factors z1, z2 are linear projections of such features,
+ * i.e. table look-ups that belong to the model around this library.
+ * 1 <= k <= 64, 2 <= n_bins <= 4096, 0 <= d_min < d_max; otherwise FIPA_ERR_INVALID_ARG /
+ * FIPA_ERR_UNSUPPORTED.  No workspace; enqueued on hip_stream.
+ */
+int fipa_knn_distogram(int32_t B, int32_t L, int32_t k, int32_t n_bins, float d_min, float d_max,
+                       const float *trans, const uint8_t *mask,
+                       int32_t *nbr_idx, float *nbr_d2, int32_t *nbr_bin, void *hip_stream);
+
+/*
  * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three
  * point sets, z1, z2 (same shapes and dtype as the inputs), gamma ([H], float32) and, when the
  * pointers are not NULL, the pair-bias weights w_b (d_w_b [H, cz], float32) and the frames

@@ -28,6 +28,7 @@ FIPA_FLAG_PACKED_PER_CHAIN = 2  # desc.flags bit: packed batches run chain after
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
            "fipa_packed_workspace_bytes", "fipa_forward_packed", "fipa_backward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
            "fipa_module_backward_workspace_bytes", "fipa_module_backward",
+           "fipa_knn_distogram",
            "fipa_profile_begin", "fipa_profile_begin_every", "fipa_profile_end", "fipa_probe_mfma")
 PROFILE_STAGES = 3
 
@@ -82,6 +83,8 @@ def lib():
         L.fipa_module_backward_workspace_bytes.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32, ctypes.POINTER(sz)]
         L.fipa_module_backward.restype = ctypes.c_int
         L.fipa_module_backward.argtypes = [ctypes.POINTER(FipaDesc), ctypes.c_int32] + [vp] * 24 + [vp, sz, vp]
+        L.fipa_knn_distogram.restype = ctypes.c_int
+        L.fipa_knn_distogram.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_float] * 2 + [vp] * 5 + [vp]
         L.fipa_profile_begin.restype = ctypes.c_int
         L.fipa_profile_begin.argtypes = [ctypes.c_int]
         L.fipa_profile_begin_every.restype = ctypes.c_int
@@ -215,6 +218,15 @@ def fipa_module_forward(desc, d_s, s, w_in, b_in, rot, trans, z1, z2, w_b, gamma
                                    ctypes.c_size_t(workspace.numel() if workspace is not None else 0), _stream())
     if rc != FIPA_OK:
         raise FipaError(rc, "fipa_module_forward")
+
+
+def fipa_knn_distogram(k, n_bins, d_min, d_max, trans, mask, nbr_idx, nbr_d2, nbr_bin):
+    """Enqueue fipa_knn_distogram on torch's current stream; trans [B, L, 3] float32, outputs [B, L, k]."""
+    B, L = int(trans.shape[0]), int(trans.shape[1])
+    rc = lib().fipa_knn_distogram(B, L, int(k), int(n_bins), float(d_min), float(d_max), _ptr(trans), _ptr(mask),
+                                  _ptr(nbr_idx), _ptr(nbr_d2), _ptr(nbr_bin), _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_knn_distogram")
 
 
 def fipa_profile_begin(capacity):

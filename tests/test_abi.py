@@ -119,6 +119,23 @@ def test_packed_workspace_query_and_backward_argument_checks_need_no_device():
     assert lib.fipa_backward_packed(ctypes.byref(f32), cu, *fake, ws, 1 << 40, None) == binding.FIPA_ERR_UNSUPPORTED
 
 
+def test_knn_distogram_argument_checks_need_no_device():
+    lib = binding.lib()
+    p = ctypes.c_void_p(0x1000)
+
+    def call(B=2, L=50, k=20, n_bins=16, d_min=2.0, d_max=22.0, trans=p, idx=p):
+        return lib.fipa_knn_distogram(B, L, k, n_bins, d_min, d_max, trans, None, idx, p, p, None)
+
+    assert call(L=0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(k=0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(n_bins=1) == binding.FIPA_ERR_INVALID_ARG
+    assert call(d_min=5.0, d_max=5.0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(d_min=-1.0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(trans=None) == binding.FIPA_ERR_INVALID_ARG
+    assert call(k=65) == binding.FIPA_ERR_UNSUPPORTED
+    assert call(idx=ctypes.c_void_p(0x1002)) == binding.FIPA_ERR_ALIGNMENT
+
+
 def test_stage_timer_argument_checks_need_no_device():
     lib = binding.lib()
     assert lib.fipa_profile_begin_every(10, 0) == binding.FIPA_ERR_INVALID_ARG
