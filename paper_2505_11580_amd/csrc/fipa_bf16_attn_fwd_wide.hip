@@ -6,7 +6,16 @@
 // issued one block ahead (the z2 block is stored once and read in both roles, as in the main
 // kernel).  The loop is software pipelined over two blocks: iteration n forms S^T of block n and,
 // interleaved with it, accumulates P V of block n-1; the softmax of block n (running maximum of
-// Algorithm 2, raised lazily) follows.  Unfused epilogue.
+// Algorithm 2, raised lazily) follows.
+// Two ways of cutting the columns into the two windows (template parameter CZ of WideCfg):
+//   CZ = 0   the lifted columns in their natural order, 288 each; the windows write the lifted
+//            output O^ and a separate kernel runs steps 8-9 (any head shape, any c_z);
+//   CZ = c_z window 0 takes the head-specific columns and, of every factor slice rho, the pair columns
+//            d < c_z/2; window 1 the pair columns d >= c_z/2.  Every output of steps 8-9 then
+//            depends on one window only -- o, o_pts and o_pair[d < c_z/2] on window 0,
+//            o_pair[d >= c_z/2] on window 1 (the contraction over rho of step 9 stays inside a
+//            window) -- and the epilogue runs on the accumulator registers as in the main kernel:
+//            no O^ in memory, no epilogue kernel.  AlphaFold2 head shape, c_z a multiple of 64.
 #include "fipa_gfx950.h"
 
 namespace fipa {
@@ -17,14 +26,26 @@ constexpr int kKB = 32;              // keys per block
 constexpr int kHS = kDH * 2 + 16;    // LDS row stride (bytes) of the head-specific k^ / v^ blocks
 constexpr float kTauW = 8.f;
 
-template <int DZ, int NWIN>
+template <int DZ, int CZ, int WIN>
 struct WideCfg {
+    static constexpr bool FUSED = CZ > 0;
     static constexpr int D = kDH + DZ;
     static constexpr int KS = D / 16, KSH = kDH / 16;
-    static constexpr int NB = D / 32, NBH = kDH / 32;
-    static constexpr int NBW = NB / NWIN;
-    static_assert(NB % NWIN == 0, "windows must tile the value columns");
-    static_assert(KS == 4 * NBW, "one P V MFMA per two S^T MFMAs");
+    static constexpr int NB = D / 32, NBH = kDH / 32, NZB = DZ / 32;
+    static_assert(!FUSED || (CZ % 64 == 0 && DZ % CZ == 0), "half a factor slice must be whole 32-column blocks");
+    static_assert(FUSED || NB % 2 == 0, "windows must tile the value columns");
+    // 32-column blocks of this window
+    static constexpr int NBW = FUSED ? (WIN == 0 ? NBH + NZB / 2 : NZB / 2) : NB / 2;
+    static constexpr int HB = FUSED ? CZ / 64 : 1;   // blocks per half factor slice
+    // Column block (0 .. NB-1 in the natural order; the first NBH are head-specific) that block nbw
+    // of this window accumulates.
+    static constexpr int col_block(int nbw)
+    {
+        if (!FUSED) return WIN * NBW + nbw;
+        if (WIN == 0 && nbw < NBH) return nbw;
+        const int t = WIN == 0 ? nbw - NBH : nbw;
+        return NBH + (t / HB) * (CZ / 32) + WIN * HB + t % HB;
+    }
     static constexpr int ZS = DZ * 2 + 48;       // LDS row stride of the z2 block (conflict free for both read patterns)
     static constexpr int Z_SPR = ZS / 16, H_SPR = kHS / 16;
     static constexpr int NZ = (kKB * Z_SPR + 63) / 64;   // wave-wide 1 KiB loads for the z2 block
@@ -78,21 +99,41 @@ __device__ __forceinline__ void wide_issue_entry(WideDma<C> &d, unsigned stage, 
 }
 
 struct WideLane {
-    int kaddr_h, kaddr_z, vaddr_h, vaddr_z, g, win;
+    int kaddr_h, kaddr_z, vaddr_h, vaddr_z, g;
 };
+
+// LDS operand of P V operation i (= 2 * window block + key half) from the stage at `st`: 32 v^ columns x 16 keys.
+template <class C, int I>
+__device__ __forceinline__ bf16x8 wide_load_pv(const char *__restrict__ st, const WideLane &ln)
+{
+    constexpr int nbw = I >> 1, tt = I & 1;
+    constexpr int nb = C::col_block(nbw);
+    constexpr bool head = nb < C::NBH;
+    const char *src = head ? st + C::VH_OFF + ln.vaddr_h + 16 * tt * kHS + nb * 64
+                           : st + C::Z_OFF + ln.vaddr_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+    constexpr int rs = head ? kHS : C::ZS;
+    const bf16x4 lo = lds_read_tr(src);
+    const bf16x4 hi = lds_read_tr(src + 8 * rs);
+    bf16x8 a;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        a[x] = lo[x];
+        a[4 + x] = hi[x];
+    }
+    return a;
+}
 
 // One step of the pipeline: S^T and the softmax of the block in stage `st` (CUR), interleaved
 // with P V of the previous block (stage `st_prev`, probabilities `pf` on entry) (PREV).  On exit
 // `pf` holds the probabilities of the current block.  When `load_next` is set the loads of the
 // next block are issued between the MFMAs, one entry every few of them (issued back to back they
 // cost about 60 cycles each).
-template <int DZ, int NWIN, bool CUR, bool PREV>
+template <class C, bool CUR, bool PREV>
 __device__ __forceinline__ void wide_step(const char *__restrict__ st, const char *__restrict__ st_prev, const WideLane &ln,
-                                          const bf16x8 (&qf)[WideCfg<DZ, NWIN>::KS], f32x16 (&acc)[WideCfg<DZ, NWIN>::NBW],
+                                          const bf16x8 (&qf)[C::KS], f32x16 (&acc)[C::NBW],
                                           bf16x8 (&pf)[2], float &m_run, float &l_run,
-                                          WideDma<WideCfg<DZ, NWIN>> &dma, unsigned next_stage, bool load_next)
+                                          WideDma<C> &dma, unsigned next_stage, bool load_next)
 {
-    using C = WideCfg<DZ, NWIN>;
     constexpr int kDmaEvery = C::KS / (C::NIW + 1);
     static_assert(kDmaEvery >= 1, "more load entries than S^T MFMAs");
     f32x16 sacc;
@@ -103,34 +144,20 @@ __device__ __forceinline__ void wide_step(const char *__restrict__ st, const cha
 #pragma unroll
             for (int x = 0; x < 4; ++x) sacc[4 * a + x] = bias[x];
         }
-    }
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) {
-        if constexpr (CUR) {
+        for (int ks = 0; ks < C::KS; ++ks) {
             const char *src = ks < C::KSH ? st + C::KH_OFF + ln.kaddr_h + ks * 32 : st + C::Z_OFF + ln.kaddr_z + (ks - C::KSH) * 32;
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(src);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
             if (load_next && ks % kDmaEvery == 0) wide_issue_entry<C>(dma, next_stage, ks / kDmaEvery);
         }
-        if constexpr (PREV) {
-            if ((ks & 1) == 0) {
-                const int i = ks >> 1, nbw = i >> 1, tt = i & 1;
-                const int nb = ln.win * C::NBW + nbw;  // global 32-column block (win is uniform)
-                const bool head = nb < C::NBH;
-                const char *src = head ? st_prev + C::VH_OFF + ln.vaddr_h + 16 * tt * kHS + nb * 64
-                                       : st_prev + C::Z_OFF + ln.vaddr_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
-                const int rs = head ? kHS : C::ZS;
-                const bf16x4 lo = lds_read_tr(src);
-                const bf16x4 hi = lds_read_tr(src + 8 * rs);
-                bf16x8 a;
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    a[x] = lo[x];
-                    a[4 + x] = hi[x];
-                }
-                acc[nbw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt], acc[nbw], 0, 0, 0);
-            }
-        }
+    }
+    if constexpr (PREV) {
+        static_for<2 * C::NBW>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            const bf16x8 a = wide_load_pv<C, i>(st_prev, ln);
+            acc[i >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[i & 1], acc[i >> 1], 0, 0, 0);
+        });
     }
     if constexpr (CUR) {
         float mx = sacc[0];
@@ -161,9 +188,8 @@ __device__ __forceinline__ void wide_step(const char *__restrict__ st, const cha
 // NPV - kTail P V MFMAs of the previous block spread between them, then the held-back kTail P V
 // MFMAs, which run while the row maximum and the exponentials of the current block are formed.
 // kind: 0 = S^T (idx = k-step), 1 = P V (idx = 2 * output block + key half).
-template <int DZ, int NWIN>
+template <class C>
 struct WideOps {
-    using C = WideCfg<DZ, NWIN>;
     static constexpr int KS = C::KS, NPV = 2 * C::NBW;
     static constexpr int kTail = 8;
     static constexpr int kInLoop = NPV - kTail;
@@ -193,14 +219,13 @@ struct WideOps {
 // by pair -- between the held-back P V MFMAs of the previous block.  Those still use the old
 // reference, so when the reference has to be raised the accumulator is rescaled only at the end
 // of the step, after the last of them.
-template <int DZ, int NWIN>
+template <class C>
 __device__ __forceinline__ void wide_step_steady(const char *__restrict__ st, const char *__restrict__ st_prev, const WideLane &ln,
-                                                 const bf16x8 (&qf)[WideCfg<DZ, NWIN>::KS], f32x16 (&acc)[WideCfg<DZ, NWIN>::NBW],
+                                                 const bf16x8 (&qf)[C::KS], f32x16 (&acc)[C::NBW],
                                                  bf16x8 (&pf)[2], float &m_run, float &l_run,
-                                                 WideDma<WideCfg<DZ, NWIN>> &dma, unsigned next_stage, bool load_next)
+                                                 WideDma<C> &dma, unsigned next_stage, bool load_next)
 {
-    using C = WideCfg<DZ, NWIN>;
-    using O = WideOps<DZ, NWIN>;
+    using O = WideOps<C>;
     constexpr int kDmaEvery = C::KS / (C::NIW + 1);
     constexpr int kLA = 3, kRing = 4;
     auto fetch = [&](auto J) -> bf16x8 {
@@ -210,21 +235,7 @@ __device__ __forceinline__ void wide_step_steady(const char *__restrict__ st, co
             const char *src = ks < C::KSH ? st + C::KH_OFF + ln.kaddr_h + ks * 32 : st + C::Z_OFF + ln.kaddr_z + (ks - C::KSH) * 32;
             return *reinterpret_cast<const bf16x8 *>(src);
         } else {
-            constexpr int nbw = o.idx >> 1, tt = o.idx & 1;
-            const int nb = ln.win * C::NBW + nbw;  // global 32-column block (win is uniform)
-            const bool head = nb < C::NBH;
-            const char *src = head ? st_prev + C::VH_OFF + ln.vaddr_h + 16 * tt * kHS + nb * 64
-                                   : st_prev + C::Z_OFF + ln.vaddr_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
-            const int rs = head ? kHS : C::ZS;
-            const bf16x4 lo = lds_read_tr(src);
-            const bf16x4 hi = lds_read_tr(src + 8 * rs);
-            bf16x8 a;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                a[x] = lo[x];
-                a[4 + x] = hi[x];
-            }
-            return a;
+            return wide_load_pv<C, o.idx>(st_prev, ln);
         }
     };
     f32x16 sacc;
@@ -283,23 +294,11 @@ __device__ __forceinline__ void wide_step_steady(const char *__restrict__ st, co
     pf[1] = __builtin_bit_cast(bf16x8, (u32x4){pp[4], pp[5], pp[6], pp[7]});
 }
 
-template <int DZ, int NWIN>
-__global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p)
+// One window of one query tile.
+template <int DZ, int CZ, int WIN>
+__device__ __forceinline__ void wide_window(const AttnParams &p, char *smem, int logical)
 {
-    using C = WideCfg<DZ, NWIN>;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    // Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tiles, and the
-    // windows of a tile are neighbours in that XCD's launch order, so that they run side by side and
-    // the key blocks one of them brings in are found in the XCD's L2 by the other (launched as a
-    // second grid dimension the windows of a tile ran far apart in time: 6.49 -> 5.92 ms at the
-    // ragged rank-4 workload).  Going further -- all heads of a group of four query tiles side by side,
-    // so that 32 workgroups share one z2 stream -- measured 7 % slower: the same lines are then
-    // wanted by every compute unit of the XCD at the same moment.
-    const int chunk = (p.total_tiles + 7) / 8;
-    const int slot = blockIdx.x / 8;
-    const int logical = (blockIdx.x % 8) * chunk + slot / NWIN;
-    if (logical >= p.total_tiles) return;
-    const int win = slot % NWIN;
+    using C = WideCfg<DZ, CZ, WIN>;
     const int bh_pos = logical / p.nQT, qt = logical - bh_pos * p.nQT;
     const int bh = p.deal ? dealt_pair_by_length(bh_pos, p.kvlen, p.B, p.H, threadIdx.x & 63) : bh_pos;
     const int b = bh / p.H;
@@ -310,16 +309,38 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
     const int nblk = (kvlen + kKB - 1) / kKB;
     const int irow = qt * kTileQ + wave * 32 + li;
 
+    // rows of this chain in the caller's tensors (a packed batch stores the chains back to back)
+    [[maybe_unused]] const int ulen = user_len(p, b);
+    [[maybe_unused]] const size_t urow0 = user_row(p, b, 0);
+    [[maybe_unused]] const int h = bh - b * p.H;
+
     // A tile whose rows all lie past the last valid residue of its chain has nothing to attend
     // from: zero output.
     if (qt * kTileQ >= kvlen) {
-        float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::D + win * C::NBW * 32;
+        if constexpr (!C::FUSED) {
+            float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::D;
 #pragma unroll
-        for (int nbw = 0; nbw < C::NBW; ++nbw)
+            for (int nbw = 0; nbw < C::NBW; ++nbw)
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-                *reinterpret_cast<f32x4 *>(orow + 32 * nbw + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (win == 0 && g == 0) p.lse2[(size_t)bh * p.Lp + irow] = -INFINITY;
+                for (int a = 0; a < 4; ++a)
+                    *reinterpret_cast<f32x4 *>(orow + 32 * C::col_block(nbw) + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (WIN == 0 && g == 0) p.lse2[(size_t)bh * p.Lp + irow] = -INFINITY;
+        } else if (irow < ulen) {
+            const size_t row = (urow0 + irow) * p.H + h;
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (WIN == 0) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a) *reinterpret_cast<f32x4 *>(p.o + row * 16 + 8 * a + 4 * g) = zero;
+#pragma unroll
+                for (int a = 0; a < 3; ++a) *reinterpret_cast<f32x4 *>(p.o_pts + row * 24 + 12 * g + 4 * a) = zero;
+                if (p.lse && g == 0) p.lse[user_lse_index(p, b, h, irow)] = 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < C::HB; ++q)
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    *reinterpret_cast<f32x4 *>(p.o_pair + row * CZ + 32 * (WIN * C::HB + q) + 8 * a + 4 * g) = zero;
+        }
         return;
     }
 
@@ -376,10 +397,8 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
         // vector goes through LDS; rows that do not exist or are masked get zeros.
         {
             float *cw = reinterpret_cast<float *>(smem + C::CW_OFF);
-            for (int x = tid; x < DZ; x += 256) cw[x] = kLog2e * p.w_L * p.w_b[(size_t)(bh - b * p.H) * p.cz + x % p.cz];
+            for (int x = tid; x < DZ; x += 256) cw[x] = kLog2e * p.w_L * p.w_b[(size_t)h * p.cz + x % p.cz];
             __syncthreads();
-            const int ulen = user_len(p, b);
-            const size_t urow0 = user_row(p, b, 0);  // (a packed batch stores the chains back to back)
             const bool ok = irow < ulen && (p.mask ? p.mask[urow0 + irow] != 0 : true);
             const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
             const bf16_t *z1row = p.z1 + (urow0 + min(irow, ulen - 1)) * DZ + 8 * g;
@@ -423,7 +442,6 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
         ln.vaddr_h = (4 * g + e4) * kHS + (16 * grp2 + 4 * j4) * 2;
         ln.vaddr_z = (4 * g + e4) * C::ZS + (16 * grp2 + 4 * j4) * 2;
         ln.g = g;
-        ln.win = win;
     }
 
     bf16x8 pf[2] = {};
@@ -448,40 +466,177 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
             ++next_blk;
         }
         if (n == 0)
-            wide_step<DZ, NWIN, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
+            wide_step<C, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
         else
-            wide_step_steady<DZ, NWIN>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
+            wide_step_steady<C>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
         st_prev = st;
     }
-    if (nblk > 0) wide_step<DZ, NWIN, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run, dma, 0u, false);
+    if (nblk > 0) wide_step<C, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run, dma, 0u, false);
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::D + win * C::NBW * 32;
+    const float lse2 = l_tot > 0.f ? m_run + __log2f(l_tot) : -INFINITY;
+    if constexpr (!C::FUSED) {
+        float *orow = p.Ohat + ((size_t)bh * p.Lp + irow) * C::D;
 #pragma unroll
-    for (int nbw = 0; nbw < C::NBW; ++nbw)
+        for (int nbw = 0; nbw < C::NBW; ++nbw)
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            f32x4 out;
+            for (int a = 0; a < 4; ++a) {
+                f32x4 out;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) out[x] = acc[nbw][4 * a + x] * inv;
-            *reinterpret_cast<f32x4 *>(orow + 32 * nbw + 8 * a + 4 * g) = out;
+                for (int x = 0; x < 4; ++x) out[x] = acc[nbw][4 * a + x] * inv;
+                *reinterpret_cast<f32x4 *>(orow + 32 * C::col_block(nbw) + 8 * a + 4 * g) = out;
+            }
+        if (WIN == 0 && g == 0) p.lse2[(size_t)bh * p.Lp + irow] = lse2;
+    } else {
+        // ---- split, inverse frame, z1 contraction (Algorithm 1 steps 8-9, Eq. 4) on the accumulator;
+        // c = 16, N_value = 8.  This window holds, for its half of the pair columns d, all R = DZ / CZ
+        // factor slices: block z0 + rho * HB + q is slice rho, columns 32 (WIN * HB + q) .. + 31.
+        constexpr int R = DZ / CZ, HB = C::HB, z0 = WIN == 0 ? C::NBH : 0;
+        const bool in_range = irow < ulen;
+        const int irow_c = min(irow, ulen - 1);  // rows past the end compute on a valid address and store nothing
+        const bool valid = (p.mask ? p.mask[urow0 + irow_c] != 0 : true) && l_tot > 0.f;
+        const float sc = valid ? inv : 0.f;
+        const size_t row = (urow0 + irow_c) * p.H + h;
+        {
+            // (read per lane from memory: 8 bytes of each of the wave's 32 rows per load.  Staging the rows
+            // through the free LDS stages during the last block, as the main kernel does, measured 2 %
+            // slower here -- the epilogue is 1 % of a unit at this width, the extra barrier is not free)
+            const bf16_t *z1row = p.z1 + (urow0 + irow_c) * DZ + 32 * WIN * HB + 4 * g;
+#pragma unroll
+            for (int rho = 0; rho < R; ++rho)
+#pragma unroll
+                for (int q = 0; q < HB; ++q)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        const uint2 zraw = *reinterpret_cast<const uint2 *>(z1row + rho * CZ + 32 * q + 8 * a);
+                        const bf16_t *zb16 = reinterpret_cast<const bf16_t *>(&zraw);
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) acc[z0 + rho * HB + q][4 * a + x] *= bf2f(zb16[x]);
+                    }
+#pragma unroll
+            for (int q = 0; q < HB; ++q)
+#pragma unroll
+                for (int rho = 1; rho < R; ++rho)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[z0 + q][r] += acc[z0 + rho * HB + q][r];
         }
-    if (win == 0 && g == 0) p.lse2[(size_t)bh * p.Lp + irow] = l_tot > 0.f ? m_run + __log2f(l_tot) : -INFINITY;
+        if (in_range) {
+            float *dst = p.o_pair + row * CZ + 32 * WIN * HB;
+#pragma unroll
+            for (int q = 0; q < HB; ++q)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    f32x4 out;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) out[x] = acc[z0 + q][4 * a + x] * sc;
+                    *reinterpret_cast<f32x4 *>(dst + 32 * q + 8 * a + 4 * g) = out;
+                }
+        }
+        if constexpr (WIN == 0) {
+            constexpr int c = 16, Pv = 8;
+            // point part: this half owns points 4g .. 4g+3, hi parts in slots u = 0..11, lo parts in
+            // slots 12..23; slot u sits in column 16 + 8*(u/4) + 4g + u%4 (see v_pt_col)
+            float Gv[12];
+#pragma unroll
+            for (int u = 0; u < 12; ++u) {
+                const int dh = 16 + 8 * (u >> 2) + (u & 3);  // column for g = 0; g = 1 adds 4
+                const int dl = 16 + 8 * ((u + 12) >> 2) + ((u + 12) & 3);
+                Gv[u] = acc[dh >> 5][4 * ((dh & 31) >> 3) + (dh & 3)] + acc[dl >> 5][4 * ((dl & 31) >> 3) + (dl & 3)];
+            }
+            if (in_range) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    f32x4 out;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) out[x] = acc[0][4 * a + x] * sc;
+                    *reinterpret_cast<f32x4 *>(p.o + row * c + 8 * a + 4 * g) = out;
+                }
+            }
+            const float *Rp = p.rot + (urow0 + irow_c) * 9;
+            const float *tr = p.trans + (urow0 + irow_c) * 3;
+            float Rm[9], tc[3];
+#pragma unroll
+            for (int a = 0; a < 9; ++a) Rm[a] = Rp[a];
+#pragma unroll
+            for (int a = 0; a < 3; ++a) tc[a] = tr[a] - p.cen[4 * b + a];
+            float outp[12];
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) {
+                const float rx = Gv[3 * pp] * inv - tc[0], ry = Gv[3 * pp + 1] * inv - tc[1],
+                            rz = Gv[3 * pp + 2] * inv - tc[2];
+#pragma unroll
+                for (int x = 0; x < 3; ++x) {
+                    const float val = Rm[x] * rx + Rm[3 + x] * ry + Rm[6 + x] * rz;  // R^T
+                    outp[3 * pp + x] = valid ? val : 0.f;
+                }
+            }
+            if (in_range) {
+                float *dst = p.o_pts + row * (Pv * 3) + 12 * g;
+#pragma unroll
+                for (int a = 0; a < 3; ++a)
+                    *reinterpret_cast<f32x4 *>(dst + 4 * a) =
+                        (f32x4){outp[4 * a], outp[4 * a + 1], outp[4 * a + 2], outp[4 * a + 3]};
+                if (p.lse && g == 0)
+                    p.lse[user_lse_index(p, b, h, irow)] = valid ? lse2 * kLn2 - p.qbias[(size_t)bh * p.Lp + irow] : 0.f;
+            }
+        }
+    }
+}
+
+template <int DZ, int CZ>
+__global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tiles, and the
+    // windows of a tile are neighbours in that XCD's launch order, so that they run side by side and
+    // the key blocks one of them brings in are found in the XCD's L2 by the other (launched as a
+    // second grid dimension the windows of a tile ran far apart in time: 6.49 -> 5.92 ms at the
+    // ragged rank-4 workload).  Going further -- all heads of a group of four query tiles side by side,
+    // so that 32 workgroups share one z2 stream -- measured 7 % slower: the same lines are then
+    // wanted by every compute unit of the XCD at the same moment.
+    const int chunk = (p.total_tiles + 7) / 8;
+    const int slot = blockIdx.x / 8;
+    const int logical = (blockIdx.x % 8) * chunk + slot / 2;
+    if (logical >= p.total_tiles) return;
+    if (slot % 2 == 0)
+        wide_window<DZ, CZ, 0>(p, smem, logical);
+    else
+        wide_window<DZ, CZ, 1>(p, smem, logical);
 }
 
 }  // namespace
 
-hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, hipStream_t stream)
+bool attn_fwd_wide_fused_supported(int DZ, int cz) { return DZ == 512 && (cz == 64 || cz == 128 || cz == 256); }
+
+namespace {
+
+template <int CZ>
+hipError_t launch_wide(const AttnParams &p, hipStream_t stream)
 {
-    if (DZ != 512) return hipErrorInvalidValue;
-    using C = WideCfg<512, 2>;
+    constexpr int lds = WideCfg<512, CZ, 0>::LDS_BYTES;
     static LdsLimit lds_limit;
-    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_attn_fwd_wide_kernel<512, 2>, C::LDS_BYTES);
+    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_attn_fwd_wide_kernel<512, CZ>, lds);
     if (e != hipSuccess) return e;
     const int chunk = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL((fipa_attn_fwd_wide_kernel<512, 2>), dim3(chunk * 8 * 2), dim3(256), C::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((fipa_attn_fwd_wide_kernel<512, CZ>), dim3(chunk * 8 * 2), dim3(256), lds, stream, p);
     return hipGetLastError();
+}
+
+}  // namespace
+
+// fused: steps 8-9 of Algorithm 1 run inside the kernel (AlphaFold2 head shape, c_z of
+// attn_fwd_wide_fused_supported); otherwise the kernel leaves O^ and the log-sum-exp in the workspace.
+hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream)
+{
+    if (DZ != 512) return hipErrorInvalidValue;
+    if (!fused) return launch_wide<0>(p, stream);
+    switch (p.cz) {
+        case 64: return launch_wide<64>(p, stream);
+        case 128: return launch_wide<128>(p, stream);
+        case 256: return launch_wide<256>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace fipa

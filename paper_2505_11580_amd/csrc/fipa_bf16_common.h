@@ -199,6 +199,12 @@ inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
 
 // The fused epilogue is compiled for the AlphaFold2-style head shape only.
 inline bool bf16_fused_epilogue(const fipa_desc &d) { return d.c == 16 && d.Pv == 8 && d.r * d.cz <= 256; }
+// The same for the two-window kernel of width r*cz = 512 (c_z such that half a factor slice is whole 32-column blocks).
+bool attn_fwd_wide_fused_supported(int DZ, int cz);
+inline bool bf16_wide_fused_epilogue(const fipa_desc &d)
+{
+    return d.c == 16 && d.Pv == 8 && attn_fwd_wide_fused_supported(d.r * d.cz, d.cz);
+}
 
 struct PackParams {
     const bf16_t *q, *k, *v, *q_pts, *k_pts, *v_pts, *z1, *z2;
@@ -301,7 +307,7 @@ hipError_t launch_pack_bf16(const PackParams &p, hipStream_t stream);
 hipError_t launch_attn_fwd_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream);
 bool attn_fwd_ws_supported(int DZ, int cz);  // shapes of the wave-specialised fused kernel
 hipError_t launch_attn_fwd_ws_bf16(const AttnParams &p, int DZ, hipStream_t stream);
-hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, hipStream_t stream);  // r*cz = 512
+hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream);  // r*cz = 512
 hipError_t launch_epilogue_bf16(const EpiParams &p, hipStream_t stream);
 
 }  // namespace fipa

@@ -3,12 +3,16 @@
 
 namespace fipa {
 
-size_t bf16_forward_workspace(const fipa_desc &d) { return bf16_layout(d, !bf16_fused_epilogue(d)).total; }
+size_t bf16_forward_workspace(const fipa_desc &d)
+{
+    return bf16_layout(d, !(bf16_fused_epilogue(d) || bf16_wide_fused_epilogue(d))).total;
+}
 
 hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStream_t stream)
 {
+    const bool wide_fused = bf16_wide_fused_epilogue(d);
     const bool fused = bf16_fused_epilogue(d);
-    const Bf16Layout w = bf16_layout(d, !fused);
+    const Bf16Layout w = bf16_layout(d, !(fused || wide_fused));
     char *base = static_cast<char *>(ws);
     float *cen = reinterpret_cast<float *>(base + w.cen);
     int *kvlen = reinterpret_cast<int *>(base + w.kvlen);
@@ -48,7 +52,7 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     AttnParams at;
     at.Qh = pk.Qh; at.Qz = pk.Qz; at.Kh = pk.Kh; at.Vh = pk.Vh; at.Z2 = pk.Z2;
     at.kbias = pk.kbias; at.qbias = pk.qbias; at.kvlen = kvlen;
-    at.Ohat = fused ? nullptr : (float *)(base + w.Ohat);
+    at.Ohat = fused || wide_fused ? nullptr : (float *)(base + w.Ohat);
     at.lse2 = (float *)(base + w.lse2);
     at.rot = a.rot; at.trans = a.trans; at.cen = cen; at.z1 = pk.z1; at.mask = a.mask; at.cu = a.cu;
     at.o = a.o; at.o_pts = a.o_pts; at.o_pair = a.o_pair; at.lse = a.lse;
@@ -61,12 +65,12 @@ hipError_t bf16_forward(const fipa_desc &d, const FwdArgs &a, void *ws, hipStrea
     const bool ws_kernel = (d.flags & FIPA_FLAG_WAVE_SPECIALISED) && fused && attn_fwd_ws_supported(w.DZ, d.cz) &&
                            w.total < (1ull << 32) && !a.cu;
     timer.begin(1);
-    e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, stream)
+    e = w.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.DZ, wide_fused, stream)
         : ws_kernel ? launch_attn_fwd_ws_bf16(at, w.DZ, stream)
                     : launch_attn_fwd_bf16(at, w.DZ, fused, stream);
     if (e != hipSuccess) return e;
     timer.end(1);
-    if (fused) return hipSuccess;  // steps 8-9 ran inside the attention kernel
+    if (fused || wide_fused) return hipSuccess;  // steps 8-9 ran inside the attention kernel
 
     EpiParams ep;
     ep.Ohat = at.Ohat; ep.lse2 = at.lse2; ep.qbias = pk.qbias; ep.rot = a.rot; ep.trans = a.trans;

@@ -121,6 +121,20 @@ def test_bf16_rank4_small():
     gu.check(wl.make_inputs(3, B=2, L=300, H=2, min_len=40, trans_scale=0.2), label="bf16 r=4 varlen spread")
 
 
+@pytest.mark.parametrize("cz,r,kw", [(64, 8, {}), (256, 2, {}), (32, 16, {}), (128, 4, dict(c=8, Pq=2, Pv=3)),
+                                     (128, 4, dict(c=16, Pq=3, Pv=7))])
+def test_bf16_width512_other_factor_shapes(cz, r, kw):
+    # r*c_z = 512 with other splits into rank and width: c_z = 64 and 256 take the windows that keep the
+    # contraction over rho inside a window (epilogue on the registers); c_z = 32 and head shapes other
+    # than c = 16, N_value = 8 take the natural-order windows with the separate epilogue kernel
+    inp = wl.make_inputs(3, B=2, L=260, H=2, cz=cz, r=r, min_len=30, trans_scale=0.3, **kw)
+    gu.check(inp, label="bf16 width 512: cz=%d r=%d %s" % (cz, r, kw))
+    got = gu.run_gpu(inp)
+    for b, ln in enumerate(inp["lengths"]):
+        for n in gu.NAMES:
+            assert np.all(got[n][b, int(ln):] == 0), (n, b)
+
+
 def test_bf16_workload3_sampled_rows():
     # variable-length padded batch, lengths U[1024, 8192], r = 4: 256 rows of every batch element
     # (first / last valid / first padded, one in every 128-row query tile, the rest random) against
