@@ -12,6 +12,9 @@ namespace fipa {
 namespace {
 
 // One wave per (batch, head, residue < Lp): lifted upstream gradient row, D_i, and -lse.
+// Lane l takes head-specific column l and the four pair columns 4 l' .. 4 l' + 3 of each group of
+// 256 (l' = l), so that the pair part moves in 16-byte (fp32) and 8-byte (bf16) pieces and all loads
+// of a row are independent of each other.
 __global__ __launch_bounds__(256) void fipa_bwd_pack_bf16_kernel(BwdPackParams p)
 {
     const int lane = threadIdx.x & 63;
@@ -28,12 +31,35 @@ __global__ __launch_bounds__(256) void fipa_bwd_pack_bf16_kernel(BwdPackParams p
     const float *oh = p.Ohat + row_id * D;
     bf16_t *dst = p.dOhat + row_id * D;
     float dsum = 0.f;
-    for (int col = lane; col < D; col += 64) {
+    // ---- pair part: columns kDH + 4 q, q = lane, lane + 64, ...
+    for (int q = lane; 4 * q < p.DZ; q += 64) {
+        const int x = 4 * q;
+        f32x4 val = {0.f, 0.f, 0.f, 0.f}, o4 = {0.f, 0.f, 0.f, 0.f};
+        if (valid) {
+            const uint2 zr = *reinterpret_cast<const uint2 *>(p.z1 + urow * p.DZ + x);  // four bf16 values
+            const f32x4 g4 = *reinterpret_cast<const f32x4 *>(p.d_o_pair + rec * p.cz + x % p.cz);  // (cz is a multiple of 8)
+            o4 = *reinterpret_cast<const f32x4 *>(oh + kDH + x);
+            val[0] = __uint_as_float(zr.x << 16) * g4[0];
+            val[1] = __uint_as_float(zr.x & 0xFFFF0000u) * g4[1];
+            val[2] = __uint_as_float(zr.y << 16) * g4[2];
+            val[3] = __uint_as_float(zr.y & 0xFFFF0000u) * g4[3];
+        }
+        __attribute__((aligned(8))) bf16_t bv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            bv[e] = f2bf(val[e]);
+            dsum += bf2f(bv[e]) * o4[e];  // D uses the rounded gradient the MFMAs will see
+        }
+        *reinterpret_cast<uint2 *>(dst + kDH + x) = *reinterpret_cast<const uint2 *>(bv);
+    }
+    // ---- head-specific part: column `lane`
+    {
+        const int col = lane;
         float val = 0.f;
         if (valid) {
             if (col < c) {
                 val = p.d_o[rec * c + col];
-            } else if (col < kDH) {
+            } else {
                 // inverse of v_pt_col: which (point, axis) lives in this column, if any
                 const int cp = col - c, within = cp & 7;
                 const int gh = within >> 2, u = 4 * (cp >> 3) + (within & 3);
@@ -43,14 +69,11 @@ __global__ __launch_bounds__(256) void fipa_bwd_pack_bf16_kernel(BwdPackParams p
                     const float *g = p.d_o_pts + (rec * p.Pv + pt) * 3;
                     val = R[3 * ax] * g[0] + R[3 * ax + 1] * g[1] + R[3 * ax + 2] * g[2];  // dG = R_i d_o_pts
                 }
-            } else {
-                const int x = col - kDH;
-                val = bf2f(p.z1[urow * p.DZ + x]) * p.d_o_pair[rec * p.cz + x % p.cz];
             }
         }
         const bf16_t bv = f2bf(val);
         dst[col] = bv;
-        dsum += bf2f(bv) * (valid ? oh[col] : 0.f);  // D uses the rounded gradient the MFMAs will see
+        dsum += bf2f(bv) * (valid ? oh[col] : 0.f);
     }
     for (int off = 32; off > 0; off >>= 1) dsum += __shfl_xor(dsum, off);
     if (lane == 0) {
