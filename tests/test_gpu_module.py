@@ -40,6 +40,8 @@ def test_module_small_shapes():
     # three query points: the point tensors of Eq. 1's result start at columns that are no multiples
     # of 8 and the result is 180 wide (pieces of an output row that straddle two tensors or its end)
     check_module(wl.make_module_inputs(1, d_s=64, B=1, L=70, H=2, Pq=3), "module Pq=3")
+    # rank 4 (lifted width 576: the two-window attention kernel with its epilogue on the registers)
+    check_module(wl.make_module_inputs(3, d_s=64, B=2, L=200, H=2, min_len=50), "module r=4 ragged")
 
 
 def test_module_masked_rows_receive_the_bias():
