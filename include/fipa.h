@@ -50,7 +50,9 @@ extern "C" {
  *   qk_scale: the 1/sqrt(c) of Eq. 3.
  * Shapes supported:  FIPA_DTYPE_F32: c + 3*Pv + r*cz <= 576 and r*cz <= 512.
  *                    FIPA_DTYPE_BF16: c % 8 == 0, cz % 8 == 0, c + 12*Pq <= 64,
- *                    c + 8*ceil(3*ceil(Pv/2)/2) <= 64, r*cz in {32, 64, 128, 256, 512}.
+ *                    c + 8*ceil(3*ceil(Pv/2)/2) <= 64, r*cz in {32, 64, 128, 256, 512, 1024}
+ *                    (1024, e.g. rank 8 at cz = 128 -- the larger lifted widths that Section 4.1 names as
+ *                    the way to higher rank: forward only, a plain kernel that is not tuned).
  */
 typedef struct fipa_desc {
     int32_t B, L, H, c, Pq, Pv, cz, r;

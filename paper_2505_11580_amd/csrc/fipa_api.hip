@@ -28,8 +28,8 @@ int check_desc(const fipa_desc *d, bool backward)
         if (d->c % 8 != 0 || d->cz % 8 != 0 || d->c + 12 * d->Pq > 64 ||
             d->c + 8 * ((6 * PH + 3) / 4) > 64)
             return FIPA_ERR_UNSUPPORTED;
-        if (DZ != 32 && DZ != 64 && DZ != 128 && DZ != 256 && DZ != 512) return FIPA_ERR_UNSUPPORTED;
-        if (DZ == 512 && backward) return FIPA_ERR_UNSUPPORTED;
+        if (DZ != 32 && DZ != 64 && DZ != 128 && DZ != 256 && DZ != 512 && DZ != 1024) return FIPA_ERR_UNSUPPORTED;
+        if (DZ >= 512 && backward) return FIPA_ERR_UNSUPPORTED;
     }
     return FIPA_OK;
 }

@@ -1,5 +1,6 @@
 // Fused attention on the lifted features (Algorithm 1 step 7) for wide pair factors (r*c_z = 512,
-// lifted width 576): same mathematics and register layout as the main kernel, but the output
+// lifted width 576; and r*c_z = 1024, width 1088, see the end of this comment): same mathematics and
+// register layout as the main kernel, but the output
 // accumulator of 32 x 576 fp32 per wave does not fit the register file, so the value columns are
 // cut into windows and each workgroup computes one window (recomputing S^T and the softmax).
 // Key blocks of 32 residues arrive in a ring of three LDS stages by direct global -> LDS loads
@@ -16,6 +17,12 @@
 //            o_pair[d >= c_z/2] on window 1 (the contraction over rho of step 9 stays inside a
 //            window) -- and the epilogue runs on the accumulator registers as in the main kernel:
 //            no O^ in memory, no epilogue kernel.  AlphaFold2 head shape, c_z a multiple of 64.
+// Width 1088 (rank 8 at c_z = 128; the larger head widths that Section 4.1 names as the way to higher
+// rank): the query fragments alone take 272 registers per lane, which leaves room for a quarter of the
+// output columns, so there are four natural-order windows (the 34 column blocks padded to 36, nine per
+// window; S^T is formed four times), a key block is 77 KB and only two stages fit LDS, so the loop is
+// not pipelined across blocks (S^T, softmax and P V of a block one after the other while the next block
+// loads), and the epilogue is the separate kernel.  It makes the shape usable; it is not tuned.
 #include "fipa_gfx950.h"
 
 namespace fipa {
@@ -26,16 +33,17 @@ constexpr int kKB = 32;              // keys per block
 constexpr int kHS = kDH * 2 + 16;    // LDS row stride (bytes) of the head-specific k^ / v^ blocks
 constexpr float kTauW = 8.f;
 
-template <int DZ, int CZ, int WIN>
+template <int DZ, int CZ, int NWIN, int WIN>
 struct WideCfg {
     static constexpr bool FUSED = CZ > 0;
     static constexpr int D = kDH + DZ;
     static constexpr int KS = D / 16, KSH = kDH / 16;
     static constexpr int NB = D / 32, NBH = kDH / 32, NZB = DZ / 32;
     static_assert(!FUSED || (CZ % 64 == 0 && DZ % CZ == 0), "half a factor slice must be whole 32-column blocks");
-    static_assert(FUSED || NB % 2 == 0, "windows must tile the value columns");
-    // 32-column blocks of this window
-    static constexpr int NBW = FUSED ? (WIN == 0 ? NBH + NZB / 2 : NZB / 2) : NB / 2;
+    static_assert(!FUSED || NWIN == 2, "the slice-halving windows come in pairs");
+    // 32-column blocks of this window (natural order: the last window may end in padding blocks,
+    // col_block() >= NB, which are neither multiplied nor stored)
+    static constexpr int NBW = FUSED ? (WIN == 0 ? NBH + NZB / 2 : NZB / 2) : (NB + NWIN - 1) / NWIN;
     static constexpr int HB = FUSED ? CZ / 64 : 1;   // blocks per half factor slice
     // Column block (0 .. NB-1 in the natural order; the first NBH are head-specific) that block nbw
     // of this window accumulates.
@@ -55,7 +63,8 @@ struct WideCfg {
     static constexpr int Z_OFF = 0, KH_OFF = NZ * 1024, VH_OFF = (NZ + NH) * 1024;
     static constexpr int KB_OFF = NIW * 4 * 1024;        // 32 per-key fp32 biases (a full 1 KiB load lands here)
     static constexpr int STAGE = KB_OFF + 1024;
-    static constexpr int NSTAGE = 3;
+    static constexpr int NSTAGE = STAGE * 3 + DZ * 4 <= 160 * 1024 ? 3 : 2;
+    static constexpr bool PIPELINED = NSTAGE == 3;       // S^T of block n together with P V of block n-1
     static constexpr int CW_OFF = NSTAGE * STAGE;        // per-head scale vector of the query-side factors (DZ floats)
     static constexpr int LDS_BYTES = CW_OFF + DZ * 4;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -155,8 +164,10 @@ __device__ __forceinline__ void wide_step(const char *__restrict__ st, const cha
     if constexpr (PREV) {
         static_for<2 * C::NBW>([&](auto I) {
             constexpr int i = decltype(I)::value;
-            const bf16x8 a = wide_load_pv<C, i>(st_prev, ln);
-            acc[i >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[i & 1], acc[i >> 1], 0, 0, 0);
+            if constexpr (C::col_block(i >> 1) < C::NB) {
+                const bf16x8 a = wide_load_pv<C, i>(st_prev, ln);
+                acc[i >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[i & 1], acc[i >> 1], 0, 0, 0);
+            }
         });
     }
     if constexpr (CUR) {
@@ -295,10 +306,10 @@ __device__ __forceinline__ void wide_step_steady(const char *__restrict__ st, co
 }
 
 // One window of one query tile.
-template <int DZ, int CZ, int WIN>
+template <int DZ, int CZ, int NWIN, int WIN>
 __device__ __forceinline__ void wide_window(const AttnParams &p, char *smem, int logical)
 {
-    using C = WideCfg<DZ, CZ, WIN>;
+    using C = WideCfg<DZ, CZ, NWIN, WIN>;
     const int bh_pos = logical / p.nQT, qt = logical - bh_pos * p.nQT;
     const int bh = p.deal ? dealt_pair_by_length(bh_pos, p.kvlen, p.B, p.H, threadIdx.x & 63) : bh_pos;
     const int b = bh / p.H;
@@ -323,7 +334,8 @@ __device__ __forceinline__ void wide_window(const AttnParams &p, char *smem, int
             for (int nbw = 0; nbw < C::NBW; ++nbw)
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
-                    *reinterpret_cast<f32x4 *>(orow + 32 * C::col_block(nbw) + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    if (C::col_block(nbw) < C::NB)
+                        *reinterpret_cast<f32x4 *>(orow + 32 * C::col_block(nbw) + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
             if (WIN == 0 && g == 0) p.lse2[(size_t)bh * p.Lp + irow] = -INFINITY;
         } else if (irow < ulen) {
             const size_t row = (urow0 + irow) * p.H + h;
@@ -423,7 +435,10 @@ __device__ __forceinline__ void wide_window(const AttnParams &p, char *smem, int
         // operand directly (left to itself the compiler parks them there and copies each one to
         // an architectural register before its MFMA): 16 * NBW registers hold the output
         // accumulator, 16 the S^T accumulator, the rest of the 256 takes fragments.
-        constexpr int kInAcc = (256 - 16 * C::NBW - 16) / 4 < C::KS ? (256 - 16 * C::NBW - 16) / 4 : C::KS;
+        // (Width 1088: the fragments fill the accumulation registers and the accumulators live in the
+        // architectural ones.)
+        constexpr int kWant = C::KS * 4 > 256 ? 64 : (256 - 16 * C::NBW - 16) / 4;
+        constexpr int kInAcc = kWant < C::KS ? kWant : C::KS;
 #pragma unroll
         for (int ks = 0; ks < kInAcc; ++ks) asm volatile("" : "+a"(qf[ks]));
     }
@@ -465,13 +480,19 @@ __device__ __forceinline__ void wide_window(const AttnParams &p, char *smem, int
             next_stage = smem_lds + sidx * C::STAGE;
             ++next_blk;
         }
-        if (n == 0)
-            wide_step<C, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
-        else
-            wide_step_steady<C>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
+        if constexpr (C::PIPELINED) {
+            if (n == 0)
+                wide_step<C, true, false>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
+            else
+                wide_step_steady<C>(st, st_prev, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
+        } else {
+            // two stages: everything of block n now, while block n+1 loads into the other stage
+            wide_step<C, true, false>(st, st, ln, qf, acc, pf, m_run, l_run, dma, next_stage, load_next);
+            wide_step<C, false, true>(st, st, ln, qf, acc, pf, m_run, l_run, dma, 0u, false);
+        }
         st_prev = st;
     }
-    if (nblk > 0) wide_step<C, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run, dma, 0u, false);
+    if (C::PIPELINED && nblk > 0) wide_step<C, false, true>(st_prev, st_prev, ln, qf, acc, pf, m_run, l_run, dma, 0u, false);
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -485,7 +506,7 @@ __device__ __forceinline__ void wide_window(const AttnParams &p, char *smem, int
                 f32x4 out;
 #pragma unroll
                 for (int x = 0; x < 4; ++x) out[x] = acc[nbw][4 * a + x] * inv;
-                *reinterpret_cast<f32x4 *>(orow + 32 * C::col_block(nbw) + 8 * a + 4 * g) = out;
+                if (C::col_block(nbw) < C::NB) *reinterpret_cast<f32x4 *>(orow + 32 * C::col_block(nbw) + 8 * a + 4 * g) = out;
             }
         if (WIN == 0 && g == 0) p.lse2[(size_t)bh * p.Lp + irow] = lse2;
     } else {
@@ -584,7 +605,7 @@ __device__ __forceinline__ void wide_window(const AttnParams &p, char *smem, int
     }
 }
 
-template <int DZ, int CZ>
+template <int DZ, int CZ, int NWIN>
 __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -597,12 +618,19 @@ __global__ __launch_bounds__(256, 1) void fipa_attn_fwd_wide_kernel(AttnParams p
     // wanted by every compute unit of the XCD at the same moment.
     const int chunk = (p.total_tiles + 7) / 8;
     const int slot = blockIdx.x / 8;
-    const int logical = (blockIdx.x % 8) * chunk + slot / 2;
+    const int logical = (blockIdx.x % 8) * chunk + slot / NWIN;
     if (logical >= p.total_tiles) return;
-    if (slot % 2 == 0)
-        wide_window<DZ, CZ, 0>(p, smem, logical);
-    else
-        wide_window<DZ, CZ, 1>(p, smem, logical);
+    const int win = slot % NWIN;
+    if (win == 0)
+        wide_window<DZ, CZ, NWIN, 0>(p, smem, logical);
+    else if (NWIN == 2 || win == 1)
+        wide_window<DZ, CZ, NWIN, 1>(p, smem, logical);
+    else if constexpr (NWIN > 2) {
+        if (win == 2)
+            wide_window<DZ, CZ, NWIN, 2>(p, smem, logical);
+        else
+            wide_window<DZ, CZ, NWIN, 3>(p, smem, logical);
+    }
 }
 
 }  // namespace
@@ -611,30 +639,32 @@ bool attn_fwd_wide_fused_supported(int DZ, int cz) { return DZ == 512 && (cz == 
 
 namespace {
 
-template <int CZ>
+template <int DZ, int CZ, int NWIN>
 hipError_t launch_wide(const AttnParams &p, hipStream_t stream)
 {
-    constexpr int lds = WideCfg<512, CZ, 0>::LDS_BYTES;
+    static_assert(NWIN == 2 || NWIN == 4, "window dispatch of the kernel");
+    constexpr int lds = WideCfg<DZ, CZ, NWIN, 0>::LDS_BYTES;
     static LdsLimit lds_limit;
-    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_attn_fwd_wide_kernel<512, CZ>, lds);
+    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_attn_fwd_wide_kernel<DZ, CZ, NWIN>, lds);
     if (e != hipSuccess) return e;
     const int chunk = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL((fipa_attn_fwd_wide_kernel<512, CZ>), dim3(chunk * 8 * 2), dim3(256), lds, stream, p);
+    hipLaunchKernelGGL((fipa_attn_fwd_wide_kernel<DZ, CZ, NWIN>), dim3(chunk * 8 * NWIN), dim3(256), lds, stream, p);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// fused: steps 8-9 of Algorithm 1 run inside the kernel (AlphaFold2 head shape, c_z of
+// fused: steps 8-9 of Algorithm 1 run inside the kernel (width 576, AlphaFold2 head shape, c_z of
 // attn_fwd_wide_fused_supported); otherwise the kernel leaves O^ and the log-sum-exp in the workspace.
 hipError_t launch_attn_fwd_wide_bf16(const AttnParams &p, int DZ, bool fused, hipStream_t stream)
 {
+    if (DZ == 1024) return fused ? hipErrorInvalidValue : launch_wide<1024, 0, 4>(p, stream);
     if (DZ != 512) return hipErrorInvalidValue;
-    if (!fused) return launch_wide<0>(p, stream);
+    if (!fused) return launch_wide<512, 0, 2>(p, stream);
     switch (p.cz) {
-        case 64: return launch_wide<64>(p, stream);
-        case 128: return launch_wide<128>(p, stream);
-        case 256: return launch_wide<256>(p, stream);
+        case 64: return launch_wide<512, 64, 2>(p, stream);
+        case 128: return launch_wide<512, 128, 2>(p, stream);
+        case 256: return launch_wide<512, 256, 2>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

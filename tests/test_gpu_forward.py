@@ -135,6 +135,19 @@ def test_bf16_width512_other_factor_shapes(cz, r, kw):
             assert np.all(got[n][b, int(ln):] == 0), (n, b)
 
 
+@pytest.mark.parametrize("cz,r,kw", [(128, 8, {}), (64, 16, {}), (256, 4, {}), (128, 8, dict(c=8, Pq=2, Pv=3))])
+def test_bf16_width1024_rank8(cz, r, kw):
+    # r*c_z = 1024 (lifted width 1088: rank 8 at c_z = 128): four windows, two LDS stages, separate epilogue;
+    # several key blocks, three query tiles with a ragged tail, a masked batch, spread attention
+    inp = wl.make_inputs(3, B=2, L=300, H=2, cz=cz, r=r, min_len=40, trans_scale=0.3, **kw)
+    gu.check(inp, label="bf16 width 1024: cz=%d r=%d %s" % (cz, r, kw))
+    gu.check(wl.make_inputs(3, B=1, L=70, H=1, cz=cz, r=r, varlen=False, **kw), label="bf16 width 1024 L=70")
+    got = gu.run_gpu(inp)
+    for b, ln in enumerate(inp["lengths"]):
+        for n in gu.NAMES:
+            assert np.all(got[n][b, int(ln):] == 0), (n, b)
+
+
 def test_bf16_workload3_sampled_rows():
     # variable-length padded batch, lengths U[1024, 8192], r = 4: 256 rows of every batch element
     # (first / last valid / first padded, one in every 128-row query tile, the rest random) against
