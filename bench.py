@@ -246,6 +246,7 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="workload index (2 = the L=2048 headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true", help="skip the fipa_backward leg (workload 4)")
+    ap.add_argument("--backward-workload", type=int, default=4, help="workload of the fipa_backward leg (3: the ragged rank-4 batch)")
     ap.add_argument("--no-module", action="store_true", help="skip the module leg (fipa_module_forward / backward)")
     ap.add_argument("--no-measured-peaks", action="store_true", help="skip the MFMA-only and copy probes")
     ap.add_argument("--wave-specialised", action="store_true",
@@ -354,7 +355,8 @@ def main():
     if not args.no_module:
         result["module"] = module_leg(args.workload)
     if not args.no_backward:
-        result["backward"] = backward_leg(4)
+        result["backward"] = backward_leg(args.backward_workload, steps=30 if args.backward_workload == 4 else 5,
+                                          warmup=10 if args.backward_workload == 4 else 2)
     if args.packed_leg:
         result["packed"] = packed_leg()
     if not args.no_cpu_baseline:

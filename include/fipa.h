@@ -158,7 +158,7 @@ int fipa_forward_static(const fipa_desc *desc,
  *     desc->flags, which asks for the smallest workspace): chain after chain on the caller's
  *     stream, as B = 1 problems on offset pointers sharing a workspace sized for the longest
  *     chain; the backward adds the chains' d_gamma and d_w_b in chain order.
- * Nothing is computed for padding either way.  fipa_backward_packed: bf16, r*cz <= 256; gradient
+ * Nothing is computed for padding either way.  fipa_backward_packed: bf16, r*cz <= 512; gradient
  * tensors packed like their inputs, d_gamma [H] and d_w_b [H, cz] (or NULL) summed over all chains,
  * d_rot / d_trans [total, 3, 3] / [total, 3] (both or neither).
  */
@@ -221,7 +221,8 @@ int fipa_knn_distogram(int32_t B, int32_t L, int32_t k, int32_t n_bins, float d_
  * read (the attention weights and outputs are recomputed from the inputs); each may be NULL.
  * d_gamma, d_w_b, d_rot and d_trans are overwritten (not accumulated).  The paper gives no backward; it is the chain
  * rule through Eqs. 3-4 and z_ij = z1_i^T z2_j.
- * Supported for FIPA_DTYPE_BF16 with r*cz <= 256; otherwise FIPA_ERR_UNSUPPORTED.
+ * Supported for FIPA_DTYPE_BF16 with r*cz <= 512 (512, the rank-4 shape at cz = 128, on plain gradient
+ * kernels that are not tuned); otherwise FIPA_ERR_UNSUPPORTED.
  */
 int fipa_backward(const fipa_desc *desc,
                   const void *q, const void *k, const void *v,
@@ -274,7 +275,7 @@ int fipa_module_forward(const fipa_desc *desc, int32_t d_s,
  * d_trans, both or neither).  Everything is recomputed from the inputs: no forward results are
  * taken.  The bfloat16 rounding of Eq. 1's results is transparent to the gradient; the norm of a
  * zero vector contributes zero.  All outputs are overwritten.
- * Shapes: as fipa_module_forward, and r*cz <= 256, N_in % 8 == 0; else FIPA_ERR_UNSUPPORTED.
+ * Shapes: as fipa_module_forward, and r*cz <= 512, N_in % 8 == 0; else FIPA_ERR_UNSUPPORTED.
  */
 int fipa_module_backward_workspace_bytes(const fipa_desc *desc, int32_t d_s, size_t *bytes);
 int fipa_module_backward(const fipa_desc *desc, int32_t d_s,

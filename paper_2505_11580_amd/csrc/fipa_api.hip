@@ -29,7 +29,7 @@ int check_desc(const fipa_desc *d, bool backward)
             d->c + 8 * ((6 * PH + 3) / 4) > 64)
             return FIPA_ERR_UNSUPPORTED;
         if (DZ != 32 && DZ != 64 && DZ != 128 && DZ != 256 && DZ != 512 && DZ != 1024) return FIPA_ERR_UNSUPPORTED;
-        if (DZ >= 512 && backward) return FIPA_ERR_UNSUPPORTED;
+        if (DZ > 512 && backward) return FIPA_ERR_UNSUPPORTED;
     }
     return FIPA_OK;
 }

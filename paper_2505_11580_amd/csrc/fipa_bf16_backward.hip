@@ -349,7 +349,7 @@ struct BwdLayout {
 BwdLayout bwd_layout(const fipa_desc &d)
 {
     BwdLayout w;
-    w.f = bf16_layout(d, true);
+    w.f = bf16_layout(d, true, true);
     const size_t BHL = (size_t)d.B * d.H * w.f.Lp;
     const size_t D = kDH + w.f.DZ;
     size_t off = w.f.total;
@@ -443,7 +443,8 @@ hipError_t backward_forward_part(const fipa_desc &d, const FwdArgs &f, const Bwd
     at.nQT = w.f.Lp / kTileQ; at.total_tiles = at.nQT * d.B * d.H; at.cz = d.cz; at.r = d.r; at.w_b = f.w_b; at.w_L = d.w_L;
     at.plan = w.f.plan; at.partial = nullptr; at.counters = nullptr;  // (unfused: never split)
     at.deal = f.mask != nullptr || f.cu != nullptr;
-    e = launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
+    // (width 576: the two-window kernel in its form that leaves O^ in the workspace)
+    e = w.f.DZ > 256 ? launch_attn_fwd_wide_bf16(at, w.f.DZ, false, stream) : launch_attn_fwd_bf16(at, w.f.DZ, false, stream);
     if (e != hipSuccess || !f.o) return e;
 
     EpiParams ep;

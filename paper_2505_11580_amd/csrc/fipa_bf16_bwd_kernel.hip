@@ -18,6 +18,12 @@
 //
 // The streamed blocks arrive in a ring of three LDS stages by direct global -> LDS loads issued
 // one block ahead; one barrier per block publishes the new stage and releases the oldest.
+//
+// Lifted width 576 (r*c_z = 512): the two sets of stationary fragments take 288 registers per lane,
+// so a workgroup accumulates one of three windows of 192 output columns (template parameters NWIN,
+// WIN) and the small products are formed once per window; a streamed block of queries (q^ and dO^,
+// 78 KB) fits LDS twice only, so DK and DV run without the pipeline across blocks (everything of
+// block n while block n+1 loads).  Plain forms that make the shape trainable; not tuned.
 #include "fipa_gfx950.h"
 
 namespace fipa {
@@ -27,13 +33,15 @@ namespace {
 constexpr int kSB = 32;              // streamed rows per block
 constexpr int kHS = kDH * 2 + 16;    // LDS row stride (bytes) of a 64-column head-specific tile
 
-template <int DZ, int MODE>
+template <int DZ, int MODE, int NWIN = 1, int WIN = 0>
 struct BwdCfg {
     static constexpr int D = kDH + DZ;           // lifted width
     static constexpr int KS = D / 16;            // k-steps of the small products
     static constexpr int KSH = kDH / 16;
     static constexpr int NB = D / 32;            // 32-row blocks of the accumulator
     static constexpr int NBH = kDH / 32;
+    static_assert(NB % NWIN == 0, "windows must tile the output columns");
+    static constexpr int NBW = NB / NWIN;        // blocks this workgroup accumulates: WIN * NBW .. + NBW - 1
     static constexpr int ZS = DZ * 2 + 48;       // LDS row stride of a pair-part tile: conflict free for row reads and transposing reads
     static constexpr int Z_SPR = ZS / 16, H_SPR = kHS / 16;   // 16-byte slots per row
     static constexpr int NZ = (kSB * Z_SPR + 63) / 64;         // wave-wide 1 KiB loads per pair-part tile
@@ -48,9 +56,14 @@ struct BwdCfg {
     static constexpr int NI = (kSharedZ ? NZ : 2 * NZ) + 2 * NH;
     static constexpr int NIW = (NI + 3) / 4;     // per wave
     static constexpr int NSC = MODE == FIPA_BWD_DK ? 2 : 1;   // per-streamed-row scalars: logit term (+ D for DK)
-    static constexpr int SC_OFF = NIW * 4 * 1024;              // each scalar load covers 1 KiB (its first 128 bytes are data)
+    // Three stages where they fit.  Otherwise two, without the spare KiB for the surplus entries of
+    // the last round of loads (the waves that would issue them skip them; every wait in this kernel
+    // is for all outstanding loads, so the waves need not issue the same number).
+    static constexpr bool PIPELINED = 3 * (NIW * 4 * 1024 + 2 * 1024) <= 160 * 1024;
+    static constexpr bool kSkipSurplus = !PIPELINED;
+    static constexpr int SC_OFF = (PIPELINED ? NIW * 4 : NI) * 1024;   // each scalar load covers 1 KiB (its first 128 bytes are data)
     static constexpr int STAGE = SC_OFF + 2 * 1024;
-    static constexpr int NSTAGE = 3;
+    static constexpr int NSTAGE = PIPELINED ? 3 : 2;
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static constexpr int VM_PER_BLOCK = NIW + NSC;             // vector-memory ops one wave issues per block
@@ -59,42 +72,45 @@ struct BwdCfg {
 // The direct loads of one wave (see dma16): wave w issues entries w, w+4, ... of the flat list;
 // surplus entries repeat entry 0 into the spare KiB the stage keeps for them.  Lanes whose slot
 // lies in the row padding or past the last row fetch element 0 of the tile again (harmless).
-template <int DZ, int MODE>
+template <class C>
 struct BwdDma {
-    using C = BwdCfg<DZ, MODE>;
     const char *src[C::NIW + C::NSC];  // wave-uniform
     int step[C::NIW + C::NSC];         // wave-uniform: bytes from one block to the next
     int voff[C::NIW + C::NSC];         // per lane: byte offset of the previously requested block
     unsigned wave_lds;
+    int wave;                          // wave-uniform
 };
 
-template <int DZ, int MODE, int K = 0>
-__device__ __forceinline__ void bwd_issue_block(BwdDma<DZ, MODE> &d, unsigned stage)
+// Entry K of the loads of a block.  (Entry wave + 4 K of the flat list; past its end: a surplus entry.)
+template <class C, int K>
+__device__ __forceinline__ void bwd_issue_one(BwdDma<C> &d, unsigned stage)
 {
-    using C = BwdCfg<DZ, MODE>;
     if constexpr (K < C::NIW) {
+        if (C::kSkipSurplus && d.wave + 4 * K >= C::NI) return;
         dma16<4096 * K>(d.src[K], d.voff[K], d.step[K], stage + d.wave_lds);
-        bwd_issue_block<DZ, MODE, K + 1>(d, stage);
-    } else if constexpr (K < C::NIW + C::NSC) {
+    } else {
         dma16<C::SC_OFF + 1024 * (K - C::NIW)>(d.src[K], d.voff[K], d.step[K], stage);
-        bwd_issue_block<DZ, MODE, K + 1>(d, stage);
+    }
+}
+
+template <class C, int K = 0>
+__device__ __forceinline__ void bwd_issue_block(BwdDma<C> &d, unsigned stage)
+{
+    if constexpr (K < C::NIW + C::NSC) {
+        bwd_issue_one<C, K>(d, stage);
+        bwd_issue_block<C, K + 1>(d, stage);
     }
 }
 
 // Entry k of the loads of a block (k is a compile-time constant after unrolling).
-template <int DZ, int MODE, int K = 0>
-__device__ __forceinline__ void bwd_issue_entry(BwdDma<DZ, MODE> &d, unsigned stage, int k)
+template <class C, int K = 0>
+__device__ __forceinline__ void bwd_issue_entry(BwdDma<C> &d, unsigned stage, int k)
 {
-    using C = BwdCfg<DZ, MODE>;
     if constexpr (K < C::NIW + C::NSC) {
-        if (k == K) {
-            if constexpr (K < C::NIW)
-                dma16<4096 * K>(d.src[K], d.voff[K], d.step[K], stage + d.wave_lds);
-            else
-                dma16<C::SC_OFF + 1024 * (K - C::NIW)>(d.src[K], d.voff[K], d.step[K], stage);
-        } else {
-            bwd_issue_entry<DZ, MODE, K + 1>(d, stage, k);
-        }
+        if (k == K)
+            bwd_issue_one<C, K>(d, stage);
+        else
+            bwd_issue_entry<C, K + 1>(d, stage, k);
     }
 }
 
@@ -107,13 +123,13 @@ struct BwdLane {
 // current block followed by its share of the first KS - kTail accumulation MFMAs of the previous
 // block; then the held-back kTail accumulation MFMAs, which are issued among the exponentials of
 // the new weights.  kind: 0 = S, 1 = dP, 2 = accumulation; idx: k-step, or accumulation number.
-template <int DZ, int MODE>
+template <class C, int MODE>
 struct BwdOps {
-    using C = BwdCfg<DZ, MODE>;
     static constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
     static constexpr int KS = C::KS;
-    static constexpr int kTail = KS >= 16 ? 8 : KS / 2;  // (8, 12 and 16 measured: 1.96, 2.00, 2.00 ms of gradient kernels at L = 4096)
-    static constexpr int kInLoop = KS - kTail;
+    static constexpr int NACC = 2 * C::NBW;  // accumulation MFMAs of a block (= KS when there is one window)
+    static constexpr int kTail = NACC >= 16 ? 8 : NACC / 2;  // (8, 12 and 16 measured: 1.96, 2.00, 2.00 ms of gradient kernels at L = 4096)
+    static constexpr int kInLoop = NACC - kTail;
     static constexpr int NL = (kNeedDP ? 2 : 1) * KS + kInLoop;  // before the weights
     static constexpr int NT = NL + kTail;
     struct Op {
@@ -144,15 +160,14 @@ struct BwdOps {
 // operand of every MFMA is requested kLA MFMAs ahead, in order of use, into a small ring; one
 // load entry of the next block goes out per k-step; the weights of the current block are formed
 // pair by pair between the held-back accumulation MFMAs.
-template <int DZ, int MODE>
+template <class C, int MODE, int WIN>
 __device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, const char *__restrict__ st_prev, const BwdLane &ln,
-                                                const bf16x8 (&y1f)[BwdCfg<DZ, MODE>::KS],
-                                                const bf16x8 (&y2f)[MODE != FIPA_BWD_DV ? BwdCfg<DZ, MODE>::KS : 1],
-                                                f32x16 (&acc)[BwdCfg<DZ, MODE>::NB], bf16x8 (&wf)[2], float &wsum,
-                                                BwdDma<DZ, MODE> &dma, unsigned next_stage)
+                                                const bf16x8 (&y1f)[C::KS],
+                                                const bf16x8 (&y2f)[MODE != FIPA_BWD_DV ? C::KS : 1],
+                                                f32x16 (&acc)[C::NBW], bf16x8 (&wf)[2], float &wsum,
+                                                BwdDma<C> &dma, unsigned next_stage)
 {
-    using C = BwdCfg<DZ, MODE>;
-    using O = BwdOps<DZ, MODE>;
+    using O = BwdOps<C, MODE>;
     constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
     constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;
     constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
@@ -175,7 +190,7 @@ __device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, con
             const char *s2 = ks < C::KSH ? st + C::X2H_OFF + ln.ka_h + ks * 32 : st + C::X2Z_OFF + ln.ka_z + (ks - C::KSH) * 32;
             return *reinterpret_cast<const bf16x8 *>(s2);
         } else {
-            const int nb = o.idx >> 1, tt = o.idx & 1;
+            const int nb = WIN * C::NBW + (o.idx >> 1), tt = o.idx & 1;  // block of the whole lifted row
             const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
                                           : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
             const int rs = nb < C::NBH ? kHS : C::ZS;
@@ -231,7 +246,7 @@ __device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, con
             if (next_stage != 0xFFFFFFFFu) {
 #pragma unroll
                 for (int e = o.idx * kEntries / kDmaSteps; e < (o.idx + 1) * kEntries / kDmaSteps; ++e)
-                    if (e < kEntries) bwd_issue_entry<DZ, MODE>(dma, next_stage, e);
+                    if (e < kEntries) bwd_issue_entry<C>(dma, next_stage, e);
             }
         } else if constexpr (o.kind == 1) {
             dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % kRing], y2f[kNeedDP ? o.idx : 0], dpacc, 0, 0, 0);
@@ -248,21 +263,20 @@ __device__ __forceinline__ void bwd_step_steady(const char *__restrict__ st, con
 // `st` (CUR: the first block, nothing to accumulate yet) or the accumulation of the last block
 // (PREV: stage `st_prev`, weights `wf`).  On exit of a CUR step `wf` holds the block's weights.
 // The loads of the next block (stage `next_stage`) are issued spread over the k-steps.
-template <int DZ, int MODE, bool CUR, bool PREV>
+template <class C, int MODE, int WIN, bool CUR, bool PREV>
 __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char *__restrict__ st_prev, const BwdLane &ln,
-                                         const bf16x8 (&y1f)[BwdCfg<DZ, MODE>::KS],
-                                         const bf16x8 (&y2f)[MODE != FIPA_BWD_DV ? BwdCfg<DZ, MODE>::KS : 1],
-                                         f32x16 (&acc)[BwdCfg<DZ, MODE>::NB], bf16x8 (&wf)[2], float &wsum,
-                                         BwdDma<DZ, MODE> &dma, unsigned next_stage)
+                                         const bf16x8 (&y1f)[C::KS],
+                                         const bf16x8 (&y2f)[MODE != FIPA_BWD_DV ? C::KS : 1],
+                                         f32x16 (&acc)[C::NBW], bf16x8 (&wf)[2], float &wsum,
+                                         BwdDma<C> &dma, unsigned next_stage)
 {
     static_assert(CUR != PREV, "the steady step is bwd_step_steady");
-    using C = BwdCfg<DZ, MODE>;
     constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
     constexpr int AZ_OFF = MODE == FIPA_BWD_DV ? C::X2Z_OFF : C::X1Z_OFF;  // tile the accumulation reads
     constexpr int AH_OFF = MODE == FIPA_BWD_DV ? C::X2H_OFF : C::X1H_OFF;
     constexpr int kEntries = C::NIW + C::NSC;  // load entries of a block
-    f32x16 sacc, dpacc;
     if constexpr (CUR) {
+        f32x16 sacc, dpacc;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             const f32x4 sb = *reinterpret_cast<const f32x4 *>(st + C::SC_OFF + (8 * a + 4 * ln.g) * 4);
@@ -277,10 +291,8 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
                 for (int x = 0; x < 4; ++x) dpacc[4 * a + x] = -ln.dlane;
             }
         }
-    }
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) {
-        if constexpr (CUR) {
+        for (int ks = 0; ks < C::KS; ++ks) {
             // S (and dP) of the current block: [32 streamed rows] x [32 stationary rows (lanes)]
             const char *s1 = ks < C::KSH ? st + C::X1H_OFF + ln.ka_h + ks * 32 : st + C::X1Z_OFF + ln.ka_z + (ks - C::KSH) * 32;
             const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(s1);
@@ -293,27 +305,9 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
             if (next_stage != 0xFFFFFFFFu) {
 #pragma unroll
                 for (int e = ks * kEntries / C::KS; e < (ks + 1) * kEntries / C::KS; ++e)
-                    bwd_issue_entry<DZ, MODE>(dma, next_stage, e);
+                    bwd_issue_entry<C>(dma, next_stage, e);
             }
         }
-        if constexpr (PREV) {
-            // acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
-            const int nb = ks >> 1, tt = ks & 1;
-            const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
-                                          : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
-            const int rs = nb < C::NBH ? kHS : C::ZS;
-            const bf16x4 lo = lds_read_tr(src);
-            const bf16x4 hi = lds_read_tr(src + 8 * rs);
-            bf16x8 a;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                a[x] = lo[x];
-                a[4 + x] = hi[x];
-            }
-            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wf[tt], acc[nb], 0, 0, 0);
-        }
-    }
-    if constexpr (CUR) {
         // weights of the accumulating product: P (DV) or dS = P (dP - D) (DQ, DK)
         unsigned wp[8];
 #pragma unroll
@@ -328,18 +322,33 @@ __device__ __forceinline__ void bwd_step(const char *__restrict__ st, const char
         wf[0] = __builtin_bit_cast(bf16x8, (u32x4){wp[0], wp[1], wp[2], wp[3]});
         wf[1] = __builtin_bit_cast(bf16x8, (u32x4){wp[4], wp[5], wp[6], wp[7]});
     }
+    if constexpr (PREV) {
+#pragma unroll
+        for (int i = 0; i < 2 * C::NBW; ++i) {
+            // acc^T[feature, stationary row] += X^T[feature, streamed row] W[streamed row, stationary row]
+            const int nb = WIN * C::NBW + (i >> 1), tt = i & 1;  // block of the whole lifted row
+            const char *src = nb < C::NBH ? st_prev + AH_OFF + ln.va_h + 16 * tt * kHS + nb * 64
+                                          : st_prev + AZ_OFF + ln.va_z + 16 * tt * C::ZS + (nb - C::NBH) * 64;
+            const int rs = nb < C::NBH ? kHS : C::ZS;
+            const bf16x4 lo = lds_read_tr(src);
+            const bf16x4 hi = lds_read_tr(src + 8 * rs);
+            bf16x8 a;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                a[x] = lo[x];
+                a[4 + x] = hi[x];
+            }
+            acc[i >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wf[tt], acc[i >> 1], 0, 0, 0);
+        }
+    }
 }
 
-template <int DZ, int MODE>
-__global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
+// One window (of NWIN) of the output columns of one tile of stationary rows.
+template <int DZ, int MODE, int NWIN, int WIN>
+__device__ __forceinline__ void bwd_window(const BwdParams &p, char *smem, int logical)
 {
-    using C = BwdCfg<DZ, MODE>;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    using C = BwdCfg<DZ, MODE, NWIN, WIN>;
     constexpr bool kNeedDP = MODE != FIPA_BWD_DV;
-
-    const int chunk = (p.total_tiles + 7) / 8;
-    const int logical = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
-    if (logical >= p.total_tiles) return;
     const int nT = p.Lp / kTileQ;
     const int bh_pos = logical / nT, tile = logical - bh_pos * nT;
     const int bh = p.deal ? dealt_pair_by_length(bh_pos, p.kvlen, p.B, p.H, threadIdx.x & 63) : bh_pos;
@@ -354,13 +363,13 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     // Stationary rows past the last valid residue of the chain (padding of a ragged batch) take
     // part in nothing: zero gradient.
     if (tile * kTileQ >= kvlen) {
-        float *orow = p.out + ((size_t)bh * p.Lp + srow) * C::D;
+        float *orow = p.out + ((size_t)bh * p.Lp + srow) * C::D + 32 * WIN * C::NBW;
 #pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb)
+        for (int nb = 0; nb < C::NBW; ++nb)
 #pragma unroll
             for (int a = 0; a < 4; ++a)
                 *reinterpret_cast<f32x4 *>(orow + 32 * nb + 8 * a + 4 * g) = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (p.wsum && g == 0) p.wsum[(size_t)bh * p.Lp + srow] = 0.f;
+        if (WIN == 0 && p.wsum && g == 0) p.wsum[(size_t)bh * p.Lp + srow] = 0.f;
         return;
     }
 
@@ -387,8 +396,9 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     }
 
     // ---- direct global -> LDS loads of the streamed blocks -------------------------------------
-    BwdDma<DZ, MODE> dma;
+    BwdDma<C> dma;
     dma.wave_lds = 1024u * wave;
+    dma.wave = wave;
 #pragma unroll
     for (int k = 0; k < C::NIW; ++k) {
         int i = wave + 4 * k;
@@ -417,7 +427,7 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
         dma.voff[C::NIW + 1] = min(lane, 7) * 16 - dma.step[C::NIW + 1];
     }
     const unsigned smem_lds = lds_address(smem);
-    if (nblk > 0) bwd_issue_block<DZ, MODE>(dma, smem_lds);
+    if (nblk > 0) bwd_issue_block<C>(dma, smem_lds);
 
     // stationary fragments: features 16*ks + 8*g .. +7 of row srow
     bf16x8 y1f[C::KS], y2f[kNeedDP ? C::KS : 1];
@@ -436,17 +446,19 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     // operand directly; the accumulators and the small products, which the vector ALU works on,
     // are left to the register allocator (this file is compiled with the MFMA results in the
     // general vector-register class: see build.py).
+    // (At width 576 the two sets are 288 registers: 64 fragments fill the accumulation registers.)
+    constexpr int kPin2 = !kNeedDP ? 0 : (2 * C::KS <= 64 ? C::KS : 64 - C::KS);
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
         asm volatile("" : "+a"(y1f[ks]));
-        if (kNeedDP) asm volatile("" : "+a"(y2f[ks]));
+        if (ks < kPin2) asm volatile("" : "+a"(y2f[ks]));
     }
     const float slane = slane_src[srow];
     const float dlane = dlane_src ? dlane_src[srow] : 0.f;
 
-    f32x16 acc[C::NB];
+    f32x16 acc[C::NBW];
 #pragma unroll
-    for (int nb = 0; nb < C::NB; ++nb)
+    for (int nb = 0; nb < C::NBW; ++nb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
     float wsum = 0.f;  // sum over streamed rows of the rounded dS (DQ: row sums, DK: column sums)
@@ -477,18 +489,25 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
         sidx = sidx + 1 < C::NSTAGE ? sidx + 1 : 0;
         // (0xFFFFFFFF: no next block)
         const unsigned next_stage = n + 1 < nblk ? smem_lds + sidx * C::STAGE : 0xFFFFFFFFu;
-        if (n == 0)
-            bwd_step<DZ, MODE, true, false>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
-        else
-            bwd_step_steady<DZ, MODE>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
+        if constexpr (C::PIPELINED) {
+            if (n == 0)
+                bwd_step<C, MODE, WIN, true, false>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
+            else
+                bwd_step_steady<C, MODE, WIN>(st, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
+        } else {
+            // two stages: everything of block n now, while block n+1 loads into the other stage
+            bwd_step<C, MODE, WIN, true, false>(st, st, ln, y1f, y2f, acc, wf, wsum, dma, next_stage);
+            bwd_step<C, MODE, WIN, false, true>(st, st, ln, y1f, y2f, acc, wf, wsum, dma, 0xFFFFFFFFu);
+        }
         st_prev = st;
     }
-    if (nblk > 0) bwd_step<DZ, MODE, false, true>(st_prev, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, 0xFFFFFFFFu);
+    if (C::PIPELINED && nblk > 0)
+        bwd_step<C, MODE, WIN, false, true>(st_prev, st_prev, ln, y1f, y2f, acc, wf, wsum, dma, 0xFFFFFFFFu);
 
     // ---- write acc^T: row srow, columns 32*nb + 8*(r/4) + 4*g + r%4 -------------------------------
-    float *orow = p.out + ((size_t)bh * p.Lp + srow) * C::D;
+    float *orow = p.out + ((size_t)bh * p.Lp + srow) * C::D + 32 * WIN * C::NBW;
 #pragma unroll
-    for (int nb = 0; nb < C::NB; ++nb)
+    for (int nb = 0; nb < C::NBW; ++nb)
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             f32x4 out;
@@ -496,21 +515,45 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
             for (int x = 0; x < 4; ++x) out[x] = acc[nb][4 * a + x];
             *reinterpret_cast<f32x4 *>(orow + 32 * nb + 8 * a + 4 * g) = out;
         }
-    if (p.wsum) {
+    if (WIN == 0 && p.wsum) {  // (every window forms the same sums)
         const float tot = wsum + __shfl_xor(wsum, 32);
         if (g == 0) p.wsum[(size_t)bh * p.Lp + srow] = tot;
+    }
+}
+
+template <int DZ, int MODE, int NWIN>
+__global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // each XCD gets a contiguous run of tiles; the windows of a tile are neighbours in its launch order
+    const int chunk = (p.total_tiles + 7) / 8;
+    const int slot = blockIdx.x / 8;
+    const int logical = (blockIdx.x % 8) * chunk + slot / NWIN;
+    if (logical >= p.total_tiles) return;
+    if constexpr (NWIN == 1) {
+        bwd_window<DZ, MODE, 1, 0>(p, smem, logical);
+    } else {
+        static_assert(NWIN == 3, "window dispatch");
+        const int win = slot % NWIN;
+        if (win == 0)
+            bwd_window<DZ, MODE, NWIN, 0>(p, smem, logical);
+        else if (win == 1)
+            bwd_window<DZ, MODE, NWIN, 1>(p, smem, logical);
+        else
+            bwd_window<DZ, MODE, NWIN, 2>(p, smem, logical);
     }
 }
 
 template <int DZ, int MODE>
 hipError_t launch(const BwdParams &p, hipStream_t stream)
 {
-    using C = BwdCfg<DZ, MODE>;
+    constexpr int NWIN = DZ > 256 ? 3 : 1;
+    using C = BwdCfg<DZ, MODE, NWIN, 0>;
     static LdsLimit lds_limit;
-    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_bwd_kernel<DZ, MODE>, C::LDS_BYTES);
+    hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_bwd_kernel<DZ, MODE, NWIN>, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     const int chunk = (p.total_tiles + 7) / 8;
-    hipLaunchKernelGGL((fipa_bwd_kernel<DZ, MODE>), dim3(chunk * 8), dim3(256), C::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((fipa_bwd_kernel<DZ, MODE, NWIN>), dim3(chunk * 8 * NWIN), dim3(256), C::LDS_BYTES, stream, p);
     return hipGetLastError();
 }
 
@@ -534,6 +577,7 @@ hipError_t launch_bwd_bf16(const BwdParams &p, int DZ, int mode, hipStream_t str
         case 64: return launch_mode<64>(p, mode, stream);
         case 128: return launch_mode<128>(p, mode, stream);
         case 256: return launch_mode<256>(p, mode, stream);
+        case 512: return launch_mode<512>(p, mode, stream);
         default: return hipErrorInvalidValue;
     }
 }

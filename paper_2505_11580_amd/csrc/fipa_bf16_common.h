@@ -161,8 +161,9 @@ struct Bf16Layout {
     size_t cen, kvlen, Qh, Qz, Kh, Vh, Z2, kbias, qbias, Ohat, lse2, partial, counters, total;
 };
 
-// with_ohat: the unfused epilogue needs the lifted output O^ in memory.
-inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
+// with_ohat: the unfused epilogue needs the lifted output O^ in memory.  with_qz: the per-head
+// query-side factor vectors are wanted whatever the width (the gradient kernels stream them).
+inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat, bool with_qz = false)
 {
     Bf16Layout w;
     w.Lp = (int)align_up((size_t)d.L, kTileQ);
@@ -180,7 +181,7 @@ inline Bf16Layout bf16_layout(const fipa_desc &d, bool with_ohat)
     w.Qh = take(BH * w.Lp * kDH * 2);
     // (per-head query-side factor vectors: only where the attention kernel does not form them itself,
     // i.e. the unfused path up to width 256, which the backward uses too)
-    w.Qz = with_ohat && w.DZ <= 256 ? take(BH * w.Lp * (size_t)w.DZ * 2) : 0;
+    w.Qz = (with_ohat && w.DZ <= 256) || with_qz ? take(BH * w.Lp * (size_t)w.DZ * 2) : 0;
     w.Kh = take(BH * w.Lp * kDH * 2);
     w.Vh = take(BH * w.Lp * kDH * 2);
     w.Z2 = take((size_t)d.B * w.Lp * w.DZ * 2);

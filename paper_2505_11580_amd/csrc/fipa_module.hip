@@ -513,7 +513,7 @@ ModuleBwdLayout module_bwd_layout(const fipa_desc &d, int d_s)
 bool module_backward_shape_supported(const fipa_desc &d, int d_s)
 {
     const int n_in = d.H * (3 * d.c + 3 * (2 * d.Pq + d.Pv));
-    return module_shape_supported(d, d_s) && n_in % 8 == 0 && (long long)d.r * d.cz <= 256;
+    return module_shape_supported(d, d_s) && n_in % 8 == 0 && (long long)d.r * d.cz <= 512;
 }
 
 bool module_shape_supported(const fipa_desc &d, int d_s)

@@ -79,6 +79,21 @@ def test_backward_masked_odd_pair_count():
     check_backward(wl.make_inputs(4, B=5, L=140, H=3, cz=32, varlen=True, min_len=10, trans_scale=0.5), "bwd varlen B=5 H=3")
 
 
+@pytest.mark.parametrize("kw", [dict(B=1, L=128, H=2), dict(B=2, L=300, H=2, varlen=True, min_len=40, trans_scale=0.3),
+                                dict(B=1, L=200, H=3, cz=256, r=2, trans_scale=0.5), dict(B=2, L=160, H=2, c=8, Pq=2, Pv=3, varlen=True, min_len=30)])
+def test_backward_rank4_width512(kw):
+    # r*c_z = 512 (the rank-4 workload's head shape): three windows of output columns per tile of stationary
+    # rows, queries streamed through two LDS stages; all twelve gradients against the oracle
+    check_backward(wl.make_inputs(3, with_grads=True, **{"varlen": False, **kw}), "bwd width 512 %s" % kw)
+
+
+def test_backward_rank4_ragged_l2048_sampled():
+    # the rank-4 workload's generators at B=2, L<=2048 (ragged, masked): many streamed blocks and tiles per
+    # chain, gradients of 128 sampled residues per chain and the full d_gamma, d_w_b against the row-walking oracle
+    inp = wl.make_inputs(3, B=2, L=2048, H=4, min_len=700, with_grads=True)
+    check_backward(inp, "bwd width 512 ragged L<=2048, 128 sampled residues", samples=wl.select_rows(inp, 128))
+
+
 def test_backward_workload4_full_size_sampled():
     # workload 4 at full size (B=2, L=4096): the gradients of 256 residues per batch element (first,
     # last, one in every 128-row tile, the rest random; each both as query row and as key column)

@@ -96,6 +96,7 @@ def test_module_backward_small_shapes():
     # B*L = 130 is neither a multiple of the row tile nor of the K chunk of the weight gradients
     check_module_backward(wl.make_module_inputs(4, d_s=48, B=1, L=130, H=4, trans_scale=0.3), "module bwd L=130 d_s=48")
     check_module_backward(wl.make_module_inputs(4, d_s=64, B=2, L=96, H=2, cz=32, r=2), "module bwd B=2 L=96 cz=32")
+    check_module_backward(wl.make_module_inputs(4, d_s=64, B=1, L=150, H=2, cz=128, r=4, trans_scale=0.5), "module bwd rank 4")
 
 
 def test_module_backward_masked_and_without_biases():

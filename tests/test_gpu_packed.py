@@ -129,7 +129,8 @@ def packed_backward(inp, flags=0):
 
 @pytest.mark.parametrize("kw", [dict(B=3, L=192, H=3, min_len=40, trans_scale=0.5),
                                 dict(B=5, L=140, H=2, cz=32, min_len=10, trans_scale=0.5),
-                                dict(B=2, L=150, H=2, min_len=60, c=8, Pq=2, Pv=3, cz=32)])
+                                dict(B=2, L=150, H=2, min_len=60, c=8, Pq=2, Pv=3, cz=32),
+                                dict(B=3, L=200, H=2, min_len=50, cz=128, r=4, trans_scale=0.5)])
 def test_packed_backward_matches_the_padded_oracle(kw):
     inp = wl.make_inputs(4, varlen=True, **kw)
     want = ipa_oracle.backward(inp, inp["d_o"], inp["d_o_pts"], inp["d_o_pair"])
