@@ -21,7 +21,8 @@
 //
 // Lifted width 576 (r*c_z = 512): the two sets of stationary fragments take 288 registers per lane,
 // so a workgroup accumulates one of three windows of 192 output columns (template parameters NWIN,
-// WIN) and the small products are formed once per window; a streamed block of queries (q^ and dO^,
+// WIN; DV, with one set of fragments, one of two windows of 288) and the small products are formed once
+// per window; a streamed block of queries (q^ and dO^,
 // 78 KB) fits LDS twice only, so DK and DV run without the pipeline across blocks (everything of
 // block n while block n+1 loads).  Plain forms that make the shape trainable; not tuned.
 #include "fipa_gfx950.h"
@@ -533,13 +534,13 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
     if constexpr (NWIN == 1) {
         bwd_window<DZ, MODE, 1, 0>(p, smem, logical);
     } else {
-        static_assert(NWIN == 3, "window dispatch");
+        static_assert(NWIN == 2 || NWIN == 3, "window dispatch");
         const int win = slot % NWIN;
         if (win == 0)
             bwd_window<DZ, MODE, NWIN, 0>(p, smem, logical);
-        else if (win == 1)
+        else if (NWIN == 2 || win == 1)
             bwd_window<DZ, MODE, NWIN, 1>(p, smem, logical);
-        else
+        else if constexpr (NWIN == 3)
             bwd_window<DZ, MODE, NWIN, 2>(p, smem, logical);
     }
 }
@@ -547,7 +548,8 @@ __global__ __launch_bounds__(256, 1) void fipa_bwd_kernel(BwdParams p)
 template <int DZ, int MODE>
 hipError_t launch(const BwdParams &p, hipStream_t stream)
 {
-    constexpr int NWIN = DZ > 256 ? 3 : 1;
+    // (DV keeps one set of stationary fragments: half of the output columns fit beside it)
+    constexpr int NWIN = DZ > 256 ? (MODE == FIPA_BWD_DV ? 2 : 3) : 1;
     using C = BwdCfg<DZ, MODE, NWIN, 0>;
     static LdsLimit lds_limit;
     hipError_t e = raise_lds_limit(lds_limit, (const void *)fipa_bwd_kernel<DZ, MODE, NWIN>, C::LDS_BYTES);
