@@ -343,6 +343,15 @@ def main():
                      "traffic_source": "not measured for this variant" if over or args.wave_specialised
                      else MEASURED_TRAFFIC.get(args.workload, (None, "not measured for this workload"))[1]},
     }
+    # the pack kernel against the HBM roofline: bytes it must move per residue (bf16 inputs of Algorithm 1
+    # steps 2-6 read once; head-specific lifted rows, the shared z2 copy and the two bias vectors written once)
+    H, DZ = dims["H"], dims["r"] * dims["cz"]
+    pack_bytes = residues * (2 * (3 * H * dims["c"] + 3 * H * (2 * dims["Pq"] + dims["Pv"])) + 48 + 2 * DZ  # read (z1 is the attention kernel's)
+                             + 3 * H * 128 + 2 * DZ + 8 * H)                                                      # written
+    if stage_ms[0] > 0:
+        result["pack_roofline"] = {"kernel": "fipa_pack_heads_af2_bf16_kernel", "bound": "hbm", "bytes": pack_bytes,
+                                   "achieved": pack_bytes / (stage_ms[0] * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                                   "frac": pack_bytes / (stage_ms[0] * 1e-3) / 8e12}
     if not args.no_measured_peaks:
         pk = measured_peaks()
         result["roofline"]["peak_measured"] = pk["mfma_bf16_tflops"]
