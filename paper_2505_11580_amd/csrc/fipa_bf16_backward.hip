@@ -417,7 +417,11 @@ PackParams bwd_pack_params(const fipa_desc &d, const FwdArgs &f, const BwdLayout
     pk.Pv = d.Pv; pk.cz = d.cz; pk.r = d.r; pk.DZ = w.f.DZ;
     pk.w_L = d.w_L; pk.w_C = d.w_C; pk.qk_scale = d.qk_scale;
     pk.skip_qz = false;
-    pk.cen_out = nullptr; pk.kvlen_out = nullptr; pk.counters = nullptr; pk.n_counters = 0;
+    // (with the AlphaFold2 head shape the pack kernel finds the per-batch reference point and key-loop bound itself)
+    const bool prep_in_pack = d.c == 16 && d.Pq == 4 && d.Pv == 8;
+    pk.cen_out = prep_in_pack ? reinterpret_cast<float *>(base + w.f.cen) : nullptr;
+    pk.kvlen_out = prep_in_pack ? reinterpret_cast<int *>(base + w.f.kvlen) : nullptr;
+    pk.counters = nullptr; pk.n_counters = 0;
     return pk;
 }
 
@@ -427,9 +431,12 @@ hipError_t backward_forward_part(const fipa_desc &d, const FwdArgs &f, const Bwd
 {
     float *cen = reinterpret_cast<float *>(base + w.f.cen);
     int *kvlen = reinterpret_cast<int *>(base + w.f.kvlen);
-    hipError_t e = launch_prep(d, f.trans, f.mask, f.cu, cen, kvlen, nullptr, 0, stream);
-    if (e != hipSuccess) return e;
     const PackParams pk = bwd_pack_params(d, f, w, base);
+    hipError_t e = hipSuccess;
+    if (!pk.cen_out) {
+        e = launch_prep(d, f.trans, f.mask, f.cu, cen, kvlen, nullptr, 0, stream);
+        if (e != hipSuccess) return e;
+    }
     e = launch_pack_bf16(pk, stream);
     if (e != hipSuccess) return e;
 
