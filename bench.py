@@ -115,12 +115,36 @@ def backward_leg(workload, steps=30, warmup=10):
     stage_ms, _ = binding.fipa_profile_end()
     pairs = workloads.valid_pairs(inp)
     fpp = workloads.bwd_flops_per_pair(dims)
+
+    # a training step = forward call + backward call: as two independent calls (the backward
+    # recomputes what it needs), and with FIPA_FLAG_KEEP_FORWARD (the forward leaves it in the
+    # backward's workspace)
+    def step_ms(flags, ws):
+        desc.flags = flags
+        out_ws = out["workspace"]
+        out["workspace"] = ws
+        for _ in range(warmup):
+            binding.forward(desc, dev, out)
+            binding.backward(desc, dev, out, grads)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            binding.forward(desc, dev, out)
+            binding.backward(desc, dev, out, grads)
+        torch.cuda.synchronize()
+        out["workspace"] = out_ws
+        desc.flags = 0
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    step_plain = step_ms(0, out["workspace"])
+    step_keep = step_ms(binding.FIPA_FLAG_KEEP_FORWARD, grads["workspace"])
     return {
         "workload": "workload %d: B=%d L=%d H=%d cz=%d r=%d, bf16" % (workload, dims["B"], dims["L"], dims["H"],
                                                                     dims["cz"], dims["r"]),
         "ms_per_call": ms, "value": pairs * fpp / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
         "valid_pairs": pairs, "flops_per_pair": fpp, "steps": steps,
         "stage_ms": {"recompute_forward": stage_ms[0], "gradient_kernels": stage_ms[1], "unpack": stage_ms[2]},
+        "training_step_ms": {"forward_then_backward": step_plain, "with_keep_forward_flag": step_keep},
     }
 
 

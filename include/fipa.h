@@ -71,6 +71,23 @@ typedef struct fipa_desc {
  */
 #define FIPA_FLAG_WAVE_SPECIALISED 1u
 
+/*
+ * Training steps (a forward call followed by the backward call on the same inputs), bf16, the shapes
+ * the backward accepts: fipa_forward / fipa_forward_packed with this flag take a workspace of the
+ * BACKWARD's size and leave in it what the gradient needs from the forward -- the lifted operands of
+ * Algorithm 1 steps 1-6, the un-normalised lifted output O^ and the log-sum-exp -- and
+ * fipa_backward / fipa_backward_packed with this flag, the same descriptor, the same input tensors
+ * and that workspace skip the recomputation (about a sixth of the backward's time at the headline
+ * shape; the forward call is slower by the separate epilogue pass, so the pair gains about a tenth).
+ * Outputs and gradients are the same as without the flag.  The caller keeps the workspace untouched
+ * between the two calls; a backward call with the flag on a workspace that the matching forward call
+ * did not fill returns gradients of garbage without an error.  Not for fipa_forward_static
+ * (FIPA_ERR_UNSUPPORTED); packed batches only where they run as one launch (FIPA_ERR_UNSUPPORTED
+ * with FIPA_FLAG_PACKED_PER_CHAIN or when the plan falls back to chain-by-chain); the fipa_module_*
+ * calls ignore it.
+ */
+#define FIPA_FLAG_KEEP_FORWARD 4u
+
 /* Library version, major*10000 + minor*100 + patch. */
 int fipa_version(void);
 

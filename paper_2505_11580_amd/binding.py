@@ -24,6 +24,7 @@ FIPA_DTYPE_F32 = 0
 FIPA_DTYPE_BF16 = 1
 FIPA_FLAG_WAVE_SPECIALISED = 1  # desc.flags bit: opt-in attention kernel with two waves per SIMD
 FIPA_FLAG_PACKED_PER_CHAIN = 2  # desc.flags bit: packed batches run chain after chain (smallest workspace)
+FIPA_FLAG_KEEP_FORWARD = 4  # desc.flags bit: forward fills a backward-sized workspace, backward skips the recomputation
 
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
            "fipa_packed_workspace_bytes", "fipa_forward_packed", "fipa_backward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",

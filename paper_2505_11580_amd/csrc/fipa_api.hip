@@ -15,7 +15,7 @@ int check_desc(const fipa_desc *d, bool backward)
         d->r <= 0)
         return FIPA_ERR_INVALID_ARG;
     if (d->dtype != FIPA_DTYPE_F32 && d->dtype != FIPA_DTYPE_BF16) return FIPA_ERR_INVALID_ARG;
-    if ((d->flags & ~(uint32_t)(FIPA_FLAG_WAVE_SPECIALISED | FIPA_FLAG_PACKED_PER_CHAIN)) != 0) return FIPA_ERR_INVALID_ARG;
+    if ((d->flags & ~(uint32_t)(FIPA_FLAG_WAVE_SPECIALISED | FIPA_FLAG_PACKED_PER_CHAIN | FIPA_FLAG_KEEP_FORWARD)) != 0) return FIPA_ERR_INVALID_ARG;
     if (!(d->w_L == d->w_L) || !(d->w_C == d->w_C) || !(d->qk_scale == d->qk_scale))
         return FIPA_ERR_INVALID_ARG;
     const long long DZ = (long long)d->r * d->cz;
@@ -98,6 +98,15 @@ int fipa_forward(const fipa_desc *desc, const void *q, const void *k, const void
     if (!workspace) return FIPA_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return FIPA_ERR_ALIGNMENT;
     size_t need = 0;
+    if (desc->flags & FIPA_FLAG_KEEP_FORWARD) {
+        // the forward part of the backward, which leaves the lifted operands, O^ and the
+        // log-sum-exp in a workspace of the backward's size, gives the same outputs
+        if (check_desc(desc, true) != FIPA_OK || desc->dtype != FIPA_DTYPE_BF16) return FIPA_ERR_UNSUPPORTED;
+        fipa_workspace_bytes(desc, nullptr, &need);
+        if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
+        return bf16_backward_begin(*desc, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? FIPA_OK
+                                                                                                           : FIPA_ERR_LAUNCH;
+    }
     fipa_workspace_bytes(desc, &need, nullptr);
     if (workspace_bytes < need) return FIPA_ERR_WORKSPACE;
     return enqueue_forward(*desc, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? FIPA_OK
@@ -122,7 +131,8 @@ int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const voi
         if (!ptr) return FIPA_ERR_INVALID_ARG;
         if (!aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
     }
-    // (the saved forward results are not read: everything is recomputed from the inputs)
+    // (the saved forward results are not read: what the gradient needs is recomputed from the
+    // inputs, or kept in the workspace by the forward call)
     const void *saved[] = {o, o_pts, o_pair, lse};
     for (const void *ptr : saved)
         if (ptr && !aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
@@ -140,7 +150,10 @@ int fipa_backward(const fipa_desc *desc, const void *q, const void *k, const voi
     a.d_q = d_q; a.d_k = d_k; a.d_v = d_v; a.d_q_pts = d_q_pts; a.d_k_pts = d_k_pts;
     a.d_v_pts = d_v_pts; a.d_z1 = d_z1; a.d_z2 = d_z2; a.d_gamma = d_gamma; a.d_w_b = d_w_b;
     a.d_rot = d_rot; a.d_trans = d_trans;
-    const hipError_t e = bf16_backward(*desc, a, workspace, static_cast<hipStream_t>(hip_stream));
+    // (with FIPA_FLAG_KEEP_FORWARD the workspace still holds what the forward call left there)
+    const hipError_t e = (desc->flags & FIPA_FLAG_KEEP_FORWARD)
+                             ? bf16_backward_finish(*desc, a, workspace, static_cast<hipStream_t>(hip_stream))
+                             : bf16_backward(*desc, a, workspace, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
 }
 

@@ -136,8 +136,14 @@ int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens, const 
                         float *lse, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     PackedPlan pl;
-    const int rc = packed_plan(desc, cu_seqlens, false, pl);
+    const bool keep = desc && (desc->flags & FIPA_FLAG_KEEP_FORWARD);
+    const int rc = packed_plan(desc, cu_seqlens, keep, pl);
     if (rc != FIPA_OK) return rc;
+    if (keep) {  // one workspace for the whole batch, of the backward's size and layout
+        if (!pl.one_launch && pl.total > 0) return FIPA_ERR_UNSUPPORTED;
+        pl.fwd_bytes = pl.bwd_bytes;
+        pl.cu_fwd = pl.cu_bwd;
+    }
     const void *req[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, o, o_pts, o_pair, workspace};
     for (const void *ptr : req)
         if (!ptr) return FIPA_ERR_INVALID_ARG;
@@ -154,7 +160,8 @@ int fipa_forward_packed(const fipa_desc *desc, const int32_t *cu_seqlens, const 
         FwdArgs a{q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask, o, o_pts, o_pair, lse};
         a.cu = cu_dev;
         a.total_rows = pl.total;
-        return bf16_forward(pl.d, a, workspace, stream) == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
+        const hipError_t e = keep ? bf16_backward_begin(pl.d, a, workspace, stream) : bf16_forward(pl.d, a, workspace, stream);
+        return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
     }
 
     // chain by chain: bytes per residue of each tensor
@@ -187,6 +194,8 @@ int fipa_backward_packed(const fipa_desc *desc, const int32_t *cu_seqlens, const
     PackedPlan pl;
     const int rc = packed_plan(desc, cu_seqlens, true, pl);
     if (rc != FIPA_OK) return rc;
+    const bool keep = (desc->flags & FIPA_FLAG_KEEP_FORWARD) != 0;
+    if (keep && !pl.one_launch && pl.total > 0) return FIPA_ERR_UNSUPPORTED;
     const void *req[] = {q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma,
                          d_o, d_o_pts, d_o_pair, d_q, d_k, d_v, d_q_pts, d_k_pts, d_v_pts, d_z1, d_z2,
                          d_gamma, workspace};
@@ -213,7 +222,8 @@ int fipa_backward_packed(const fipa_desc *desc, const int32_t *cu_seqlens, const
         if (upload_ints(cu_seqlens, desc->B + 1, cu_dev, stream) != hipSuccess) return FIPA_ERR_LAUNCH;
         a.f.cu = cu_dev;
         a.f.total_rows = pl.total;
-        return bf16_backward(pl.d, a, workspace, stream) == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
+        const hipError_t e = keep ? bf16_backward_finish(pl.d, a, workspace, stream) : bf16_backward(pl.d, a, workspace, stream);
+        return e == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
     }
 
     // chain by chain; gamma and w_b are shared by the chains, so each chain leaves its own sums in

@@ -53,6 +53,7 @@ extern "C" int fipa_forward_static(const fipa_desc *desc, const void *q, const v
     const fipa::FwdArgs a{q, k, v, q_pts, k_pts, v_pts, rot, trans, z1, z2, w_b, gamma, mask, o, o_pts, o_pair, lse};
     const int rc = fipa::check_forward_args(desc, a);
     if (rc != FIPA_OK) return rc;
+    if (desc->flags & FIPA_FLAG_KEEP_FORWARD) return FIPA_ERR_UNSUPPORTED;  // (nothing is kept in the shared scratch)
     size_t need = 0;
     fipa_workspace_bytes(desc, &need, nullptr);
     if (need > (size_t)FIPA_STATIC_SCRATCH_BYTES) return FIPA_ERR_WORKSPACE;  // problem too large for the static scratch
