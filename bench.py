@@ -180,6 +180,27 @@ def module_leg(workload, d_s=256, steps=300, warmup=100):
         binding.module_backward(desc, d_s, dev, up, grads)
     torch.cuda.synchronize()
     out["backward_ms_per_call"] = (time.perf_counter() - t0) / bsteps * 1e3
+
+    # a training step = forward call + backward call, as two independent calls and with
+    # FIPA_FLAG_KEEP_FORWARD (the forward runs in the backward's workspace and leaves its results there)
+    def step_ms(flags, ws):
+        desc.flags = flags
+        fwd_ws, dev["workspace"] = dev["workspace"], ws
+        for _ in range(3):
+            binding.module_forward(desc, d_s, dev)
+            binding.module_backward(desc, d_s, dev, up, grads)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(bsteps):
+            binding.module_forward(desc, d_s, dev)
+            binding.module_backward(desc, d_s, dev, up, grads)
+        torch.cuda.synchronize()
+        dev["workspace"] = fwd_ws
+        desc.flags = 0
+        return (time.perf_counter() - t0) / bsteps * 1e3
+
+    out["training_step_ms"] = {"forward_then_backward": step_ms(0, dev["workspace"]),
+                               "with_keep_forward_flag": step_ms(binding.FIPA_FLAG_KEEP_FORWARD, grads["workspace"])}
     return out
 
 

@@ -83,8 +83,10 @@ typedef struct fipa_desc {
  * between the two calls; a backward call with the flag on a workspace that the matching forward call
  * did not fill returns gradients of garbage without an error.  Not for fipa_forward_static
  * (FIPA_ERR_UNSUPPORTED); packed batches only where they run as one launch (FIPA_ERR_UNSUPPORTED
- * with FIPA_FLAG_PACKED_PER_CHAIN or when the plan falls back to chain-by-chain); the fipa_module_*
- * calls ignore it.
+ * with FIPA_FLAG_PACKED_PER_CHAIN or when the plan falls back to chain-by-chain).
+ * fipa_module_forward / fipa_module_backward take it the same way: the forward call needs
+ * fipa_module_backward_workspace_bytes and also leaves the projected inputs (Eq. 1) and the core's
+ * outputs; the backward call then starts at Eq. 5's gradient.
  */
 #define FIPA_FLAG_KEEP_FORWARD 4u
 

@@ -173,7 +173,8 @@ int fipa_module_forward(const fipa_desc *desc, int32_t d_s, const void *s, const
                         float *s_out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     size_t need = 0;
-    const int rc = fipa_module_workspace_bytes(desc, d_s, &need);
+    const bool keep = desc && (desc->flags & FIPA_FLAG_KEEP_FORWARD);  // runs in the backward's workspace
+    const int rc = keep ? fipa_module_backward_workspace_bytes(desc, d_s, &need) : fipa_module_workspace_bytes(desc, d_s, &need);
     if (rc != FIPA_OK) return rc;
     const void *req[] = {s, w_in, rot, trans, z1, z2, w_b, gamma, w_out, s_out, workspace};
     for (const void *ptr : req) {

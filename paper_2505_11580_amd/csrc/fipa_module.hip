@@ -482,6 +482,9 @@ ModuleBwdLayout module_bwd_layout(const fipa_desc &d, int d_s)
     w.f.o = take(M * d.H * d.c * 4);
     w.f.o_pts = take(M * d.H * d.Pv * 3 * 4);
     w.f.o_pair = take(M * d.H * d.cz * 4);
+    // (for a forward call that runs in this layout, FIPA_FLAG_KEEP_FORWARD: its partial products)
+    const OutSplit os = out_projection_split((int)M, d_s, (int)n_cat);
+    w.f.part = os.nsplit > 1 ? take((size_t)os.nsplit * M * d_s * 4) : 0;
     w.f.total = 0;
     w.g16 = take(M * d_s * 2);
     w.gT = take(Mp * d_s * 2);
@@ -527,7 +530,11 @@ size_t module_forward_workspace(const fipa_desc &d, int d_s) { return module_lay
 
 hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void *ws, hipStream_t stream)
 {
-    const ModuleLayout w = module_layout(d, d_s);
+    // With FIPA_FLAG_KEEP_FORWARD the call runs in the backward's layout and leaves there what the
+    // backward call would otherwise compute again: the projected inputs, the core's outputs, and
+    // inside the core's slot the lifted operands, O^ and the log-sum-exp.
+    const bool keep = (d.flags & FIPA_FLAG_KEEP_FORWARD) != 0;
+    const ModuleLayout w = keep ? module_bwd_layout(d, d_s).f : module_layout(d, d_s);
     char *base = static_cast<char *>(ws);
     const int M = d.B * d.L;
 
@@ -550,7 +557,7 @@ hipError_t module_forward(const fipa_desc &d, int d_s, const ModuleArgs &a, void
     FwdArgs f{base + w.q, base + w.k, base + w.v, base + w.q_pts, base + w.k_pts, base + w.v_pts,
               a.rot, a.trans, a.z1, a.z2, a.w_b, a.gamma, a.mask,
               (float *)(base + w.o), (float *)(base + w.o_pts), (float *)(base + w.o_pair), nullptr};
-    e = bf16_forward(d, f, base + w.core, stream);
+    e = keep ? bf16_backward_begin(d, f, base + w.core, stream) : bf16_forward(d, f, base + w.core, stream);
     if (e != hipSuccess) return e;
 
     // ---- Eq. 5: s_out = concat(o_pair, o, o_pts, |o_pts|) W_out^T + b_out --------------------------
@@ -604,13 +611,14 @@ hipError_t module_backward(const fipa_desc &d, int d_s, const ModuleArgs &a, con
     }
     g1.N = g1.seg_start[6];
     const int n_in = g1.N;
-    FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, true>(g1, stream)));
+    const bool kept = (d.flags & FIPA_FLAG_KEEP_FORWARD) != 0;  // the forward call left all of this in the workspace
+    if (!kept) FIPA_TRY((launch_gemm<GemmTile<2, 2, 1, 1>, false, true>(g1, stream)));
     FwdArgs f{base + w.f.q, base + w.f.k, base + w.f.v, base + w.f.q_pts, base + w.f.k_pts, base + w.f.v_pts,
               a.rot, a.trans, a.z1, a.z2, a.w_b, a.gamma, a.mask,
               (float *)(base + w.f.o), (float *)(base + w.f.o_pts), (float *)(base + w.f.o_pair), nullptr};
     // (the forward part of the core's backward, which leaves O^ and the log-sum-exp for the gradient
     // kernels, also gives the core's outputs: no separate forward call)
-    FIPA_TRY(bf16_backward_begin(d, f, base + w.f.core, stream));
+    if (!kept) FIPA_TRY(bf16_backward_begin(d, f, base + w.f.core, stream));
 
     // ---- through Eq. 5: d cat = d s_out W_out; d W_out = d s_out^T cat; d b_out = column sums ----------
     bf16_t *g16 = (bf16_t *)(base + w.g16), *gT = (bf16_t *)(base + w.gT);

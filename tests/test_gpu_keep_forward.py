@@ -117,3 +117,39 @@ def test_keep_forward_refusals():
     with pytest.raises(binding.FipaError) as e:
         binding.forward(desc32, dev32, out32)
     assert e.value.code == binding.FIPA_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("kw", [dict(d_s=48, B=1, L=130, H=4, trans_scale=0.3),
+                                dict(d_s=64, B=2, L=160, H=4, varlen=True, min_len=30, trans_scale=0.5),
+                                dict(d_s=256, B=1, L=512, H=4, trans_scale=0.5)])
+def test_keep_forward_module(kw):
+    # the whole module: forward with the flag in the backward's workspace (d_s = 256 at 512 rows
+    # splits the output projection, so its partial products live there too), then backward with it
+    import torch
+    from oracle import module_ref
+    from tests.test_gpu_module import MODULE_GRADS
+    m = wl.make_module_inputs(4, **kw)
+    d = m["dims"]
+    up = torch.from_numpy(np.random.default_rng(5).standard_normal((d["B"], d["L"], m["d_s"])).astype(np.float32)).to("cuda:0")
+    desc, dev = binding.upload_module(m)
+    plain = binding.alloc_module_grads(desc, m["d_s"])
+    binding.module_backward(desc, m["d_s"], dev, up, plain)
+    desc.flags = binding.FIPA_FLAG_KEEP_FORWARD
+    kept = binding.alloc_module_grads(desc, m["d_s"])
+    for n, _ in MODULE_GRADS:
+        kept[n].fill_(float("nan"))
+    small = dev["workspace"]
+    with pytest.raises(binding.FipaError) as e:  # the forward's own workspace is too small for this
+        binding.module_forward(desc, m["d_s"], dev)
+    assert e.value.code == binding.FIPA_ERR_WORKSPACE and small.numel() < kept["workspace"].numel()
+    dev["workspace"] = kept["workspace"]
+    dev["workspace"].fill_(0xFF)
+    dev["s_out"].fill_(float("nan"))
+    binding.module_forward(desc, m["d_s"], dev)
+    binding.module_backward(desc, m["d_s"], dev, up, kept)
+    torch.cuda.synchronize()
+    got = dev["s_out"].cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert gu.rel_err(got, module_ref.module_forward(m)) <= 2e-2
+    for n, _ in MODULE_GRADS:
+        assert torch.equal(kept[n], plain[n]), (kw, n, float((kept[n].float() - plain[n].float()).abs().max()))
