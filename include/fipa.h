@@ -220,14 +220,40 @@ int fipa_backward_packed(const fipa_desc *desc, const int32_t *cu_seqlens,
  *     edges, one rounding per operation.
  * Outputs (device, 4-byte aligned, fully overwritten): nbr_idx [B, L, k] int32, nbr_d2 [B, L, k]
  * float32 (squared distances), nbr_bin [B, L, k] int32.  A one-hot distogram is
- * feat[b, i, s, nbr_bin[b, i, s]] = 1; the factors z1, z2 are linear projections of such features,
- * i.e. table look-ups that belong to the model around this library.
+ * feat[b, i, s, nbr_bin[b, i, s]] = 1; the factors z1, z2 are linear projections of such features
+ * (fipa_factor_project below).
  * 1 <= k <= 64, 2 <= n_bins <= 4096, 0 <= d_min < d_max; otherwise FIPA_ERR_INVALID_ARG /
  * FIPA_ERR_UNSUPPORTED.  No workspace; enqueued on hip_stream.
  */
 int fipa_knn_distogram(int32_t B, int32_t L, int32_t k, int32_t n_bins, float d_min, float d_max,
                        const float *trans, const uint8_t *mask,
                        int32_t *nbr_idx, float *nbr_d2, int32_t *nbr_bin, void *hip_stream);
+
+/*
+ * Pair pseudo-factors from those features (Section 2.4: every pair feature is represented by two
+ * [L, r, c_z] tensors obtained via linear projections; Section 2.5: the neighbours' identities
+ * enter through a positional encoding of their indices).  The paper gives no formula; this call
+ * fixes: the feature vector of residue i is the concatenation over its k neighbour slots s of
+ * [one-hot(nbr_bin[b,i,s]) | one-hot(code(b,i,s))] with an empty slot (index < 0) all zero, and a
+ * factor is one linear projection of it plus a bias.  A projection of one-hot vectors is a sum of
+ * table rows, so the weights are passed as tables and nothing is multiplied:
+ *   z[b, i, :] = bias + sum_s ( e_bin[s, nbr_bin[b,i,s], :] + e_pos[s, code(b,i,s), :] )
+ *   pos_mode 0: code = min(j, n_pos - 1) with j = nbr_idx[b,i,s] (the neighbour's own index);
+ *   pos_mode 1: code = clip(j - i, -(n_pos-1)/2, +(n_pos-1)/2) + (n_pos-1)/2 (its offset; n_pos odd).
+ * A fixed encoding (sines and cosines of the code, say) followed by a linear map is the table
+ * e_pos[s, code, :] = W_s enc(code) that the caller tabulates once.
+ * nbr_idx, nbr_bin [B, L, k] int32 as fipa_knn_distogram writes them (device, 4-byte aligned; a bin
+ * outside 0 .. n_bins - 1 in a filled slot is clamped into the table); e_bin [k, n_bins, n_out] and
+ * e_pos [k, n_pos, n_out] bf16 (e_pos NULL exactly when n_pos = 0), bias [n_out] float32 or NULL,
+ * z [B, L, n_out] bf16 fully overwritten (a residue without neighbours gets the bias) -- all device,
+ * 16-byte aligned.  n_out = r c_z, so z is a z1 or z2 argument of fipa_forward as it stands; call
+ * twice, with the two sets of tables.  Sums in float32, slot by slot, one rounding to bf16 at the end.
+ * n_out a multiple of 8, 1 <= k <= 64; otherwise FIPA_ERR_INVALID_ARG / FIPA_ERR_UNSUPPORTED.
+ * No workspace; enqueued on hip_stream.
+ */
+int fipa_factor_project(int32_t B, int32_t L, int32_t k, int32_t n_bins, int32_t n_pos, int32_t pos_mode,
+                        int32_t n_out, const int32_t *nbr_idx, const int32_t *nbr_bin, const void *e_bin,
+                        const void *e_pos, const float *bias, void *z, void *hip_stream);
 
 /*
  * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three

@@ -136,6 +136,26 @@ def test_knn_distogram_argument_checks_need_no_device():
     assert call(idx=ctypes.c_void_p(0x1002)) == binding.FIPA_ERR_ALIGNMENT
 
 
+def test_factor_project_argument_checks_need_no_device():
+    lib = binding.lib()
+    p = ctypes.c_void_p(0x1000)
+
+    def call(B=2, L=50, k=20, n_bins=16, n_pos=65, pos_mode=1, n_out=256, idx=p, e_pos=p, z=p):
+        return lib.fipa_factor_project(B, L, k, n_bins, n_pos, pos_mode, n_out, idx, p, p, e_pos, None, z, None)
+
+    assert call(L=0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(n_bins=0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(pos_mode=2) == binding.FIPA_ERR_INVALID_ARG
+    assert call(n_pos=64) == binding.FIPA_ERR_INVALID_ARG          # offsets need an odd number of rows
+    assert call(n_pos=0) == binding.FIPA_ERR_INVALID_ARG           # a table without rows
+    assert call(e_pos=None) == binding.FIPA_ERR_INVALID_ARG        # rows without a table
+    assert call(z=None) == binding.FIPA_ERR_INVALID_ARG
+    assert call(n_out=100) == binding.FIPA_ERR_UNSUPPORTED
+    assert call(k=65) == binding.FIPA_ERR_UNSUPPORTED
+    assert call(z=ctypes.c_void_p(0x1008)) == binding.FIPA_ERR_ALIGNMENT
+    assert call(idx=ctypes.c_void_p(0x1002)) == binding.FIPA_ERR_ALIGNMENT
+
+
 def test_stage_timer_argument_checks_need_no_device():
     lib = binding.lib()
     assert lib.fipa_profile_begin_every(10, 0) == binding.FIPA_ERR_INVALID_ARG
