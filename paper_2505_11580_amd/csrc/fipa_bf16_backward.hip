@@ -83,16 +83,30 @@ __global__ __launch_bounds__(256) void fipa_bwd_pack_bf16_kernel(BwdPackParams p
     }
 }
 
-// One workgroup per (batch, residue): chain rule from dQ^, dK^, dV^ back to the inputs.
+// One wave per (batch, residue), four residues per workgroup: chain rule from dQ^, dK^, dV^ back to
+// the inputs.  Nothing is exchanged between the waves, so there is no workgroup barrier: sums over
+// the lanes of a wave go through shuffles in a fixed order.
+//   first the per-head tasks -- 2 Pq + Pv point gradients and the three scalar rows of each head --
+//   dealt to the lanes kind by kind (few bytes, many small scattered accesses);
+//   then the pair factors (the bulk of the bytes): a lane owns four neighbouring lifted columns and
+//   adds up the heads one after the other (16-byte loads of the four big arrays, all independent);
+//   where the lifted width is below 256 the lanes form 64 / (DZ / 4) groups that take every
+//   group-th head and are added at the end, above it a lane takes DZ / 256 sets of columns.
+// Measured at B = 2, L = 4096, H = 12, r c_z = 256 (about 520 MB moved): 0.139 ms; the pair-factor part
+// alone 0.099 ms (5.1 TB/s); the earlier form, one workgroup per residue with the sums of its threads
+// meeting in LDS behind workgroup barriers, 0.191 ms.
 __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackParams p)
 {
-    __shared__ float gsm[256];
-    const int b = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const long long rr = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // (b, i); uniform over the wave
+    if (rr >= (long long)p.B * p.L) return;
+    const int b = (int)(rr / p.L), i = (int)(rr - (long long)b * p.L);
     const int c = p.c, Pq = p.Pq, Pv = p.Pv, nq = 3 * Pq, D = kDH + p.DZ;
-    const int NTASK = 2 * Pq + Pv + 3;
     if (i >= user_len(p, b)) return;  // (packed batch: the grid covers the longest chain)
     const size_t urow = user_row(p, b, i);
     const bool valid = p.mask ? p.mask[urow] != 0 : true;
+
+    // ---- per-head tasks ----------------------------------------------------------------------------
     const float *R = p.rot + urow * 9;
     const float *t = p.trans + urow * 3;
     float Rm[9], tc[3];
@@ -103,156 +117,182 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
     // contributes g to d t_i and g x^T to d R_i (G = R_i x + t_i); the output points
     // o_pts = R_i^T (G - t_i) contribute -R_i d_o_pts and (G - t_i) d_o_pts^T
     float ft[3] = {0.f, 0.f, 0.f}, fr[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const int HP = 256 / NTASK;  // heads per pass: the tasks of one head stay inside one pass
-    for (int h0 = 0; h0 < p.H; h0 += HP) {
-        float gpartial = 0.f;
-        const int hl = tid / NTASK;
-        const bool active = hl < HP && h0 + hl < p.H;
-        const int h = active ? h0 + hl : 0, tk = active ? tid - hl * NTASK : 0;
-        if (active) {
+    // Three kinds of task, each dealt to the lanes in passes of its own so that a pass runs one
+    // piece of code: the 2 Pq query and key points of a head (whole heads per pass: their
+    // contributions to d gamma are added across the head's lanes), the Pv value points, and the
+    // scalar rows d_q, d_k, d_v in pieces of eight channels.
+    {
+        const int per = 2 * Pq, HP = 64 / per;
+        for (int h0 = 0; h0 < p.H; h0 += HP) {
+            float gpartial = 0.f;
+            const int hl = lane / per;
+            const bool active = hl < HP && h0 + hl < p.H;
+            const int h = active ? h0 + hl : 0, tk = active ? lane - hl * per : 0;
             const size_t bh = (size_t)b * p.H + h;
-            const size_t rec = urow * p.H + h;
-            const float *dQ = p.dQhat + (bh * p.Lp + i) * D;
-            const float *dK = p.dKhat + (bh * p.Lp + i) * D;
-            const float *dV = p.dVhat + (bh * p.Lp + i) * D;
-            const float pscale = p.gamma[h] * p.w_L * p.w_C;
-            const float kscale = kLog2e * pscale;
-            if (tk < 2 * Pq) {
+            if (active) {
+                const size_t rec = urow * p.H + h;
+                const float pscale = p.gamma[h] * p.w_L * p.w_C;
                 const bool isq = tk < Pq;
+                const float sc = isq ? 1.f : kLog2e * pscale, inv_sc = sc != 0.f ? 1.f / sc : 0.f;
                 const int pt = isq ? tk : tk - Pq;
+                const float *dX = (isq ? p.dQhat : p.dKhat) + (bh * p.Lp + i) * D + c + 3 * pt;  // hi columns of this point
+                const int lo_off = isq ? nq : 2 * nq;                                             // to its lo columns
+                const float ws = (isq ? p.rowsum : p.colsum)[bh * p.Lp + i];
                 const bf16_t *src = (isq ? p.q_pts : p.k_pts) + (rec * Pq + pt) * 3;
-                const float lx = bf2f(src[0]), ly = bf2f(src[1]), lz = bf2f(src[2]);
-                float grad[3], eff[3];
+                const float lc[3] = {bf2f(src[0]), bf2f(src[1]), bf2f(src[2])};
+                float grad[3];
                 float gacc = 0.f;
+#pragma unroll
                 for (int a = 0; a < 3; ++a) {
-                    const float G0 = Rm[3 * a] * lx + Rm[3 * a + 1] * ly + Rm[3 * a + 2] * lz + tc[a];
-                    const int cc = 3 * pt + a;
-                    if (isq) {
-                        // the effective (hi + lo) global query coordinate the kernels used
-                        const bf16_t hi = f2bf(G0), lo = f2bf(G0 - bf2f(hi));
-                        eff[a] = bf2f(hi) + bf2f(lo);
-                        const float rs = p.rowsum[bh * p.Lp + i];
-                        // d s / dQ = gamma w_L w_C (K - Q) summed with dS; sum_j dS K^ sits in the Khi and Klo columns
-                        grad[a] = kLn2 * (dQ[c + cc] + dQ[c + nq + cc]) - pscale * rs * eff[a];
-                        gacc += rs * eff[a] * eff[a];
-                    } else {
-                        const float Gs = kscale * G0;
-                        const bf16_t hi = f2bf(Gs), lo = f2bf(Gs - bf2f(hi));
-                        eff[a] = kscale != 0.f ? (bf2f(hi) + bf2f(lo)) / kscale : G0;
-                        const float cs = p.colsum[bh * p.Lp + i];
-                        const float X = dK[c + cc] + dK[c + 2 * nq + cc];  // sum_i dS Q (Qhi and Qlo columns)
-                        grad[a] = pscale * (X - cs * eff[a]);
-                        gacc += cs * eff[a] * eff[a] - 2.f * eff[a] * X;
-                    }
+                    const float G0 = Rm[3 * a] * lc[0] + Rm[3 * a + 1] * lc[1] + Rm[3 * a + 2] * lc[2] + tc[a];
+                    const float X = dX[a] + dX[lo_off + a];  // sum over the other side of dS times its hi and lo coordinates
+                    // the effective (hi + lo) global coordinate the kernels used: the query's as it is, the
+                    // key's scaled by log2e gamma w_L w_C before the split
+                    const float Gs = sc * G0;
+                    const bf16_t hi = f2bf(Gs), lo = f2bf(Gs - bf2f(hi));
+                    const float eff = sc != 0.f ? (bf2f(hi) + bf2f(lo)) * inv_sc : G0;
+                    // query: d s / dQ = gamma w_L w_C (K - Q) summed with dS, and sum_j dS K^ sits in the Khi and
+                    // Klo columns (in log2 units); key: the same with the sides exchanged
+                    grad[a] = isq ? kLn2 * X - pscale * ws * eff : pscale * (X - ws * eff);
+                    gacc += isq ? ws * eff * eff : ws * eff * eff - 2.f * eff * X;
                 }
                 gpartial = gacc;
-                const float lc[3] = {lx, ly, lz};
+#pragma unroll
                 for (int x = 0; x < 3; ++x) {
                     ft[x] += grad[x];
+#pragma unroll
                     for (int y = 0; y < 3; ++y) fr[3 * x + y] += grad[x] * lc[y];
                 }
                 bf16_t *dst = (isq ? p.d_q_pts : p.d_k_pts) + (rec * Pq + pt) * 3;
+#pragma unroll
                 for (int x = 0; x < 3; ++x) {
                     const float val = Rm[x] * grad[0] + Rm[3 + x] * grad[1] + Rm[6 + x] * grad[2];  // R^T
                     dst[x] = f2bf(valid ? val : 0.f);
                 }
-            } else if (tk < 2 * Pq + Pv) {
-                const int pt = tk - 2 * Pq;
-                float grad[3];
-                for (int a = 0; a < 3; ++a) grad[a] = dV[v_pt_col(c, Pv, pt, a, 0)];
-                if (p.d_rot) {
-                    const bf16_t *vl = p.v_pts + (rec * Pv + pt) * 3;
-                    const float *gp = p.d_o_pts + (rec * Pv + pt) * 3;
-                    const float *oh = p.Ohat + (bh * p.Lp + i) * D;
-                    const bf16_t *dgh = p.dOhat + (bh * p.Lp + i) * D;
-                    for (int x = 0; x < 3; ++x) {
-                        // R_i d_o_pts, in the rounded form that the gradient kernels used: it then cancels
-                        // against the value-point term exactly where the mathematics says so (shift invariance)
-                        const float dGx = bf2f(dgh[v_pt_col(c, Pv, pt, x, 0)]);
-                        const float Gm = oh[v_pt_col(c, Pv, pt, x, 0)] + oh[v_pt_col(c, Pv, pt, x, 1)] - tc[x];
-                        ft[x] += grad[x] - dGx;
-                        for (int y = 0; y < 3; ++y) fr[3 * x + y] += grad[x] * bf2f(vl[y]) + Gm * gp[y];
-                    }
-                }
-                bf16_t *dst = p.d_v_pts + (rec * Pv + pt) * 3;
-                for (int x = 0; x < 3; ++x) {
-                    const float val = Rm[x] * grad[0] + Rm[3 + x] * grad[1] + Rm[6 + x] * grad[2];
-                    dst[x] = f2bf(valid ? val : 0.f);
-                }
-            } else {
-                const int which = tk - 2 * Pq - Pv;  // 0: d_q, 1: d_k, 2: d_v
-                const float *src = which == 0 ? dQ : (which == 1 ? dK : dV);
-                const float scale = which == 0 ? kLn2 : (which == 1 ? p.w_L * p.qk_scale : 1.f);
-                bf16_t *dst = (which == 0 ? p.d_q : (which == 1 ? p.d_k : p.d_v)) + rec * c;
-                for (int x = 0; x < c; ++x) dst[x] = f2bf(valid ? scale * src[x] : 0.f);
             }
-        }
-        // d gamma: this residue's contribution, summed over its query and key points in a fixed order
-        __syncthreads();
-        gsm[tid] = gpartial;
-        __syncthreads();
-        if (active && tk == 0) {
-            float s = 0.f;
-            for (int x = 0; x < 2 * Pq; ++x) s += gsm[tid + x];
-            p.gpart[((size_t)b * p.H + h) * p.Lp + i] = valid ? s : 0.f;
+            // d gamma: this residue's contribution, summed over the query and key points of a head in
+            // a fixed order (they sit in the 2 Pq lanes from the head's first on)
+            float gsum = 0.f;
+            for (int x = 0; x < per; ++x) gsum += __shfl(gpartial, (lane + x) & 63);
+            if (active && tk == 0) p.gpart[bh * p.Lp + i] = valid ? gsum : 0.f;
         }
     }
-
-    // frame gradients of this residue: sum over the threads in a fixed order
-    if (p.d_rot) {
-        __shared__ float fsm[12][256];
-        for (int x = 0; x < 3; ++x) fsm[x][tid] = ft[x];
-        for (int x = 0; x < 9; ++x) fsm[3 + x][tid] = fr[x];
-        __syncthreads();
-        for (int st = 128; st > 0; st >>= 1) {
-            if (tid < st)
-                for (int x = 0; x < 12; ++x) fsm[x][tid] += fsm[x][tid + st];
-            __syncthreads();
-        }
-        if (tid < 3) p.d_trans[urow * 3 + tid] = valid ? fsm[tid][0] : 0.f;
-        if (tid < 9) p.d_rot[urow * 9 + tid] = valid ? fsm[3 + tid][0] : 0.f;
-    }
-
-    // pair factors: sums over heads.  A thread takes four neighbouring lifted columns (16-byte loads
-    // of the four big arrays) and every kHG-th head; the partial sums of the kHG head groups meet in
-    // LDS and are added in a fixed order.
-    {
-        __shared__ float zsm[2][1024];  // [z1 | z2][head group][DZ], (256 / (DZ / 4)) * DZ = 1024 entries
-        const int NG = p.DZ / 4, HG = 256 / NG;  // DZ is 32, 64, 128 or 256
-        const int grp = tid % NG, hg = tid / NG, x0 = 4 * grp;
-        f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
-        for (int h = hg; h < p.H; h += HG) {
+    for (int t0 = 0; t0 < p.H * Pv; t0 += 64) {
+        const int tsk = t0 + lane;
+        if (tsk < p.H * Pv) {
+            const int h = tsk / Pv, pt = tsk - h * Pv;
             const size_t bh = (size_t)b * p.H + h;
-            const size_t row = (bh * p.Lp + i) * D + kDH + x0;
             const size_t rec = urow * p.H + h;
-            const f32x4 dq = *reinterpret_cast<const f32x4 *>(p.dQhat + row);
-            const f32x4 dk = *reinterpret_cast<const f32x4 *>(p.dKhat + row);
-            const f32x4 dv = *reinterpret_cast<const f32x4 *>(p.dVhat + row);
-            const f32x4 oh = *reinterpret_cast<const f32x4 *>(p.Ohat + row);
+            const float *dV = p.dVhat + (bh * p.Lp + i) * D;
+            float grad[3];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int d = (x0 + e) % p.cz;
-                // z1: through the bias vector b^{h1} = w_L w_b z1, and through o~ = z1^T U
-                s1[e] += p.w_L * p.w_b[(size_t)h * p.cz + d] * dq[e] + p.d_o_pair[rec * p.cz + d] * oh[e];
-                // z2: as key feature (the log2e sits on the query side) and as value feature
-                s2[e] += kLn2 * dk[e] + dv[e];
+            for (int a = 0; a < 3; ++a) grad[a] = dV[v_pt_col(c, Pv, pt, a, 0)];
+            if (p.d_rot) {
+                const bf16_t *vl = p.v_pts + (rec * Pv + pt) * 3;
+                const float *gp = p.d_o_pts + (rec * Pv + pt) * 3;
+                const float *oh = p.Ohat + (bh * p.Lp + i) * D;
+                const bf16_t *dgh = p.dOhat + (bh * p.Lp + i) * D;
+#pragma unroll
+                for (int x = 0; x < 3; ++x) {
+                    // R_i d_o_pts, in the rounded form that the gradient kernels used: it then cancels
+                    // against the value-point term exactly where the mathematics says so (shift invariance)
+                    const float dGx = bf2f(dgh[v_pt_col(c, Pv, pt, x, 0)]);
+                    const float Gm = oh[v_pt_col(c, Pv, pt, x, 0)] + oh[v_pt_col(c, Pv, pt, x, 1)] - tc[x];
+                    ft[x] += grad[x] - dGx;
+#pragma unroll
+                    for (int y = 0; y < 3; ++y) fr[3 * x + y] += grad[x] * bf2f(vl[y]) + Gm * gp[y];
+                }
+            }
+            bf16_t *dst = p.d_v_pts + (rec * Pv + pt) * 3;
+#pragma unroll
+            for (int x = 0; x < 3; ++x) {
+                const float val = Rm[x] * grad[0] + Rm[3 + x] * grad[1] + Rm[6 + x] * grad[2];
+                dst[x] = f2bf(valid ? val : 0.f);
             }
         }
-        __syncthreads();  // (zsm is free: nothing above uses it)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            zsm[0][hg * p.DZ + x0 + e] = s1[e];
-            zsm[1][hg * p.DZ + x0 + e] = s2[e];
-        }
-        __syncthreads();
-        for (int x = tid; x < p.DZ; x += 256) {
-            float t1 = 0.f, t2 = 0.f;
-            for (int g = 0; g < HG; ++g) {
-                t1 += zsm[0][g * p.DZ + x];
-                t2 += zsm[1][g * p.DZ + x];
+    }
+    {
+        const int nchunk = c / 8, per = 3 * nchunk;  // (c is a multiple of 8; every piece is 16-byte aligned on both sides)
+        for (int t0 = 0; t0 < p.H * per; t0 += 64) {
+            const int tsk = t0 + lane;
+            if (tsk < p.H * per) {
+                const int h = tsk / per, rem = tsk - h * per;
+                const int which = rem / nchunk, x = 8 * (rem - which * nchunk);  // 0: d_q, 1: d_k, 2: d_v
+                const size_t row = (((size_t)b * p.H + h) * p.Lp + i) * D + x;
+                const float *src = (which == 0 ? p.dQhat : (which == 1 ? p.dKhat : p.dVhat)) + row;
+                const float scale = which == 0 ? kLn2 : (which == 1 ? p.w_L * p.qk_scale : 1.f);
+                bf16_t *dst = (which == 0 ? p.d_q : (which == 1 ? p.d_k : p.d_v)) + (urow * p.H + h) * c + x;
+                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(src);
+                const f32x4 v1 = *reinterpret_cast<const f32x4 *>(src + 4);
+                uint4 o;
+                o.x = (unsigned)f2bf(valid ? scale * v0[0] : 0.f) | ((unsigned)f2bf(valid ? scale * v0[1] : 0.f) << 16);
+                o.y = (unsigned)f2bf(valid ? scale * v0[2] : 0.f) | ((unsigned)f2bf(valid ? scale * v0[3] : 0.f) << 16);
+                o.z = (unsigned)f2bf(valid ? scale * v1[0] : 0.f) | ((unsigned)f2bf(valid ? scale * v1[1] : 0.f) << 16);
+                o.w = (unsigned)f2bf(valid ? scale * v1[2] : 0.f) | ((unsigned)f2bf(valid ? scale * v1[3] : 0.f) << 16);
+                *reinterpret_cast<uint4 *>(dst) = o;
             }
-            p.d_z1[urow * p.DZ + x] = f2bf(valid ? t1 : 0.f);
-            p.d_z2[urow * p.DZ + x] = f2bf(valid ? t2 : 0.f);
+        }
+    }
+
+    // ---- pair factors: sums over heads -------------------------------------------------------------
+    {
+        const int NG = p.DZ >= 256 ? 64 : p.DZ / 4, HG = 64 / NG;  // lanes per set of columns, head groups
+        const int grp = lane % NG, hg = lane / NG;
+        for (int x0 = 4 * grp; x0 < p.DZ; x0 += 256) {
+            const int d0 = x0 % p.cz;
+            f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+            for (int h = hg; h < p.H; h += HG) {
+                const size_t bh = (size_t)b * p.H + h;
+                const size_t row = (bh * p.Lp + i) * D + kDH + x0;
+                const size_t rec = urow * p.H + h;
+                const f32x4 dq = *reinterpret_cast<const f32x4 *>(p.dQhat + row);
+                const f32x4 dk = *reinterpret_cast<const f32x4 *>(p.dKhat + row);
+                const f32x4 dv = *reinterpret_cast<const f32x4 *>(p.dVhat + row);
+                const f32x4 oh = *reinterpret_cast<const f32x4 *>(p.Ohat + row);
+                const f32x4 wb = *reinterpret_cast<const f32x4 *>(p.w_b + (size_t)h * p.cz + d0);
+                const f32x4 dop = *reinterpret_cast<const f32x4 *>(p.d_o_pair + rec * p.cz + d0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // z1: through the bias vector b^{h1} = w_L w_b z1, and through o~ = z1^T U
+                    s1[e] += p.w_L * wb[e] * dq[e] + dop[e] * oh[e];
+                    // z2: as key feature (the log2e sits on the query side) and as value feature
+                    s2[e] += kLn2 * dk[e] + dv[e];
+                }
+            }
+            for (int o = NG; o < 64; o <<= 1)  // (HG > 1: the head groups, added pairwise in a fixed order)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    s1[e] += __shfl_xor(s1[e], o);
+                    s2[e] += __shfl_xor(s2[e], o);
+                }
+            if (hg == 0) {
+                uint2 o1, o2;
+                o1.x = (unsigned)f2bf(valid ? s1[0] : 0.f) | ((unsigned)f2bf(valid ? s1[1] : 0.f) << 16);
+                o1.y = (unsigned)f2bf(valid ? s1[2] : 0.f) | ((unsigned)f2bf(valid ? s1[3] : 0.f) << 16);
+                o2.x = (unsigned)f2bf(valid ? s2[0] : 0.f) | ((unsigned)f2bf(valid ? s2[1] : 0.f) << 16);
+                o2.y = (unsigned)f2bf(valid ? s2[2] : 0.f) | ((unsigned)f2bf(valid ? s2[3] : 0.f) << 16);
+                *reinterpret_cast<uint2 *>(p.d_z1 + urow * p.DZ + x0) = o1;
+                *reinterpret_cast<uint2 *>(p.d_z2 + urow * p.DZ + x0) = o2;
+            }
+        }
+    }
+
+    // frame gradients of this residue: sum over the lanes in a fixed order
+    if (p.d_rot) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+#pragma unroll
+            for (int x = 0; x < 3; ++x) ft[x] += __shfl_xor(ft[x], o);
+#pragma unroll
+            for (int x = 0; x < 9; ++x) fr[x] += __shfl_xor(fr[x], o);
+        }
+        if (lane < 3) p.d_trans[urow * 3 + lane] = valid ? (lane == 0 ? ft[0] : (lane == 1 ? ft[1] : ft[2])) : 0.f;
+        if (lane < 9) {
+            float v = fr[0];
+#pragma unroll
+            for (int x = 1; x < 9; ++x) v = lane == x ? fr[x] : v;
+            p.d_rot[urow * 9 + lane] = valid ? v : 0.f;
         }
     }
 }
@@ -383,7 +423,7 @@ hipError_t launch_bwd_pack_bf16(const BwdPackParams &p, hipStream_t stream)
 
 hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(fipa_bwd_unpack_bf16_kernel, dim3(p.L, p.B), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(fipa_bwd_unpack_bf16_kernel, dim3((unsigned)(((long long)p.B * p.L + 3) / 4)), dim3(256), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fipa_bwd_gamma_kernel, dim3(p.H), dim3(256), 0, stream, p.gpart, p.d_gamma, p.B, p.H, p.L,
