@@ -70,3 +70,42 @@ def test_packed_forward_replays_from_a_graph():
                                     out["o"], out["o_pts"], out["o_pair"], out["lse"], ws)
 
     _replay_and_compare(enqueue, out, "packed")
+
+
+def test_training_step_replays_from_a_graph():
+    # forward (keeping its lifted state in the backward's workspace) and backward captured as one graph:
+    # every replay must give the eager step's outputs and gradients, with the workspace scribbled over
+    # between the replays (nothing in it may be expected to survive from one step to the next)
+    import torch
+    from tests.test_gpu_backward import GRADS
+    inp = wl.make_inputs(4, B=2, L=300, H=3, varlen=True, min_len=80, trans_scale=0.5)
+    desc, dev = binding.upload(inp)
+    desc.flags = binding.FIPA_FLAG_KEEP_FORWARD
+    out = binding.alloc_outputs(desc)
+    grads = binding.alloc_grads(desc)
+    out["workspace"] = grads["workspace"]
+    names = [(out, n) for n in NAMES] + [(grads, n) for n, _ in GRADS]
+
+    def enqueue():
+        binding.forward(desc, dev, out)
+        binding.backward(desc, dev, out, grads)
+
+    enqueue()
+    torch.cuda.synchronize()
+    want = [d[n].clone() for d, n in names]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        enqueue()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    for rep in range(3):
+        for d, n in names:
+            d[n].fill_(float("nan"))
+        grads["workspace"].fill_(0xFF)  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (d, n), w in zip(names, want):
+            assert torch.equal(d[n], w), (rep, n)
