@@ -297,21 +297,28 @@ __global__ __launch_bounds__(256) void fipa_bwd_unpack_bf16_kernel(BwdUnpackPara
     }
 }
 
-// d gamma^h = -(w_L w_C / 2) * sum over (batch, residue) of the partial sums, in a fixed order.
+// d gamma^h = -(w_L w_C / 2) * sum over (batch, residue) of the partial sums, in a fixed order:
+// one workgroup of 1024 threads per head, four independent chains of loads per thread.
 // (cu: row offsets of a packed batch, whose chain b has cu[b+1] - cu[b] residues, or null.)
-__global__ __launch_bounds__(256) void fipa_bwd_gamma_kernel(const float *gpart, float *d_gamma, int B, int H,
-                                                             int L, int Lp, const int *cu, float coef)
+__global__ __launch_bounds__(1024) void fipa_bwd_gamma_kernel(const float *gpart, float *d_gamma, int B, int H,
+                                                              int L, int Lp, const int *cu, float coef)
 {
-    __shared__ float red[256];
+    __shared__ float red[1024];
     const int h = blockIdx.x, tid = threadIdx.x;
-    float s = 0.f;
+    float s4[4] = {0.f, 0.f, 0.f, 0.f};
     for (int b = 0; b < B; ++b) {
         const int len = cu ? cu[b + 1] - cu[b] : L;
-        for (int i = tid; i < len; i += 256) s += gpart[((size_t)b * H + h) * Lp + i];
+        const float *g = gpart + ((size_t)b * H + h) * Lp;
+        for (int i0 = tid; i0 < len; i0 += 4096)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + 1024 * u;
+                s4[u] += i < len ? g[i] : 0.f;
+            }
     }
-    red[tid] = s;
+    red[tid] = (s4[0] + s4[1]) + (s4[2] + s4[3]);
     __syncthreads();
-    for (int st = 128; st > 0; st >>= 1) {
+    for (int st = 512; st > 0; st >>= 1) {
         if (tid < st) red[tid] += red[tid + st];
         __syncthreads();
     }
@@ -324,60 +331,81 @@ __global__ __launch_bounds__(256) void fipa_bwd_gamma_kernel(const float *gpart,
 // sum over chunks and rho.
 constexpr int kWbChunk = 32;
 
+// One workgroup per (chunk, head): a thread takes four neighbouring lifted columns (16 bytes of
+// dQ^, 8 of z1) of every NRG-th residue of the chunk, all loads independent; the NRG partial sums
+// per column meet in LDS and are added in a fixed order.  r c_z <= 512 here, so NRG >= 2.
 __global__ __launch_bounds__(256) void fipa_bwd_wb_partial_kernel(BwdUnpackParams p)
 {
+    __shared__ float red[256 * 4];  // [residue group][DZ], NRG * DZ = 1024 entries
     const int h = blockIdx.y, chunk = blockIdx.x, D = kDH + p.DZ;
     const int nres = p.total_rows;  // rows of the caller's tensors: B L, or the packed batch's total
-    for (int x = threadIdx.x; x < p.DZ; x += 256) {
-        float s4[4] = {0.f, 0.f, 0.f, 0.f};  // four independent chains of loads; summed in a fixed order
-        for (int t0 = 0; t0 < kWbChunk; t0 += 4) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int bi = min(chunk * kWbChunk + t0 + u, nres - 1);
-                int b, i;
-                if (p.cu) {  // the chain that holds row bi: last b with cu[b] <= bi
-                    int lo = 0, hi = p.B - 1;
-                    while (lo < hi) {
-                        const int mid = (lo + hi + 1) >> 1;
-                        if (p.cu[mid] <= bi) lo = mid; else hi = mid - 1;
-                    }
-                    b = lo;
-                    i = bi - p.cu[b];
-                } else {
-                    b = bi / p.L;
-                    i = bi - b * p.L;
-                }
-                const bool valid = chunk * kWbChunk + t0 + u < nres && (p.mask ? p.mask[bi] != 0 : true);
-                const float prod = bf2f(p.z1[(size_t)bi * p.DZ + x]) * p.dQhat[(((size_t)b * p.H + h) * p.Lp + i) * D + kDH + x];
-                s4[u] += valid ? prod : 0.f;
+    const int NG = p.DZ / 4, NRG = 256 / NG;
+    const int cg = threadIdx.x % NG, rg = threadIdx.x / NG, x0 = 4 * cg;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int t = rg; t < kWbChunk; t += NRG) {
+        const int bi = min(chunk * kWbChunk + t, nres - 1);
+        int b, i;
+        if (p.cu) {  // the chain that holds row bi: last b with cu[b] <= bi
+            int lo = 0, hi = p.B - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (p.cu[mid] <= bi) lo = mid; else hi = mid - 1;
             }
+            b = lo;
+            i = bi - p.cu[b];
+        } else {
+            b = bi / p.L;
+            i = bi - b * p.L;
         }
-        p.wpart[((size_t)h * gridDim.x + chunk) * p.DZ + x] = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+        const bool valid = chunk * kWbChunk + t < nres && (p.mask ? p.mask[bi] != 0 : true);
+        const uint2 zr = *reinterpret_cast<const uint2 *>(p.z1 + (size_t)bi * p.DZ + x0);
+        const f32x4 dq = *reinterpret_cast<const f32x4 *>(p.dQhat + (((size_t)b * p.H + h) * p.Lp + i) * D + kDH + x0);
+        if (valid) {
+            s[0] += __uint_as_float(zr.x << 16) * dq[0];
+            s[1] += __uint_as_float(zr.x & 0xFFFF0000u) * dq[1];
+            s[2] += __uint_as_float(zr.y << 16) * dq[2];
+            s[3] += __uint_as_float(zr.y & 0xFFFF0000u) * dq[3];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[rg * p.DZ + x0 + e] = s[e];
+    __syncthreads();
+    for (int x = threadIdx.x; x < p.DZ; x += 256) {
+        float t = 0.f;
+        for (int g = 0; g < NRG; ++g) t += red[g * p.DZ + x];
+        p.wpart[((size_t)h * gridDim.x + chunk) * p.DZ + x] = t;
     }
 }
 
-__global__ __launch_bounds__(256) void fipa_bwd_wb_reduce_kernel(BwdUnpackParams p, int nchunk)
+// One workgroup of 1024 threads per head: the chunks are dealt to 1024 / DZ groups of threads
+// (four independent chains of loads each); groups, then rho, are added in a fixed order.
+__global__ __launch_bounds__(1024) void fipa_bwd_wb_reduce_kernel(BwdUnpackParams p, int nchunk)
 {
-    __shared__ float col[512];  // per lifted pair column: sum over the chunks
+    __shared__ float part[1024];  // [chunk group][DZ]
+    __shared__ float col[512];    // per lifted pair column: sum over the chunks
     const int h = blockIdx.x;
-    for (int x = threadIdx.x; x < p.DZ; x += 256) {
-        // eight independent chains of loads (one chain would pay the load latency nchunk times);
-        // summed in a fixed order
-        float s8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int ch0 = 0; ch0 < nchunk; ch0 += 8) {
+    const int NCG = 1024 / p.DZ, x = threadIdx.x % p.DZ, cgp = threadIdx.x / p.DZ;
+    float s4[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int ch0 = cgp; ch0 < nchunk; ch0 += 4 * NCG)
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float v = p.wpart[((size_t)h * nchunk + min(ch0 + u, nchunk - 1)) * p.DZ + x];
-                s8[u] += ch0 + u < nchunk ? v : 0.f;
-            }
+        for (int u = 0; u < 4; ++u) {
+            const int ch = ch0 + u * NCG;
+            const float v = p.wpart[((size_t)h * nchunk + min(ch, nchunk - 1)) * p.DZ + x];
+            s4[u] += ch < nchunk ? v : 0.f;
         }
-        col[x] = ((s8[0] + s8[1]) + (s8[2] + s8[3])) + ((s8[4] + s8[5]) + (s8[6] + s8[7]));
+    part[cgp * p.DZ + x] = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+    __syncthreads();
+    if (threadIdx.x < p.DZ) {
+        float t = 0.f;
+        for (int g = 0; g < NCG; ++g) t += part[g * p.DZ + threadIdx.x];
+        col[threadIdx.x] = t;
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < p.cz; d += 256) {
-        float s = 0.f;
-        for (int rho = 0; rho < p.r; ++rho) s += col[rho * p.cz + d];
-        p.d_w_b[(size_t)h * p.cz + d] = p.w_L * s;
+    for (int d = threadIdx.x; d < p.cz; d += 1024) {
+        float t = 0.f;
+        for (int rho = 0; rho < p.r; ++rho) t += col[rho * p.cz + d];
+        p.d_w_b[(size_t)h * p.cz + d] = p.w_L * t;
     }
 }
 
@@ -426,12 +454,12 @@ hipError_t launch_bwd_unpack_bf16(const BwdUnpackParams &p, hipStream_t stream)
     hipLaunchKernelGGL(fipa_bwd_unpack_bf16_kernel, dim3((unsigned)(((long long)p.B * p.L + 3) / 4)), dim3(256), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fipa_bwd_gamma_kernel, dim3(p.H), dim3(256), 0, stream, p.gpart, p.d_gamma, p.B, p.H, p.L,
+    hipLaunchKernelGGL(fipa_bwd_gamma_kernel, dim3(p.H), dim3(1024), 0, stream, p.gpart, p.d_gamma, p.B, p.H, p.L,
                        p.Lp, p.cu, -0.5f * p.w_L * p.w_C);
     if (p.d_w_b) {
         const int nchunk = (p.total_rows + kWbChunk - 1) / kWbChunk;
         hipLaunchKernelGGL(fipa_bwd_wb_partial_kernel, dim3(nchunk, p.H), dim3(256), 0, stream, p);
-        hipLaunchKernelGGL(fipa_bwd_wb_reduce_kernel, dim3(p.H), dim3(256), 0, stream, p, nchunk);
+        hipLaunchKernelGGL(fipa_bwd_wb_reduce_kernel, dim3(p.H), dim3(1024), 0, stream, p, nchunk);
     }
     return hipGetLastError();
 }
