@@ -60,3 +60,19 @@ def factor_project(idx, bins, e_bin, e_pos, bias, pos_mode=1):
     B, L = x.shape[:2]
     z = x.reshape(B, L, k * (n_bins + n_pos)) @ w.reshape(k * (n_bins + n_pos), n_out)
     return z if bias is None else z + np.asarray(bias, dtype=np.float64)
+
+
+def factor_project_backward(idx, bins, d_z, n_bins, n_pos, pos_mode=1, mask=None):
+    """Gradient of a loss through factor_project with respect to its tables and bias, given d_z
+    [B, L, n_out] = d loss / d z: the projection is linear, z = x W + b, so d W = x^T d_z and
+    d b = sum of d_z over the residues (residues with mask 0 contribute nothing).
+    Returns d_e_bin [k, n_bins, n_out], d_e_pos [k, n_pos, n_out] (None when n_pos = 0), d_bias [n_out]."""
+    d_z = np.asarray(d_z, dtype=np.float64)
+    B, L, n_out = d_z.shape
+    k = np.asarray(idx).shape[2]
+    if mask is not None:
+        d_z = d_z * (np.asarray(mask) != 0)[:, :, None]
+    x = features(idx, bins, n_bins, n_pos, pos_mode)
+    dw = x.reshape(B * L, k * (n_bins + n_pos)).T @ d_z.reshape(B * L, n_out)
+    dw = dw.reshape(k, n_bins + n_pos, n_out)
+    return dw[:, :n_bins], (dw[:, n_bins:] if n_pos > 0 else None), d_z.reshape(B * L, n_out).sum(axis=0)

@@ -88,3 +88,39 @@ def test_relative_codes_do_not_see_a_shift_of_the_chain():
     assert np.allclose(zs[0, 5:], z[0], atol=1e-12)
     assert not np.allclose(fr.factor_project(big_idx, big_bins, e_bin, e_pos, bias, pos_mode=0)[0, 5:],
                            fr.factor_project(idx, bins, e_bin, e_pos, bias, pos_mode=0)[0])
+
+
+def test_backward_is_the_adjoint_of_the_projection_and_a_direct_scatter():
+    rng = np.random.default_rng(14)
+    for pos_mode in (0, 1):
+        idx, bins, e_bin, e_pos, bias = _random_case(rng)
+        B, L, k = idx.shape
+        d_z = rng.standard_normal((B, L, e_bin.shape[2]))
+        mask = (rng.random((B, L)) > 0.25).astype(np.uint8)
+        g_bin, g_pos, g_bias = fr.factor_project_backward(idx, bins, d_z, e_bin.shape[1], e_pos.shape[1], pos_mode, mask)
+        # adjoint identity of a linear map: <d_z, z(E, b)> = <dE, E> + <db, b> (masked residues left out of the loss)
+        z = fr.factor_project(idx, bins, e_bin, e_pos, bias, pos_mode)
+        lhs = float((z * d_z * mask[:, :, None]).sum())
+        rhs = float((g_bin * e_bin).sum() + (g_pos * e_pos).sum() + (g_bias * bias).sum())
+        assert abs(lhs - rhs) <= 1e-9 * max(1.0, abs(lhs))
+        # direct scatter with loops
+        want_bin, want_pos = np.zeros_like(e_bin), np.zeros_like(e_pos)
+        n_pos = e_pos.shape[1]
+        for b in range(B):
+            for i in range(L):
+                if not mask[b, i]:
+                    continue
+                for s in range(k):
+                    j = idx[b, i, s]
+                    if j < 0:
+                        continue
+                    code = min(j, n_pos - 1) if pos_mode == 0 else min(max(j - i, -(n_pos // 2)), n_pos // 2) + n_pos // 2
+                    want_bin[s, bins[b, i, s]] += d_z[b, i]
+                    want_pos[s, code] += d_z[b, i]
+        assert np.allclose(g_bin, want_bin, atol=1e-12) and np.allclose(g_pos, want_pos, atol=1e-12)
+        assert np.allclose(g_bias, (d_z * mask[:, :, None]).sum(axis=(0, 1)), atol=1e-12)
+    # a table row that no residue selects gets no gradient
+    idx1 = np.array([[[1], [0]]])
+    bins1 = np.array([[[2], [2]]])
+    g_bin, g_pos, _ = fr.factor_project_backward(idx1, bins1, np.ones((1, 2, 3)), 4, 0)
+    assert g_pos is None and np.array_equal(g_bin[0, 2], [2.0, 2.0, 2.0]) and not g_bin[0, [0, 1, 3]].any()
