@@ -256,6 +256,24 @@ int fipa_factor_project(int32_t B, int32_t L, int32_t k, int32_t n_bins, int32_t
                         const void *e_pos, const float *bias, void *z, void *hip_stream);
 
 /*
+ * Gradient of fipa_factor_project with respect to its tables and bias, for training the producer of
+ * the factors (d_z is fipa_backward's d_z1 or d_z2): the projection is linear, so
+ *   d_e_bin[s, m, :] = sum of d_z[b, i, :] over the residues whose slot s is filled and holds bin m,
+ *   d_e_pos[s, c, :] = the same by position code, d_bias = sum of d_z over all residues;
+ * residues with mask[b, i] = 0 (mask [B, L] bytes or NULL) add nothing.  Same index arguments and
+ * codes as the forward call; d_z [B, L, n_out] bf16; d_e_bin [k, n_bins, n_out], d_e_pos
+ * [k, n_pos, n_out] (NULL exactly when n_pos = 0) and d_bias [n_out] (or NULL) float32, fully
+ * overwritten (rows that nothing selects get 0) -- device, 16-byte aligned.  Sums are float32 in the
+ * order of the residues (every fourth residue into one of four sums, which are then added in order): the same bits on every
+ * run.  (n_bins + n_pos + 1) * 256 bytes must fit 120 KB (FIPA_ERR_UNSUPPORTED otherwise); the other
+ * limits as in the forward call.  No workspace; enqueued on hip_stream.
+ */
+int fipa_factor_project_backward(int32_t B, int32_t L, int32_t k, int32_t n_bins, int32_t n_pos, int32_t pos_mode,
+                                 int32_t n_out, const int32_t *nbr_idx, const int32_t *nbr_bin, const void *d_z,
+                                 const uint8_t *mask, float *d_e_bin, float *d_e_pos, float *d_bias,
+                                 void *hip_stream);
+
+/*
  * Backward of fipa_forward: gradients of a scalar loss with respect to q, k, v, the three
  * point sets, z1, z2 (same shapes and dtype as the inputs), gamma ([H], float32) and, when the
  * pointers are not NULL, the pair-bias weights w_b (d_w_b [H, cz], float32) and the frames

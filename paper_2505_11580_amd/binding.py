@@ -29,7 +29,7 @@ FIPA_FLAG_KEEP_FORWARD = 4  # desc.flags bit: forward fills a backward-sized wor
 EXPORTS = ("fipa_version", "fipa_status_string", "fipa_workspace_bytes", "fipa_forward",
            "fipa_packed_workspace_bytes", "fipa_forward_packed", "fipa_backward_packed", "fipa_forward_static", "fipa_backward", "fipa_module_workspace_bytes", "fipa_module_forward",
            "fipa_module_backward_workspace_bytes", "fipa_module_backward",
-           "fipa_knn_distogram", "fipa_factor_project",
+           "fipa_knn_distogram", "fipa_factor_project", "fipa_factor_project_backward",
            "fipa_profile_begin", "fipa_profile_begin_every", "fipa_profile_end", "fipa_probe_mfma")
 PROFILE_STAGES = 3
 
@@ -88,6 +88,8 @@ def lib():
         L.fipa_knn_distogram.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_float] * 2 + [vp] * 5 + [vp]
         L.fipa_factor_project.restype = ctypes.c_int
         L.fipa_factor_project.argtypes = [ctypes.c_int32] * 7 + [vp] * 6 + [vp]
+        L.fipa_factor_project_backward.restype = ctypes.c_int
+        L.fipa_factor_project_backward.argtypes = [ctypes.c_int32] * 7 + [vp] * 7 + [vp]
         L.fipa_profile_begin.restype = ctypes.c_int
         L.fipa_profile_begin.argtypes = [ctypes.c_int]
         L.fipa_profile_begin_every.restype = ctypes.c_int
@@ -242,6 +244,18 @@ def fipa_factor_project(pos_mode, nbr_idx, nbr_bin, e_bin, e_pos, bias, z):
                                    _ptr(e_bin), _ptr(e_pos), _ptr(bias), _ptr(z), _stream())
     if rc != FIPA_OK:
         raise FipaError(rc, "fipa_factor_project")
+
+
+def fipa_factor_project_backward(pos_mode, nbr_idx, nbr_bin, d_z, mask, d_e_bin, d_e_pos, d_bias):
+    """Enqueue fipa_factor_project_backward on torch's current stream; d_z [B, L, n_out] bf16, d_e_bin
+    [k, n_bins, n_out], d_e_pos [k, n_pos, n_out] (or None) and d_bias [n_out] (or None) float32."""
+    B, L, k = (int(x) for x in nbr_idx.shape)
+    n_bins, n_out = int(d_e_bin.shape[1]), int(d_e_bin.shape[2])
+    n_pos = 0 if d_e_pos is None else int(d_e_pos.shape[1])
+    rc = lib().fipa_factor_project_backward(B, L, k, n_bins, n_pos, int(pos_mode), n_out, _ptr(nbr_idx), _ptr(nbr_bin),
+                                            _ptr(d_z), _ptr(mask), _ptr(d_e_bin), _ptr(d_e_pos), _ptr(d_bias), _stream())
+    if rc != FIPA_OK:
+        raise FipaError(rc, "fipa_factor_project_backward")
 
 
 def fipa_profile_begin(capacity):

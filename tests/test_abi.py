@@ -156,6 +156,24 @@ def test_factor_project_argument_checks_need_no_device():
     assert call(idx=ctypes.c_void_p(0x1002)) == binding.FIPA_ERR_ALIGNMENT
 
 
+def test_factor_project_backward_argument_checks_need_no_device():
+    lib = binding.lib()
+    p = ctypes.c_void_p(0x1000)
+
+    def call(B=2, L=50, k=20, n_bins=16, n_pos=65, pos_mode=1, n_out=256, d_z=p, d_e_pos=p, d_e_bin=p):
+        return lib.fipa_factor_project_backward(B, L, k, n_bins, n_pos, pos_mode, n_out, p, p, d_z, None, d_e_bin, d_e_pos,
+                                                None, None)
+
+    assert call(B=0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(d_z=None) == binding.FIPA_ERR_INVALID_ARG
+    assert call(d_e_pos=None) == binding.FIPA_ERR_INVALID_ARG
+    assert call(n_pos=0) == binding.FIPA_ERR_INVALID_ARG
+    assert call(n_pos=64) == binding.FIPA_ERR_INVALID_ARG
+    assert call(n_out=100) == binding.FIPA_ERR_UNSUPPORTED
+    assert call(n_bins=4096) == binding.FIPA_ERR_UNSUPPORTED      # the table slice does not fit LDS
+    assert call(d_e_bin=ctypes.c_void_p(0x1004)) == binding.FIPA_ERR_ALIGNMENT
+
+
 def test_stage_timer_argument_checks_need_no_device():
     lib = binding.lib()
     assert lib.fipa_profile_begin_every(10, 0) == binding.FIPA_ERR_INVALID_ARG

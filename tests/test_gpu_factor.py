@@ -132,3 +132,74 @@ def test_workload3_size_timed():
     want = factor_ref.factor_project(idx.cpu().numpy(), bins.cpu().numpy(), e_bin.float().numpy(), e_pos.float().numpy(), bias, 1)
     dd = np.abs(z.float().cpu().numpy().astype(np.float64) - want)
     assert np.all(dd <= 2.0 ** -8 * np.abs(want) + 1e-5 * np.abs(want).max()), float(dd.max())
+
+
+@pytest.mark.parametrize("kw", [dict(B=2, L=77, k=20, n_bins=16, n_pos=65, n_out=256, pos_mode=1),
+                                dict(B=1, L=300, k=20, n_bins=16, n_pos=33, n_out=512, pos_mode=0),
+                                dict(B=3, L=50, k=7, n_bins=5, n_pos=0, n_out=8, pos_mode=1),
+                                dict(B=1, L=130, k=64, n_bins=64, n_pos=129, n_out=136, pos_mode=1),
+                                dict(B=2, L=40, k=1, n_bins=1, n_pos=1, n_out=32, pos_mode=1),
+                                dict(B=1, L=90, k=3, n_bins=220, n_pos=255, n_out=64, pos_mode=1)])
+def test_table_gradients(kw):
+    # (the last two shapes: a single table row that every residue hits; tables so tall that only one
+    # wave's copy fits LDS)
+    import torch
+    rng = np.random.default_rng(200 + kw["L"])
+    B, L, k, n_bins, n_pos, n_out = kw["B"], kw["L"], kw["k"], kw["n_bins"], kw["n_pos"], kw["n_out"]
+    idx = rng.integers(0, L, size=(B, L, k))
+    idx[rng.random((B, L, k)) < 0.15] = -1
+    bins = rng.integers(0, n_bins, size=(B, L, k))
+    bins[idx < 0] = -1
+    mask = (rng.random((B, L)) > 0.2).astype(np.uint8)
+    d_z = _bf16(rng.standard_normal((B, L, n_out)))
+    f = dict(dtype=torch.float32, device="cuda:0")
+    g_bin = torch.full((k, n_bins, n_out), float("nan"), **f)
+    g_pos = None if n_pos == 0 else torch.full((k, n_pos, n_out), float("nan"), **f)
+    g_bias = torch.full((n_out,), float("nan"), **f)
+    args = (kw["pos_mode"], torch.from_numpy(idx.astype(np.int32)).cuda(), torch.from_numpy(bins.astype(np.int32)).cuda(),
+            d_z.cuda(), torch.from_numpy(mask).cuda())
+    binding.fipa_factor_project_backward(*args, g_bin, g_pos, g_bias)
+    torch.cuda.synchronize()
+    first = [t.clone() for t in (g_bin, g_pos, g_bias) if t is not None]
+    w_bin, w_pos, w_bias = factor_ref.factor_project_backward(idx, bins, d_z.float().numpy(), n_bins, n_pos, kw["pos_mode"], mask)
+    # float32 sums of up to B L bf16 values against float64 sums: a few 1e-7 of the sum of magnitudes
+    scale = float(np.abs(d_z.float().numpy()).sum(axis=(0, 1)).max())
+    for got, want, name in ((g_bin, w_bin, "d_e_bin"), (g_pos, w_pos, "d_e_pos"), (g_bias, w_bias, "d_bias")):
+        if got is None:
+            continue
+        g = got.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(g)), (kw, name)
+        assert np.abs(g - want).max() <= 2e-6 * scale, (kw, name, float(np.abs(g - want).max()), scale)
+    # the same bits on a second run
+    for t in (g_bin, g_pos, g_bias):
+        if t is not None:
+            t.fill_(float("nan"))
+    binding.fipa_factor_project_backward(*args, g_bin, g_pos, g_bias)
+    torch.cuda.synchronize()
+    for a, b in zip(first, [t for t in (g_bin, g_pos, g_bias) if t is not None]):
+        assert torch.equal(a, b), kw
+
+
+def test_table_gradients_workload3_size_timed():
+    import torch
+    B, L, k, n_bins, n_pos, n_out = 4, 8192, 20, 16, 65, 512
+    rng = np.random.default_rng(300)
+    idx = np.clip(np.arange(L)[None, :, None] + rng.integers(-40, 41, size=(B, L, k)), 0, L - 1)  # near neighbours along the chain
+    bins = np.minimum(rng.geometric(0.25, size=(B, L, k)) - 1, n_bins - 1)                        # low bins much more often
+    d_z = _bf16(rng.standard_normal((B, L, n_out)))
+    f = dict(dtype=torch.float32, device="cuda:0")
+    g_bin, g_pos, g_bias = torch.empty(k, n_bins, n_out, **f), torch.empty(k, n_pos, n_out, **f), torch.empty(n_out, **f)
+    args = (1, torch.from_numpy(idx.astype(np.int32)).cuda(), torch.from_numpy(bins.astype(np.int32)).cuda(), d_z.cuda(), None)
+    binding.fipa_factor_project_backward(*args, g_bin, g_pos, g_bias)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        binding.fipa_factor_project_backward(*args, g_bin, g_pos, g_bias)
+    e1.record()
+    torch.cuda.synchronize()
+    print("factor projection backward B=%d L=%d n_out=%d: %.3f ms per call" % (B, L, n_out, e0.elapsed_time(e1) / 10), flush=True)
+    w_bin, w_pos, w_bias = factor_ref.factor_project_backward(idx, bins, d_z.float().numpy(), n_bins, n_pos, 1)
+    scale = float(np.abs(d_z.float().numpy()).sum(axis=(0, 1)).max())
+    for got, want in ((g_bin, w_bin), (g_pos, w_pos), (g_bias, w_bias)):
+        assert np.abs(got.cpu().numpy().astype(np.float64) - want).max() <= 2e-6 * scale
