@@ -263,9 +263,9 @@ int fipa_factor_project(int32_t B, int32_t L, int32_t k, int32_t n_bins, int32_t
  * residues with mask[b, i] = 0 (mask [B, L] bytes or NULL) add nothing.  Same index arguments and
  * codes as the forward call; d_z [B, L, n_out] bf16; d_e_bin [k, n_bins, n_out], d_e_pos
  * [k, n_pos, n_out] (NULL exactly when n_pos = 0) and d_bias [n_out] (or NULL) float32, fully
- * overwritten (rows that nothing selects get 0) -- device, 16-byte aligned.  Sums are float32 in the
- * order of the residues (every fourth residue into one of four sums, which are then added in order): the same bits on every
- * run.  (n_bins + n_pos + 1) * 256 bytes must fit 120 KB (FIPA_ERR_UNSUPPORTED otherwise); the other
+ * overwritten (rows that nothing selects get 0) -- device, 16-byte aligned.  Sums are float32 in a
+ * fixed order (a contraction over the residues on the matrix pipe; the one-hot operand is exact in
+ * bf16): the same bits on every run.  n_bins + n_pos <= 159 (FIPA_ERR_UNSUPPORTED otherwise); the other
  * limits as in the forward call.  No workspace; enqueued on hip_stream.
  */
 int fipa_factor_project_backward(int32_t B, int32_t L, int32_t k, int32_t n_bins, int32_t n_pos, int32_t pos_mode,

@@ -11,7 +11,7 @@
 // not by HBM (the algorithmic HBM traffic is the n_out bf16 written and 8 k index bytes read).
 // Sums are float32 in slot order (bias, then per slot the bin row, then the position row), rounded
 // to bf16 once at the end.
-#include "fipa_bf16_common.h"
+#include "fipa_gfx950.h"
 #include "fipa_internal.h"
 
 #include <algorithm>
@@ -75,103 +75,132 @@ __global__ __launch_bounds__(256) void fipa_factor_project_kernel(const int *__r
 
 // Gradient with respect to the tables: d e_bin[s, m, :] is the sum of d_z[b, i, :] over the residues
 // whose slot s is filled and holds bin m, likewise d e_pos by position code, d bias the sum over
-// all residues -- a scatter of rows.  One workgroup per (slot, 64 output columns); each of its W
-// working waves owns a private copy of the slot's table slice in LDS ([rows][64 columns], lane =
-// column) and takes every W-th residue, adding the residue's 64 values into the rows its slot selects
-// by plain LDS reads and writes: a wave's LDS instructions execute in the order issued and no other
-// wave touches its copy, so every entry is summed in residue order and the result is the same on
-// every run.  (LDS float atomics, which need no read, were three times slower: 8.6 against 2.6 ms at
-// 32768 residues, 512 columns.)  At the end the copies are added in wave order.  A residue with mask 0
-// adds nothing.  The residues arrive in tiles of 128 (their slot-s index and bin, mask, and 128 bytes
-// of d_z each) that all 256 threads fetch with 16-byte loads into registers while the previous tile
-// is being worked on, and hand over through LDS; one barrier per tile.
+// all residues.  A scatter of rows -- but a scatter into shared sums either serialises on LDS
+// round trips (per-wave table copies updated row by row: 2.1 ms at 32768 residues, 512 columns; with
+// LDS float atomics 8.6 ms) or loses the fixed summation order.  Here it is the contraction it
+// also is, over the residue axis: dE_s [rows, 64 columns] = X_s^T [rows, residues] . dZ [residues, 64],
+// with X_s the one-hot features of slot s -- exact in bf16 -- on the matrix pipe with float32
+// accumulation in a fixed order (the same bits on every run).  One workgroup per (slot, 64 output
+// columns) walks the residues in tiles of 128: every thread fetches 64 bytes of d_z (16-byte loads, in
+// flight while the previous tile is multiplied) and stores them transposed ([column][residue]); one
+// thread per residue marks that residue's (up to three) rows in the one-hot tile ([row][residue]) and
+// takes back the marks it made two tiles earlier, so the tile never needs clearing as a whole; one
+// barrier per tile; the 2 x ceil(rows / 32) output tiles are dealt to the four waves.
+// rows = n_bins + n_pos + 1 (the last one collects the bias gradient, in slot 0's workgroups).
 constexpr int kFbTile = 128;
-constexpr int kFbStageBytes = kFbTile * 128 + 3 * kFbTile * 4;  // d_z rows, then index, bin, mask flag
+constexpr int kFbStride = kFbTile * 2 + 16;  // bytes per row of either tile
+constexpr int kFbMaxRowBlocks = 5, kFbMaxOwn = (2 * kFbMaxRowBlocks + 3) / 4;
 
 template <bool HAS_POS>
 __global__ __launch_bounds__(256) void fipa_factor_backward_kernel(const int *__restrict__ nbr_idx, const int *__restrict__ nbr_bin,
                                                                    const bf16_t *__restrict__ d_z, const uint8_t *__restrict__ mask,
                                                                    float *__restrict__ d_e_bin, float *__restrict__ d_e_pos,
                                                                    float *__restrict__ d_bias, int rows, int L, int k, int n_bins,
-                                                                   int n_pos, int pos_mode, int n_out, int W)
+                                                                   int n_pos, int pos_mode, int n_out, int RB)
 {
-    extern __shared__ __attribute__((aligned(16))) char fb_smem[];  // two stages, then tab[W][R][64]
+    extern __shared__ __attribute__((aligned(16))) char fb_smem[];  // dZ^T tiles [2][64][stride], one-hot tiles [2][32 RB][stride]
     const int s = blockIdx.x, col0 = blockIdx.y * 64, tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int R = n_bins + n_pos + 1;  // bin rows, position rows, one row for the bias (used by slot 0)
-    float *tab = reinterpret_cast<float *>(fb_smem + 2 * kFbStageBytes);
-    for (int x = tid; x < W * R * 64; x += 256) tab[x] = 0.f;
-    float *t = tab + (size_t)wave * R * 64 + lane;
+    const int lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
+    const int R = n_bins + n_pos + 1, Rpad = 32 * RB;
+    char *const zt = fb_smem, *const xt = fb_smem + 2 * 64 * kFbStride;
+    for (int x = tid * 16; x < 2 * Rpad * kFbStride; x += 256 * 16) *reinterpret_cast<uint4 *>(xt + x) = (uint4){0u, 0u, 0u, 0u};
     const int half = (n_pos - 1) >> 1;
     const int ntiles = (rows + kFbTile - 1) / kFbTile;
+    const int n_own = (2 * RB - wave + 3) / 4;  // output tiles wave, wave + 4, ... of the 2 RB (row block, column block) pairs
+
+    f32x16 acc[kFbMaxOwn];
+#pragma unroll
+    for (int o = 0; o < kFbMaxOwn; ++o)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[o][r] = 0.f;
 
     uint4 rz[4];
-    int rmeta = 0;
+    int rj = 0, rb = 0;
+    bool rv = false;
     auto fetch = [&](int tile) {
         const int res0 = tile * kFbTile;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int c = tid + 256 * q, rr = c >> 3, part = c & 7;
             const int res = min(res0 + rr, rows - 1), col = col0 + 8 * part;
-            rz[q] = col < n_out ? *reinterpret_cast<const uint4 *>(d_z + (size_t)res * n_out + col) : (uint4){0u, 0u, 0u, 0u};
+            const bool ok = res0 + rr < rows && col < n_out && (mask ? mask[res] != 0 : true);
+            // (what a masked or missing residue holds never reaches the products: 0 x NaN would)
+            rz[q] = ok ? *reinterpret_cast<const uint4 *>(d_z + (size_t)res * n_out + col) : (uint4){0u, 0u, 0u, 0u};
         }
-        // threads 0..127: index, 128..255: bin of residue tid % 128 (slot s); the mask flag rides in the index's thread
-        const int rr = tid & (kFbTile - 1), res = min(res0 + rr, rows - 1);
-        rmeta = tid < kFbTile ? nbr_idx[(size_t)res * k + s] : nbr_bin[(size_t)res * k + s];
-        if (tid < kFbTile && (res0 + rr >= rows || (mask && mask[res] == 0))) rmeta = INT_MIN;  // nothing to add
+        if (tid < kFbTile) {  // this thread's residue of the tile: its slot-s neighbour and bin
+            const int res = min(res0 + tid, rows - 1);
+            rj = nbr_idx[(size_t)res * k + s];
+            rb = nbr_bin[(size_t)res * k + s];
+            rv = res0 + tid < rows && (mask ? mask[res] != 0 : true);
+        }
     };
+    int marked[2][3] = {{-1, -1, -1}, {-1, -1, -1}};  // rows this thread marked in either one-hot tile
     fetch(0);
+    __syncthreads();  // (the one-hot tiles are clear)
     for (int tile = 0; tile < ntiles; ++tile) {
-        char *st = fb_smem + (tile & 1) * kFbStageBytes;
+        const int b = tile & 1;
+        char *zs = zt + b * 64 * kFbStride, *xs = xt + b * Rpad * kFbStride;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4 *>(st + (tid + 256 * q) * 16) = rz[q];
-        reinterpret_cast<int *>(st + kFbTile * 128)[tid] = rmeta;  // [0, 128): index or INT_MIN; [128, 256): bin
-        __syncthreads();  // (also orders the clearing of the tables before the first adds)
+        for (int q = 0; q < 4; ++q) {
+            const int c = tid + 256 * q, rr = c >> 3, part = c & 7;
+            const unsigned w[4] = {rz[q].x, rz[q].y, rz[q].z, rz[q].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *reinterpret_cast<bf16_t *>(zs + (8 * part + e) * kFbStride + rr * 2) = (bf16_t)(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xffffu);
+        }
+        if (tid < kFbTile) {
+            int now[3] = {-1, -1, -1};
+            if (rv) {
+                if (s == 0) now[2] = R - 1;
+                if (rj >= 0 && rj < L) {
+                    now[0] = min(max(rb, 0), n_bins - 1);
+                    if constexpr (HAS_POS) {
+                        const int i = (tile * kFbTile + tid) % L;
+                        now[1] = n_bins + (pos_mode == 0 ? min(rj, n_pos - 1) : min(max(rj - i, -half), half) + half);
+                    }
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < 3; ++x) {
+                const int was = b == 0 ? marked[0][x] : marked[1][x];
+                if (was >= 0 && was != now[x]) *reinterpret_cast<bf16_t *>(xs + was * kFbStride + tid * 2) = 0;
+                if (now[x] >= 0) *reinterpret_cast<bf16_t *>(xs + now[x] * kFbStride + tid * 2) = 0x3F80;  // bf16 1.0
+                if (b == 0) marked[0][x] = now[x]; else marked[1][x] = now[x];
+            }
+        }
+        __syncthreads();
         if (tile + 1 < ntiles) fetch(tile + 1);
-        if (wave < W) {
-            const int *meta = reinterpret_cast<const int *>(st + kFbTile * 128);
-            // the next residue's index, bin and value are read while this one's rows are updated; the (up to)
-            // three rows of one residue are different rows, so their reads go out together
-            int j = meta[wave], bn = meta[kFbTile + wave];
-            float dz = bf2f(*reinterpret_cast<const bf16_t *>(st + wave * 128 + lane * 2));
-            for (int rr = wave; rr < kFbTile; rr += W) {
-                const int jc = j, bc = bn;
-                const float dc = dz;
-                const int nx = min(rr + W, kFbTile - 1);
-                j = meta[nx];
-                bn = meta[kFbTile + nx];
-                dz = bf2f(*reinterpret_cast<const bf16_t *>(st + nx * 128 + lane * 2));
-                if (jc == INT_MIN) continue;  // (uniform over the wave: all lanes look at the same residue)
-                const bool filled = jc >= 0 && jc < L;
-                float *p_bias = t + (R - 1) * 64;
-                float *p_bin = t + min(max(bc, 0), n_bins - 1) * 64;
-                float *p_pos = p_bin;
-                if constexpr (HAS_POS) {
-                    const int i = (tile * kFbTile + rr) % L;
-                    const int code = pos_mode == 0 ? min(jc, n_pos - 1) : min(max(jc - i, -half), half) + half;
-                    p_pos = t + (n_bins + (filled ? code : 0)) * 64;
-                }
-                const float v_bias = *p_bias, v_bin = *p_bin, v_pos = *p_pos;
-                if (s == 0) *p_bias = v_bias + dc;
-                if (filled) {
-                    *p_bin = v_bin + dc;
-                    if constexpr (HAS_POS) *p_pos = v_pos + dc;
-                }
+#pragma unroll
+        for (int o = 0; o < kFbMaxOwn; ++o) {
+            if (o >= n_own) break;
+            const int t = wave + 4 * o, mb = t >> 1, nb = t & 1;
+            const char *xa = xs + (32 * mb + li) * kFbStride + 16 * g;
+            const char *zb = zs + (32 * nb + li) * kFbStride + 16 * g;
+#pragma unroll
+            for (int ks = 0; ks < kFbTile / 16; ++ks) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(xa + 32 * ks);   // X^T[row 32 mb + li][residues 16 ks + 8 g ..]
+                const bf16x8 bz = *reinterpret_cast<const bf16x8 *>(zb + 32 * ks);  // dZ[residues 16 ks + 8 g ..][column 32 nb + li]
+                acc[o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bz, acc[o], 0, 0, 0);
             }
         }
     }
-    __syncthreads();
-    const int col = col0 + lane;
-    if (col >= n_out) return;
-    for (int row = wave; row < R; row += 4) {
-        float v = 0.f;
-        for (int w = 0; w < W; ++w) v += tab[((size_t)w * R + row) * 64 + lane];
-        if (row < n_bins)
-            d_e_bin[((size_t)s * n_bins + row) * n_out + col] = v;
-        else if (row < n_bins + n_pos)
-            d_e_pos[((size_t)s * n_pos + (row - n_bins)) * n_out + col] = v;
-        else if (s == 0 && d_bias)
-            d_bias[col] = v;
+    // accumulator register r of a lane: row 8 (r / 4) + 4 g + r % 4 of the row block, column li of the column block
+#pragma unroll
+    for (int o = 0; o < kFbMaxOwn; ++o) {
+        if (o >= n_own) break;
+        const int t = wave + 4 * o, mb = t >> 1, nb = t & 1;
+        const int col = col0 + 32 * nb + li;
+        if (col >= n_out) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * mb + 8 * (r >> 2) + 4 * g + (r & 3);
+            if (row < n_bins)
+                d_e_bin[((size_t)s * n_bins + row) * n_out + col] = acc[o][r];
+            else if (row < n_bins + n_pos)
+                d_e_pos[((size_t)s * n_pos + (row - n_bins)) * n_out + col] = acc[o][r];
+            else if (row == R - 1 && s == 0 && d_bias)
+                d_bias[col] = acc[o][r];
+        }
     }
 }
 
@@ -218,16 +247,14 @@ extern "C" int fipa_factor_project_backward(int32_t B, int32_t L, int32_t k, int
     if (pos_mode != 0 && pos_mode != 1) return FIPA_ERR_INVALID_ARG;
     if (n_pos > 0 && pos_mode == 1 && n_pos % 2 == 0) return FIPA_ERR_INVALID_ARG;
     if (n_out % 8 != 0 || k > 64 || (long long)B * L * k >= (1LL << 31)) return FIPA_ERR_UNSUPPORTED;
-    // a wave's copy of a slot's table slice: (n_bins + n_pos + 1) rows of 64 floats; as many copies (waves
-    // at work) as fit 120 KB of LDS beside the two stages of incoming residues, four at most
-    const long long copy_bytes = ((long long)n_bins + n_pos + 1) * 64 * 4;
-    const int W = (int)std::min<long long>(4, (120 * 1024) / copy_bytes);
-    if (W < 1) return FIPA_ERR_UNSUPPORTED;
+    // the one-hot tile holds 32-row blocks of the slot's rows (bins, position codes, one for the bias)
+    const int RB = (n_bins + n_pos + 1 + 31) / 32;
+    if (RB > fipa::kFbMaxRowBlocks) return FIPA_ERR_UNSUPPORTED;
     const void *al16[] = {d_z, d_e_bin, d_e_pos, d_bias};
     for (const void *ptr : al16)
         if (ptr && !fipa::aligned16(ptr)) return FIPA_ERR_ALIGNMENT;
     if ((reinterpret_cast<uintptr_t>(nbr_idx) & 3u) != 0 || (reinterpret_cast<uintptr_t>(nbr_bin) & 3u) != 0) return FIPA_ERR_ALIGNMENT;
-    const int lds = (int)(W * copy_bytes) + 2 * fipa::kFbStageBytes;
+    const int lds = 2 * (64 + 32 * RB) * fipa::kFbStride;
     const dim3 grid((unsigned)k, (unsigned)((n_out + 63) / 64));
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int rows = B * L;
@@ -237,13 +264,13 @@ extern "C" int fipa_factor_project_backward(int32_t B, int32_t L, int32_t k, int
         e = fipa::raise_lds_limit(lim, (const void *)fipa::fipa_factor_backward_kernel<true>, lds);
         if (e != hipSuccess) return FIPA_ERR_LAUNCH;
         hipLaunchKernelGGL(fipa::fipa_factor_backward_kernel<true>, grid, dim3(256), lds, stream, nbr_idx, nbr_bin,
-                           (const fipa::bf16_t *)d_z, mask, d_e_bin, d_e_pos, d_bias, rows, L, k, n_bins, n_pos, pos_mode, n_out, W);
+                           (const fipa::bf16_t *)d_z, mask, d_e_bin, d_e_pos, d_bias, rows, L, k, n_bins, n_pos, pos_mode, n_out, RB);
     } else {
         static fipa::LdsLimit lim;
         e = fipa::raise_lds_limit(lim, (const void *)fipa::fipa_factor_backward_kernel<false>, lds);
         if (e != hipSuccess) return FIPA_ERR_LAUNCH;
         hipLaunchKernelGGL(fipa::fipa_factor_backward_kernel<false>, grid, dim3(256), lds, stream, nbr_idx, nbr_bin,
-                           (const fipa::bf16_t *)d_z, mask, d_e_bin, (float *)nullptr, d_bias, rows, L, k, n_bins, 0, pos_mode, n_out, W);
+                           (const fipa::bf16_t *)d_z, mask, d_e_bin, (float *)nullptr, d_bias, rows, L, k, n_bins, 0, pos_mode, n_out, RB);
     }
     return hipGetLastError() == hipSuccess ? FIPA_OK : FIPA_ERR_LAUNCH;
 }

@@ -137,12 +137,12 @@ def test_workload3_size_timed():
 @pytest.mark.parametrize("kw", [dict(B=2, L=77, k=20, n_bins=16, n_pos=65, n_out=256, pos_mode=1),
                                 dict(B=1, L=300, k=20, n_bins=16, n_pos=33, n_out=512, pos_mode=0),
                                 dict(B=3, L=50, k=7, n_bins=5, n_pos=0, n_out=8, pos_mode=1),
-                                dict(B=1, L=130, k=64, n_bins=64, n_pos=129, n_out=136, pos_mode=1),
+                                dict(B=1, L=130, k=64, n_bins=30, n_pos=129, n_out=136, pos_mode=1),
                                 dict(B=2, L=40, k=1, n_bins=1, n_pos=1, n_out=32, pos_mode=1),
-                                dict(B=1, L=90, k=3, n_bins=220, n_pos=255, n_out=64, pos_mode=1)])
+                                dict(B=1, L=90, k=3, n_bins=64, n_pos=95, n_out=64, pos_mode=1)])
 def test_table_gradients(kw):
-    # (the last two shapes: a single table row that every residue hits; tables so tall that only one
-    # wave's copy fits LDS)
+    # (the last two shapes: a single table row that every residue hits; the tallest tables the call takes,
+    # five blocks of 32 rows)
     import torch
     rng = np.random.default_rng(200 + kw["L"])
     B, L, k, n_bins, n_pos, n_out = kw["B"], kw["L"], kw["k"], kw["n_bins"], kw["n_pos"], kw["n_out"]
