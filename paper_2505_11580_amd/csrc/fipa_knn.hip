@@ -6,8 +6,9 @@
 // One wave per query residue.  The wave keeps its 64 best candidates so far as a sorted list, one
 // entry per lane (lane s holds the s-th nearest), scans the chain 64 residues at a time, and
 // inserts the few candidates that beat the current k-th entry one by one (a shift by one lane
-// from the insertion point on).  Order is by (squared distance, index), a strict total order, so
-// the result does not depend on the order of the scan.  Every decision is taken in float32 on
+// from the insertion point on); the scan starts at the residue's own block and moves outwards.
+// Order is by (squared distance, index), a strict total order, so the result does not depend on
+// the order of the scan.  Every decision is taken in float32 on
 // ((dx*dx + dy*dy) + dz*dz) with one rounding per operation (no fused multiply-add).
 #include "fipa_internal.h"
 
@@ -42,7 +43,16 @@ __global__ __launch_bounds__(256) void fipa_knn_distogram_kernel(const float *__
         const float xi = t[3 * i], yi = t[3 * i + 1], zi = t[3 * i + 2];
         float thr_d = INFINITY;  // entry k - 1 of the list
         int thr_j = INT_MAX;
-        for (int j0 = 0; j0 < L; j0 += 64) {
+        // The blocks of 64 candidates are visited outwards from the residue's own: in a chain the
+        // neighbours along the sequence are near in space, so the list fills with near residues at
+        // once and few later candidates beat its k-th entry (in index order every residue before i
+        // arrives nearer than the one before it and is inserted, one at a time).
+        const int nblk = (L + 63) / 64, own = i / 64;
+        for (int step = 0, up = own, down = own - 1; step < nblk; ++step) {
+            // alternate above / below while both sides have blocks left
+            const bool take_up = up < nblk && (down < 0 || ((step & 1) == 0));
+            const int j0 = 64 * (take_up ? up : down);
+            if (take_up) ++up; else --down;
             const int j = j0 + lane;
             const bool ok = j < L && j != i && (!m || m[j] != 0);
             float d2 = INFINITY;
