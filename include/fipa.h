@@ -14,7 +14,8 @@
  *   - The library allocates nothing, frees nothing and never synchronises: all work is
  *     enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - `workspace` is caller-owned device scratch of at least fipa_workspace_bytes(); its
- *     contents are undefined afterwards.  Forward and backward do not share state through it.
+ *     contents are undefined afterwards.  Forward and backward do not share state through it
+ *     (unless FIPA_FLAG_KEEP_FORWARD asks for exactly that).
  *   - Outputs are fully overwritten.  Query rows whose mask byte is 0 receive zeros (and
  *     contribute nothing to any gradient); keys whose mask byte is 0 receive exactly zero
  *     weight, whatever finite values their slots hold.
@@ -75,10 +76,11 @@ typedef struct fipa_desc {
  * Training steps (a forward call followed by the backward call on the same inputs), bf16, the shapes
  * the backward accepts: fipa_forward / fipa_forward_packed with this flag take a workspace of the
  * BACKWARD's size and leave in it what the gradient needs from the forward -- the lifted operands of
- * Algorithm 1 steps 1-6, the un-normalised lifted output O^ and the log-sum-exp -- and
+ * Algorithm 1 steps 2-6, the lifted output O^ and the log-sum-exp -- and
  * fipa_backward / fipa_backward_packed with this flag, the same descriptor, the same input tensors
  * and that workspace skip the recomputation (about a sixth of the backward's time at the headline
- * shape; the forward call is slower by the separate epilogue pass, so the pair gains about a tenth).
+ * shape; the forward call is slower -- a separate epilogue pass, per-head query factors and O^ in memory,
+ * no key-range split -- so the pair gains about a tenth, less at short lengths).
  * Outputs and gradients are the same as without the flag.  The caller keeps the workspace untouched
  * between the two calls; a backward call with the flag on a workspace that the matching forward call
  * did not fill returns gradients of garbage without an error.  Not for fipa_forward_static
