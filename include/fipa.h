@@ -121,7 +121,7 @@ int fipa_workspace_bytes(const fipa_desc *desc, size_t *forward_bytes, size_t *b
  *   o_pts            [B, L, H, Pv, 3]  float32   T_i^{-1} o sum_j a_ij (T_j o v_j), local frame of i
  *   o_pair           [B, L, H, cz]     float32   sum_j a_ij z_ij
  *   lse              [B, H, L] float32, or NULL: natural log-sum-exp over valid keys of the
- *                    softmax argument of Eq. 3 (0 for masked query rows); fipa_backward needs it.
+ *                    softmax argument of Eq. 3 (0 for masked query rows).
  */
 int fipa_forward(const fipa_desc *desc,
                  const void *q, const void *k, const void *v,
@@ -283,7 +283,8 @@ int fipa_factor_project_backward(int32_t B, int32_t L, int32_t k, int32_t n_bins
  * taken as a free variable of R_i x + t_i in Eq. 3 and of R_i^T (. - t_i) in Eq. 4), given
  * the upstream gradients d_o, d_o_pts, d_o_pair (float32, shapes of o, o_pts, o_pair).
  * The forward results o, o_pts, o_pair, lse are accepted for callers that keep them but are not
- * read (the attention weights and outputs are recomputed from the inputs); each may be NULL.
+ * read (the attention weights and outputs are recomputed from the inputs, or with
+ * FIPA_FLAG_KEEP_FORWARD taken from the workspace the forward call filled); each may be NULL.
  * d_gamma, d_w_b, d_rot and d_trans are overwritten (not accumulated).  The paper gives no backward; it is the chain
  * rule through Eqs. 3-4 and z_ij = z1_i^T z2_j.
  * Supported for FIPA_DTYPE_BF16 with r*cz <= 512 (512, the rank-4 shape at cz = 128, on plain gradient
