@@ -160,6 +160,13 @@ def test_bf16_workload3_sampled_rows():
             assert np.all(got[n][b, int(ln):] == 0), (n, b)
 
 
+def test_bf16_one_chain_of_32768_residues_sampled_rows():
+    # far beyond the named workloads (Section 3.1 scales the method in length): 1024 key blocks per tile,
+    # 256 query tiles per head, one sampled row in each of them
+    inp = wl.make_inputs(1, B=1, L=32768, H=4)
+    gu.check(inp, rows=wl.select_rows(inp, 258), label="L=32768 bf16 sampled rows", chunk=16)
+
+
 def test_bf16_workload4_forward_sampled_rows():
     inp = wl.make_inputs(4, with_grads=False)
     gu.check(inp, rows=wl.select_rows(inp, 256), label="cfg4 fwd bf16 sampled rows", chunk=128)
