@@ -153,13 +153,15 @@ __device__ __forceinline__ void wide_step(const char *__restrict__ st, const cha
 #pragma unroll
             for (int x = 0; x < 4; ++x) sacc[4 * a + x] = bias[x];
         }
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
+        // (unrolled by recursion: at width 1088 the 68 steps are more than an unroll pragma will take, and
+        // a loop that stays a loop indexes the fragments at run time, which moves them to scratch memory)
+        static_for<C::KS>([&](auto I) {
+            constexpr int ks = decltype(I)::value;
             const char *src = ks < C::KSH ? st + C::KH_OFF + ln.kaddr_h + ks * 32 : st + C::Z_OFF + ln.kaddr_z + (ks - C::KSH) * 32;
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(src);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
             if (load_next && ks % kDmaEvery == 0) wide_issue_entry<C>(dma, next_stage, ks / kDmaEvery);
-        }
+        });
     }
     if constexpr (PREV) {
         static_for<2 * C::NBW>([&](auto I) {
