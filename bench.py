@@ -299,6 +299,7 @@ def main():
                          "waves per SIMD); the JSON line says so in config.attention_kernel")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (same generators)")
     ap.add_argument("--seq-len", type=int, default=0, help="override the workload's sequence length (same generators)")
+    ap.add_argument("--rank", type=int, default=0, help="override the workload's factor rank r (same generators)")
     ap.add_argument("--packed-leg", action="store_true",
                     help="also time a packed batch of 32 short chains (one launch / chain after chain / padded)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -320,6 +321,8 @@ def main():
         over["B"] = args.batch
     if args.seq_len > 0:
         over["L"] = args.seq_len
+    if args.rank > 0:
+        over["r"] = args.rank
     inp = workloads.make_inputs(args.workload, with_grads=False, **over)
     dims = inp["dims"]
     desc, dev = binding.upload(inp)
